@@ -1,0 +1,268 @@
+"""ctypes front end of the EF21 CPU oracle (``ef21_oracle.c``) -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import this module.
+It imports nothing from the HIP package and the HIP package imports nothing from here.
+
+The iteration of Algorithm 2 (EF21, multiple nodes) is composed here from the C routines, one
+call per line of the algorithm, in the order the paper states; all state lives in fp64 numpy
+arrays (``storage_f32=True`` rounds every stored value to fp32, see the C file's header).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ef21_oracle.c")
+_LIB = os.path.join(_HERE, "libef21_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, -O2, single-threaded). Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        i32, i64, dbl = C.c_int32, C.c_int64, C.c_double
+        p = C.c_void_p
+        lib.ef21o_topk.argtypes = [p, i64, i64, p, p]
+        lib.ef21o_topk.restype = C.c_int
+        lib.ef21o_logreg_loss_dense.argtypes = [p, p, i64, i64, p, dbl]
+        lib.ef21o_logreg_loss_dense.restype = dbl
+        lib.ef21o_logreg_grad_dense.argtypes = [p, p, i64, i64, p, dbl, p]
+        lib.ef21o_logreg_grad_dense.restype = None
+        lib.ef21o_logreg_loss_csr.argtypes = [p, p, p, p, i64, i64, p, dbl]
+        lib.ef21o_logreg_loss_csr.restype = dbl
+        lib.ef21o_logreg_grad_csr.argtypes = [p, p, p, p, i64, i64, p, dbl, p]
+        lib.ef21o_logreg_grad_csr.restype = None
+        lib.ef21o_round_storage.argtypes = [p, i64, C.c_int]
+        lib.ef21o_round_storage.restype = None
+        lib.ef21o_compress_update.argtypes = [i32, i64, i64, p, p, p, p, p, C.c_int]
+        lib.ef21o_compress_update.restype = C.c_int
+        lib.ef21o_model_step.argtypes = [i64, dbl, p, p, C.c_int]
+        lib.ef21o_model_step.restype = None
+        lib.ef21o_mean_rows.argtypes = [i32, i64, p, p, C.c_int]
+        lib.ef21o_mean_rows.restype = None
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+# ----------------------------------------------------------------------------- Top-k (Section 2.1)
+def topk(v, k: int):
+    """Top-k of one vector: (ascending int32 indices [k], float64 values [k])."""
+    v = _f64(v)
+    assert v.ndim == 1
+    idx = np.empty(k, dtype=np.int32)
+    val = np.empty(k, dtype=np.float64)
+    rc = _load().ef21o_topk(_ptr(v), v.size, k, _ptr(idx), _ptr(val))
+    if rc != 0:
+        raise ValueError("ef21o_topk: bad arguments")
+    return idx, val
+
+
+def topk_rows(V, k: int):
+    """Row-wise Top-k of an [n][d] array: (idx [n][k] int32, val [n][k] float64)."""
+    V = _f64(V)
+    out = [topk(row, k) for row in V]
+    return np.stack([o[0] for o in out]), np.stack([o[1] for o in out])
+
+
+def topk_dense(v, k: int) -> np.ndarray:
+    """C(v) as a dense vector: the k kept entries, zeros elsewhere."""
+    idx, val = topk(v, k)
+    out = np.zeros(len(v), dtype=np.float64)
+    out[idx] = val
+    return out
+
+
+# --------------------------------------------------------------- objective of Section 5, eq. (9)
+class LogRegDense:
+    """n workers, each with m dense fp32 rows: A [n][m][d], y [n][m] (+-1), regulariser weight lam."""
+
+    def __init__(self, A, y, lam: float):
+        self.A = np.ascontiguousarray(A, dtype=np.float32)
+        self.y = np.ascontiguousarray(y, dtype=np.float32)
+        self.n, self.m, self.d = self.A.shape
+        assert self.y.shape == (self.n, self.m)
+        self.lam = float(lam)
+
+    def loss_i(self, i: int, x) -> float:
+        x = _f64(x)
+        return _load().ef21o_logreg_loss_dense(_ptr(self.A[i]), _ptr(self.y[i]), self.m, self.d, _ptr(x),
+                                               self.lam)
+
+    def grad_i(self, i: int, x) -> np.ndarray:
+        x = _f64(x)
+        g = np.empty(self.d, dtype=np.float64)
+        _load().ef21o_logreg_grad_dense(_ptr(self.A[i]), _ptr(self.y[i]), self.m, self.d, _ptr(x), self.lam,
+                                        _ptr(g))
+        return g
+
+    def loss(self, x) -> float:
+        """f(x) = (1/n) sum_i f_i(x), eq. (1)."""
+        return sum(self.loss_i(i, x) for i in range(self.n)) / self.n
+
+    def grads(self, x) -> np.ndarray:
+        return np.stack([self.grad_i(i, x) for i in range(self.n)])
+
+
+class LogRegCSR:
+    """n workers, each with m sparse rows; one CSR over all n*m rows (rowptr int64 [n*m+1])."""
+
+    def __init__(self, rowptr, col, val, y, n: int, m: int, d: int, lam: float):
+        self.rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+        self.col = np.ascontiguousarray(col, dtype=np.int32)
+        self.val = np.ascontiguousarray(val, dtype=np.float32)
+        self.y = np.ascontiguousarray(y, dtype=np.float32).reshape(n, m)
+        self.n, self.m, self.d = n, m, d
+        assert self.rowptr.size == n * m + 1
+        self.lam = float(lam)
+
+    def _rp(self, i):
+        return self.rowptr[i * self.m:(i + 1) * self.m + 1]
+
+    def loss_i(self, i: int, x) -> float:
+        x = _f64(x)
+        rp = np.ascontiguousarray(self._rp(i))
+        return _load().ef21o_logreg_loss_csr(_ptr(rp), _ptr(self.col), _ptr(self.val), _ptr(self.y[i]), self.m,
+                                             self.d, _ptr(x), self.lam)
+
+    def grad_i(self, i: int, x) -> np.ndarray:
+        x = _f64(x)
+        rp = np.ascontiguousarray(self._rp(i))
+        g = np.empty(self.d, dtype=np.float64)
+        _load().ef21o_logreg_grad_csr(_ptr(rp), _ptr(self.col), _ptr(self.val), _ptr(self.y[i]), self.m, self.d,
+                                      _ptr(x), self.lam, _ptr(g))
+        return g
+
+    def loss(self, x) -> float:
+        return sum(self.loss_i(i, x) for i in range(self.n)) / self.n
+
+    def grads(self, x) -> np.ndarray:
+        return np.stack([self.grad_i(i, x) for i in range(self.n)])
+
+
+# ------------------------------------------------------------------ Algorithm 2 (EF21, multi-node)
+def round_storage(a, storage_f32: bool) -> np.ndarray:
+    a = _f64(a).copy()
+    _load().ef21o_round_storage(_ptr(a), a.size, int(storage_f32))
+    return a
+
+
+def mean_rows(g_i, storage_f32: bool) -> np.ndarray:
+    g_i = _f64(g_i)
+    n, d = g_i.shape
+    g = np.empty(d, dtype=np.float64)
+    _load().ef21o_mean_rows(n, d, _ptr(g_i), _ptr(g), int(storage_f32))
+    return g
+
+
+@dataclass
+class EF21State:
+    """State of Algorithm 2: iterate x [d], per-worker estimators g_i [n][d], their mean g [d]."""
+    x: np.ndarray
+    g_i: np.ndarray
+    g: np.ndarray
+    msg_idx: np.ndarray | None = None   # last messages c_i as (index, value) pairs, [n][k]
+    msg_val: np.ndarray | None = None
+
+    def copy(self) -> "EF21State":
+        return EF21State(self.x.copy(), self.g_i.copy(), self.g.copy(),
+                         None if self.msg_idx is None else self.msg_idx.copy(),
+                         None if self.msg_val is None else self.msg_val.copy())
+
+
+def init_state(x0, grads0, k: int, init: str = "grad", storage_f32: bool = True) -> EF21State:
+    """Input line of Algorithm 2.  init="compressed": g_i^0 = C(grad f_i(x^0)) (the algorithm's
+    default); init="grad": g_i^0 = grad f_i(x^0) (allowed by the remark after Theorem 2, makes
+    G^0 = 0); init="zero": g_i^0 = 0 (any vector is admissible).  g^0 = mean_i g_i^0."""
+    x = round_storage(x0, storage_f32)
+    grads0 = round_storage(grads0, storage_f32)
+    if init == "grad":
+        g_i = grads0
+    elif init == "compressed":
+        g_i = np.stack([topk_dense(row, k) for row in grads0])
+    elif init == "zero":
+        g_i = np.zeros_like(grads0)
+    else:
+        raise ValueError(init)
+    return EF21State(x, g_i, mean_rows(g_i, storage_f32))
+
+
+def compress_update(state: EF21State, grads, k: int, storage_f32: bool = True) -> None:
+    """Lines 5, 6 and 8 of Algorithm 2 for all workers, in place."""
+    grads = round_storage(grads, storage_f32)
+    n, d = state.g_i.shape
+    assert grads.shape == (n, d)
+    idx = np.empty((n, k), dtype=np.int32)
+    val = np.empty((n, k), dtype=np.float64)
+    rc = _load().ef21o_compress_update(n, d, k, _ptr(grads), _ptr(state.g_i), _ptr(state.g), _ptr(idx),
+                                       _ptr(val), int(storage_f32))
+    if rc != 0:
+        raise ValueError("ef21o_compress_update: bad arguments")
+    state.msg_idx, state.msg_val = idx, val
+
+
+def model_step(state: EF21State, gamma: float, storage_f32: bool = True) -> None:
+    """Line 3 of Algorithm 2, in place."""
+    _load().ef21o_model_step(state.x.size, float(gamma), _ptr(state.x), _ptr(state.g), int(storage_f32))
+
+
+def iteration(state: EF21State, grads_at, k: int, gamma: float, order: str = "grad_first",
+              storage_f32: bool = True) -> None:
+    """One pass of the loop body of Algorithm 2.
+
+    grads_at: callable x -> [n][d] gradients, or an [n][d] array of supplied gradients
+    (the stochastic variant, Algorithm 5, replaces grad f_i by any estimator).
+    order="step_first" is the loop body as printed: line 3, then lines 5, 6, 8 at the new x.
+    order="grad_first" is the same loop rotated by one phase: lines 5, 6, 8 at the current x,
+    then line 3.  With g_i^0 = grad f_i(x^0) both produce the same iterates x^0, x^1, ...
+    """
+    def grads_now():
+        return grads_at(state.x) if callable(grads_at) else grads_at
+
+    if order == "step_first":
+        model_step(state, gamma, storage_f32)
+        compress_update(state, grads_now(), k, storage_f32)
+    elif order == "grad_first":
+        compress_update(state, grads_now(), k, storage_f32)
+        model_step(state, gamma, storage_f32)
+    else:
+        raise ValueError(order)
+
+
+# ------------------------------------------------------------------------ theory (Section 3.4)
+def theta_beta(alpha: float):
+    """theta = 1 - sqrt(1 - alpha), beta = (1 - alpha) / (1 - sqrt(1 - alpha))  (before Theorem 1)."""
+    r = np.sqrt(1.0 - alpha)
+    return 1.0 - r, (1.0 - alpha) / (1.0 - r)
+
+
+def distortion(state: EF21State, grads) -> float:
+    """G^t = (1/n) sum_i ||g_i - grad f_i(x)||^2, eq. (8)."""
+    diff = state.g_i - _f64(grads)
+    return float(np.mean(np.sum(diff * diff, axis=1)))
