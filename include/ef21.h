@@ -1,0 +1,138 @@
+/*
+ * libef21 -- the data-parallel hot path of EF21 (Richtarik, Sokolov, Fatkhullin,
+ * arXiv 2106.05203) on one AMD MI355X (gfx950).  C ABI; no C++ or framework types cross it.
+ *
+ * The library solves the paper's problem  min_x f(x) = (1/n) sum_i f_i(x)  (eq. (1)) with
+ * Algorithm 2 ("EF21, multiple nodes"), all n workers batched as rows on one GPU:
+ *
+ *     line 3   x   <- x - gamma * g
+ *     line 5   c_i  = C(grad f_i(x) - g_i)          C = Top-k (Section 2.1)
+ *     line 6   g_i <- g_i + c_i
+ *     line 8   g   <- g + (1/n) sum_i c_i
+ *
+ * Conventions that hold for every call
+ *   - Every array argument is a DEVICE pointer to memory the caller owns (for example the
+ *     storage of a PyTorch tensor), row-major and contiguous.  Values are fp32, indices are
+ *     int32, sizes are int64.  The library copies what it needs to keep (state); it only
+ *     borrows problem data (see ef21_set_problem_*).
+ *   - Work is enqueued on a HIP stream and the call returns without waiting for it.  The
+ *     caller synchronises the stream before reading results on the host.
+ *   - Every function except ef21_create and ef21_last_error returns an EF21_* status.  On
+ *     failure nothing has been enqueued unless stated, and ef21_last_error() describes it.
+ *   - NaN inputs are outside the contract: a NaN ranks above +inf in Top-k (its bit pattern
+ *     is larger); nothing traps.
+ *   - A handle is not thread safe; different handles may be used from different threads.
+ */
+#ifndef EF21_H
+#define EF21_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ef21_ctx *ef21_handle;
+
+enum {
+    EF21_OK = 0,
+    EF21_EINVAL = -1, /* bad argument (size, NULL pointer, gamma)                       */
+    EF21_ENOMEM = -2, /* device or host allocation failed                                */
+    EF21_EHIP = -3,   /* a HIP runtime call failed; text in ef21_last_error()            */
+    EF21_ESTATE = -4  /* call not possible in the handle's state (e.g. no problem set)   */
+};
+
+/* flags of ef21_step */
+enum {
+    EF21_ORDER_GRAD_FIRST = 0u, /* lines 5, 6, 8 at the current x, then line 3 (default)      */
+    EF21_ORDER_STEP_FIRST = 1u  /* line 3, then lines 5, 6, 8 at the new x (loop as printed)  */
+};
+
+/* Human-readable text of the calling thread's last failure ("" if none).  Library-owned. */
+const char *ef21_last_error(void);
+
+/*
+ * Input line of Algorithm 2: n workers, dimension d, Top-k parameter k (1 <= k <= d), learning
+ * rate gamma > 0 (finite).  Allocates, on the current HIP device, the state x [d], g [d],
+ * g_i [n][d] (all zero) and the last messages (idx, val) [n][k].  Returns NULL on failure.
+ * d must be below 2^31 (indices are int32).
+ */
+ef21_handle ef21_create(int32_t n, int64_t d, int64_t k, float gamma);
+
+/* Waits for the handle's stream, then frees everything the handle owns.  NULL is allowed. */
+int ef21_destroy(ef21_handle h);
+
+/* Stream (a hipStream_t passed as void*) that later calls on this handle enqueue on.  The
+ * stream is borrowed.  Default: the null stream. */
+int ef21_set_stream(ef21_handle h, void *hip_stream);
+
+/*
+ * Top-k compressor of Section 2.1, batched over rows, stateless:  for each of the n rows of
+ * `rows` [n][d] keep the k entries of largest absolute value.  Magnitudes are compared as
+ * the fp32 bit pattern with the sign bit cleared, so +a ties with -a and +0 with -0; among
+ * equal magnitudes the LOWER index is kept (the paper does not specify ties).
+ *   out_idx [n][k]  kept positions of each row in ASCENDING order
+ *   out_val [n][k]  the (signed) input values at those positions
+ * Exactly k pairs are produced per row even if fewer than k entries are non-zero.
+ * Enqueued on `hip_stream` (NULL = null stream).  For rows longer than a few 10^4 entries the
+ * call uses a device workspace that the library keeps per device and grows on demand with
+ * hipMalloc (a growing call synchronises the device); concurrent ef21_topk calls on one device
+ * share that workspace and must not overlap.
+ * EF21_EINVAL: n < 1, d < 1, d >= 2^31, k < 1, k > d, NULL pointer.
+ */
+int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_idx, float *out_val,
+              void *hip_stream);
+
+/*
+ * Attach the objective of Section 5, eq. (9): logistic loss with the non-convex regulariser,
+ *   f_i(x) = (1/m) sum_l log(1 + exp(-y_il a_il^T x)) + lambda sum_j x_j^2 / (1 + x_j^2),
+ * each worker holding m rows (each f_i carries the full regulariser, so (1/n) sum_i f_i is
+ * eq. (9) for an even split of the data).
+ *   dense:  A [n][m][d] fp32, y [n][m] fp32 in {-1, +1}
+ *   csr:    one CSR over all n*m rows, worker i owning rows i*m .. (i+1)*m-1:
+ *           rowptr [n*m+1] int64, col [nnz] int32 in [0, d), val [nnz] fp32, y [n][m]
+ * The arrays are BORROWED: they must stay valid and unchanged while the handle uses them.
+ * Allocates a gradient buffer [n][d] and scratch on first use.
+ */
+int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_t m, float lambda);
+int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *col, const float *val,
+                         const float *y, int64_t m, float lambda);
+
+/*
+ * State of Algorithm 2.  set: copies x [d] and g_i [n][d] into the handle (either may be NULL
+ * = keep); g [d] NULL means "recompute g = (1/n) sum_i g_i" (the algorithm's input line).
+ * get: copies the handle's state out; any pointer may be NULL.
+ */
+int ef21_set_state(ef21_handle h, const float *x, const float *g_i, const float *g);
+int ef21_get_state(ef21_handle h, float *x, float *g_i, float *g);
+
+/* The messages c_i of the last ef21_step as (idx, val) [n][k], layout as in ef21_topk. */
+int ef21_get_messages(ef21_handle h, int32_t *idx, float *val);
+
+/*
+ * grad f_i(x) for all workers (derivative of eq. (9)):
+ *   (1/m) sum_l  -y_il / (1 + exp(y_il a_il^T x)) a_il  +  2 lambda x_j / (1 + x_j^2)^2
+ * at `x` [d] (NULL = the handle's x), written to out_grad [n][d].  EF21_ESTATE without a
+ * problem.  fp32 arithmetic; partial sums over rows are combined in a fixed order for the
+ * dense layout (bitwise reproducible) and with floating-point atomics for CSR (reproducible
+ * to rounding).
+ */
+int ef21_local_grad(ef21_handle h, const float *x, float *out_grad);
+
+/*
+ * One pass of the loop body of Algorithm 2 for all workers.
+ *   grads [n][d]: the vectors used in place of grad f_i(x) in line 5 (supplied gradients,
+ *   e.g. the stochastic estimators of Algorithm 5), or NULL to compute grad f_i at the
+ *   handle's x from the attached problem (EF21_ESTATE if none).
+ *   flags: EF21_ORDER_GRAD_FIRST or EF21_ORDER_STEP_FIRST.  With supplied gradients and
+ *   STEP_FIRST the caller must have evaluated them at x - gamma*g.
+ * The difference in line 5 is one fp32 subtraction; line 6 is one fp32 addition per kept
+ * entry; line 8 adds val/n per message with floating-point atomics (g is reproducible to
+ * rounding, g_i and the messages bitwise); line 3 is one fused multiply-add per coordinate.
+ */
+int ef21_step(ef21_handle h, const float *grads, uint32_t flags);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EF21_H */

@@ -1,0 +1,319 @@
+// C ABI of libef21 (declared in include/ef21.h): argument checks, the handle, launches.
+#include <cmath>
+#include <cstdio>
+#include <mutex>
+#include <new>
+#include <string>
+
+#include "../../include/ef21.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string &msg) {
+    g_last_error = msg;
+    return code;
+}
+
+int fail_hip(hipError_t st, const char *what) {
+    return fail(EF21_EHIP, std::string(what) + ": " + hipGetErrorString(st));
+}
+
+#define EF21_HIP(call)                                           \
+    do {                                                         \
+        hipError_t st__ = (call);                                \
+        if (st__ != hipSuccess) return fail_hip(st__, #call);    \
+    } while (0)
+
+enum ProblemKind { kNone = 0, kDense = 1, kCSR = 2 };
+
+// Rows at least this long are selected with many workgroups per row.
+constexpr int64_t kSplitMinRow = 1 << 16;
+
+bool use_split(int64_t d) { return d >= kSplitMinRow; }
+
+// Per-device workspace of the stateless ef21_topk.
+struct SharedWorkspace {
+    std::mutex mu;
+    void *ptr[64] = {};
+    size_t bytes[64] = {};
+};
+SharedWorkspace g_topk_ws;
+
+}  // namespace
+
+struct ef21_ctx {
+    int32_t n = 0;
+    int64_t d = 0, k = 0;
+    float gamma = 0.f;
+    int device = 0;
+    hipStream_t stream = nullptr;
+    // state of Algorithm 2
+    float *x = nullptr, *g = nullptr, *g_i = nullptr;
+    int32_t *msg_idx = nullptr;
+    float *msg_val = nullptr;
+    // problem (borrowed)
+    ProblemKind kind = kNone;
+    const float *A = nullptr, *y = nullptr, *val = nullptr;
+    const int64_t *rowptr = nullptr;
+    const int32_t *col = nullptr;
+    int64_t m = 0;
+    float lambda = 0.f;
+    // owned buffers for the problem path and the long-row Top-k
+    float *grad = nullptr;
+    void *scratch = nullptr;
+    size_t scratch_bytes = 0;
+    void *topk_ws = nullptr;
+};
+
+namespace {
+
+int check_handle(ef21_handle h) {
+    if (!h) return fail(EF21_EINVAL, "handle is NULL");
+    int dev = -1;
+    EF21_HIP(hipGetDevice(&dev));
+    if (dev != h->device) return fail(EF21_ESTATE, "the handle was created on another HIP device than the current one");
+    return EF21_OK;
+}
+
+int check_topk_sizes(int32_t n, int64_t d, int64_t k) {
+    if (n < 1 || n > 65535) return fail(EF21_EINVAL, "n must be in [1, 65535]");
+    if (d < 1 || d >= ((int64_t)1 << 31)) return fail(EF21_EINVAL, "d must be in [1, 2^31)");
+    if (k < 1 || k > d) return fail(EF21_EINVAL, "k must be in [1, d]");
+    return EF21_OK;
+}
+
+void free_ctx(ef21_ctx *c) {
+    if (!c) return;
+    (void)hipFree(c->x);
+    (void)hipFree(c->g);
+    (void)hipFree(c->g_i);
+    (void)hipFree(c->msg_idx);
+    (void)hipFree(c->msg_val);
+    (void)hipFree(c->grad);
+    (void)hipFree(c->scratch);
+    (void)hipFree(c->topk_ws);
+    delete c;
+}
+
+int ensure_problem_buffers(ef21_ctx *c, size_t scratch_bytes) {
+    if (!c->grad) {
+        hipError_t st = hipMalloc((void **)&c->grad, sizeof(float) * (size_t)c->n * c->d);
+        if (st != hipSuccess) return fail(EF21_ENOMEM, "hipMalloc of the gradient buffer failed");
+    }
+    if (scratch_bytes > c->scratch_bytes) {
+        EF21_HIP(hipStreamSynchronize(c->stream));
+        (void)hipFree(c->scratch);
+        c->scratch = nullptr;
+        c->scratch_bytes = 0;
+        hipError_t st = hipMalloc(&c->scratch, scratch_bytes);
+        if (st != hipSuccess) return fail(EF21_ENOMEM, "hipMalloc of the gradient scratch failed");
+        c->scratch_bytes = scratch_bytes;
+    }
+    return EF21_OK;
+}
+
+int enqueue_local_grad(ef21_ctx *c, const float *x, float *out) {
+    hipError_t st;
+    if (c->kind == kDense)
+        st = ef21::launch_logreg_grad_dense(c->A, c->y, x, out, c->n, c->m, c->d, c->lambda, c->scratch, c->stream);
+    else
+        st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->lambda,
+                                          c->stream);
+    if (st != hipSuccess) return fail_hip(st, "gradient kernel launch");
+    return EF21_OK;
+}
+
+int enqueue_topk(const ef21::TopkArgs &p, void *workspace, hipStream_t stream) {
+    hipError_t st = (use_split(p.d) && workspace) ? ef21::launch_topk_split(p, workspace, stream)
+                                                  : ef21::launch_topk_row(p, stream);
+    if (st != hipSuccess) return fail_hip(st, "Top-k kernel launch");
+    return EF21_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ef21_last_error(void) { return g_last_error.c_str(); }
+
+ef21_handle ef21_create(int32_t n, int64_t d, int64_t k, float gamma) {
+    if (check_topk_sizes(n, d, k) != EF21_OK) return nullptr;
+    if (!(gamma > 0.f) || !std::isfinite(gamma)) {
+        fail(EF21_EINVAL, "gamma must be finite and > 0");
+        return nullptr;
+    }
+    ef21_ctx *c = new (std::nothrow) ef21_ctx;
+    if (!c) {
+        fail(EF21_ENOMEM, "host allocation failed");
+        return nullptr;
+    }
+    c->n = n;
+    c->d = d;
+    c->k = k;
+    c->gamma = gamma;
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        fail(EF21_EHIP, "hipGetDevice failed");
+        delete c;
+        return nullptr;
+    }
+    const size_t nd = (size_t)n * d, nk = (size_t)n * k;
+    bool ok = hipMalloc((void **)&c->x, sizeof(float) * d) == hipSuccess &&
+              hipMalloc((void **)&c->g, sizeof(float) * d) == hipSuccess &&
+              hipMalloc((void **)&c->g_i, sizeof(float) * nd) == hipSuccess &&
+              hipMalloc((void **)&c->msg_idx, sizeof(int32_t) * nk) == hipSuccess &&
+              hipMalloc((void **)&c->msg_val, sizeof(float) * nk) == hipSuccess;
+    if (ok && use_split(d)) ok = hipMalloc(&c->topk_ws, ef21::topk_split_workspace_bytes(n, d, k)) == hipSuccess;
+    if (ok)
+        ok = hipMemset(c->x, 0, sizeof(float) * d) == hipSuccess && hipMemset(c->g, 0, sizeof(float) * d) == hipSuccess &&
+             hipMemset(c->g_i, 0, sizeof(float) * nd) == hipSuccess &&
+             hipMemset(c->msg_idx, 0, sizeof(int32_t) * nk) == hipSuccess &&
+             hipMemset(c->msg_val, 0, sizeof(float) * nk) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        free_ctx(c);
+        fail(EF21_ENOMEM, "device allocation of the EF21 state failed");
+        return nullptr;
+    }
+    return c;
+}
+
+int ef21_destroy(ef21_handle h) {
+    if (!h) return EF21_OK;
+    hipError_t st = hipStreamSynchronize(h->stream);
+    free_ctx(h);
+    if (st != hipSuccess) return fail_hip(st, "hipStreamSynchronize");
+    return EF21_OK;
+}
+
+int ef21_set_stream(ef21_handle h, void *hip_stream) {
+    if (int rc = check_handle(h)) return rc;
+    h->stream = (hipStream_t)hip_stream;
+    return EF21_OK;
+}
+
+int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_idx, float *out_val,
+              void *hip_stream) {
+    if (int rc = check_topk_sizes(n, d, k)) return rc;
+    if (!rows || !out_idx || !out_val) return fail(EF21_EINVAL, "rows, out_idx and out_val must not be NULL");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    void *ws = nullptr;
+    if (use_split(d)) {
+        int dev = 0;
+        EF21_HIP(hipGetDevice(&dev));
+        if (dev < 0 || dev >= 64) return fail(EF21_ESTATE, "device ordinal out of range");
+        const size_t need = ef21::topk_split_workspace_bytes(n, d, k);
+        std::lock_guard<std::mutex> lock(g_topk_ws.mu);
+        if (g_topk_ws.bytes[dev] < need) {
+            EF21_HIP(hipDeviceSynchronize());
+            (void)hipFree(g_topk_ws.ptr[dev]);
+            g_topk_ws.ptr[dev] = nullptr;
+            g_topk_ws.bytes[dev] = 0;
+            if (hipMalloc(&g_topk_ws.ptr[dev], need) != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(EF21_ENOMEM, "hipMalloc of the Top-k workspace failed");
+            }
+            g_topk_ws.bytes[dev] = need;
+        }
+        ws = g_topk_ws.ptr[dev];
+    }
+    ef21::TopkArgs p{rows, nullptr, n, d, k, out_idx, out_val, nullptr, nullptr, 0.f};
+    return enqueue_topk(p, ws, stream);
+}
+
+int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_t m, float lambda) {
+    if (int rc = check_handle(h)) return rc;
+    if (!A || !y) return fail(EF21_EINVAL, "A and y must not be NULL");
+    if (m < 1 || m >= ((int64_t)1 << 31)) return fail(EF21_EINVAL, "m must be in [1, 2^31)");
+    if (!(lambda >= 0.f) || !std::isfinite(lambda)) return fail(EF21_EINVAL, "lambda must be finite and >= 0");
+    if (int rc = ensure_problem_buffers(h, ef21::logreg_dense_scratch_bytes(h->n, m, h->d))) return rc;
+    h->kind = kDense;
+    h->A = A;
+    h->y = y;
+    h->m = m;
+    h->lambda = lambda;
+    return EF21_OK;
+}
+
+int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *col, const float *val,
+                         const float *y, int64_t m, float lambda) {
+    if (int rc = check_handle(h)) return rc;
+    if (!rowptr || !col || !val || !y) return fail(EF21_EINVAL, "rowptr, col, val and y must not be NULL");
+    if (m < 1 || m >= ((int64_t)1 << 31)) return fail(EF21_EINVAL, "m must be in [1, 2^31)");
+    if (!(lambda >= 0.f) || !std::isfinite(lambda)) return fail(EF21_EINVAL, "lambda must be finite and >= 0");
+    if (int rc = ensure_problem_buffers(h, 0)) return rc;
+    h->kind = kCSR;
+    h->rowptr = rowptr;
+    h->col = col;
+    h->val = val;
+    h->y = y;
+    h->m = m;
+    h->lambda = lambda;
+    return EF21_OK;
+}
+
+int ef21_set_state(ef21_handle h, const float *x, const float *g_i, const float *g) {
+    if (int rc = check_handle(h)) return rc;
+    const size_t db = sizeof(float) * (size_t)h->d;
+    if (x) EF21_HIP(hipMemcpyAsync(h->x, x, db, hipMemcpyDeviceToDevice, h->stream));
+    if (g_i) EF21_HIP(hipMemcpyAsync(h->g_i, g_i, db * h->n, hipMemcpyDeviceToDevice, h->stream));
+    if (g) {
+        EF21_HIP(hipMemcpyAsync(h->g, g, db, hipMemcpyDeviceToDevice, h->stream));
+    } else {
+        hipError_t st = ef21::launch_mean_rows(h->g_i, h->g, h->n, h->d, h->stream);
+        if (st != hipSuccess) return fail_hip(st, "mean kernel launch");
+    }
+    return EF21_OK;
+}
+
+int ef21_get_state(ef21_handle h, float *x, float *g_i, float *g) {
+    if (int rc = check_handle(h)) return rc;
+    const size_t db = sizeof(float) * (size_t)h->d;
+    if (x) EF21_HIP(hipMemcpyAsync(x, h->x, db, hipMemcpyDeviceToDevice, h->stream));
+    if (g_i) EF21_HIP(hipMemcpyAsync(g_i, h->g_i, db * h->n, hipMemcpyDeviceToDevice, h->stream));
+    if (g) EF21_HIP(hipMemcpyAsync(g, h->g, db, hipMemcpyDeviceToDevice, h->stream));
+    return EF21_OK;
+}
+
+int ef21_get_messages(ef21_handle h, int32_t *idx, float *val) {
+    if (int rc = check_handle(h)) return rc;
+    const size_t nk = (size_t)h->n * h->k;
+    if (idx) EF21_HIP(hipMemcpyAsync(idx, h->msg_idx, sizeof(int32_t) * nk, hipMemcpyDeviceToDevice, h->stream));
+    if (val) EF21_HIP(hipMemcpyAsync(val, h->msg_val, sizeof(float) * nk, hipMemcpyDeviceToDevice, h->stream));
+    return EF21_OK;
+}
+
+int ef21_local_grad(ef21_handle h, const float *x, float *out_grad) {
+    if (int rc = check_handle(h)) return rc;
+    if (!out_grad) return fail(EF21_EINVAL, "out_grad must not be NULL");
+    if (h->kind == kNone) return fail(EF21_ESTATE, "no problem attached (ef21_set_problem_dense / _csr)");
+    return enqueue_local_grad(h, x ? x : h->x, out_grad);
+}
+
+int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
+    if (int rc = check_handle(h)) return rc;
+    if (flags > EF21_ORDER_STEP_FIRST) return fail(EF21_EINVAL, "unknown flags");
+    if (!grads && h->kind == kNone)
+        return fail(EF21_ESTATE, "grads is NULL and no problem is attached to compute them from");
+    const bool step_first = flags == EF21_ORDER_STEP_FIRST;
+    if (step_first) {   // Algorithm 2, line 3
+        hipError_t st = ef21::launch_model_step(h->x, h->g, h->d, h->gamma, h->stream);
+        if (st != hipSuccess) return fail_hip(st, "model step launch");
+    }
+    if (!grads) {
+        if (int rc = enqueue_local_grad(h, h->x, h->grad)) return rc;
+        grads = h->grad;
+    }
+    // lines 5, 6, 8: Top-k of grads - g_i, fused with the update of g_i and g
+    ef21::TopkArgs p{grads, h->g_i, h->n, h->d, h->k, h->msg_idx, h->msg_val, h->g_i, h->g, 1.0f / (float)h->n};
+    if (int rc = enqueue_topk(p, h->topk_ws, h->stream)) return rc;
+    if (!step_first) {
+        hipError_t st = ef21::launch_model_step(h->x, h->g, h->d, h->gamma, h->stream);
+        if (st != hipSuccess) return fail_hip(st, "model step launch");
+    }
+    return EF21_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Host-side launchers of the HIP kernels.  Each enqueues on `stream` and returns the HIP status
+// of the launch; none of them allocates or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ef21 {
+
+// Arguments of one batched Top-k (Section 2.1) over n rows of length d.
+//   a, b      v = a - b if b != nullptr (the difference of Algorithm 2, line 5), else v = a
+//   out_idx, out_val   [n][k] ascending positions and signed values
+//   g_i, g    if g_i != nullptr the kept entries also update the EF21 state in place
+//             (lines 6 and 8 of Algorithm 2): g_i[row][j] = b[row][j] + v,  g[j] += v * inv_n
+struct TopkArgs {
+    const float *a;
+    const float *b;
+    int32_t n;
+    int64_t d;
+    int64_t k;
+    int32_t *out_idx;
+    float *out_val;
+    float *g_i;
+    float *g;
+    float inv_n;
+};
+
+// One workgroup per row, four radix passes over the row plus an ordered emission.  Needs no
+// workspace and is correct for every input; meant for rows that one compute unit can stream
+// quickly (and as the reference device path for long rows).
+hipError_t launch_topk_row(const TopkArgs &p, hipStream_t stream);
+
+// Many workgroups per row for long rows.  Workspace layout and size: topk_split_workspace_bytes.
+size_t topk_split_workspace_bytes(int32_t n, int64_t d, int64_t k);
+hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t stream);
+
+// Algorithm 2, line 3: x <- x - gamma g.
+hipError_t launch_model_step(float *x, const float *g, int64_t d, float gamma, hipStream_t stream);
+
+// g = (1/n) sum_i g_i (input line of Algorithm 2), summed in worker order.
+hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hipStream_t stream);
+
+// Gradient of eq. (9) for all workers, dense rows.  scratch: logreg_dense_scratch_bytes.
+size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d);
+hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
+                                    int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream);
+
+// Gradient of eq. (9) for all workers, CSR rows.
+hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
+                                  const float *x, float *grad, int32_t n, int64_t m, int64_t d, float lambda,
+                                  hipStream_t stream);
+
+}  // namespace ef21

@@ -1,0 +1,255 @@
+// Local gradients of the objective of Section 5, eq. (9), for all workers:
+//   grad f_i(x) = (1/m) sum_l  -y_l / (1 + exp(y_l a_l^T x)) a_l  +  2 lambda x_j / (1 + x_j^2)^2.
+//
+// These are GEMV-shaped (each matrix entry is used twice, about one flop per byte), far below
+// the matrix-core ridge, so they are written as coalesced streaming kernels, not MFMA tiles.
+//
+// Dense rows, d <= 4096: ONE pass over A.  A wavefront owns whole rows; a lane keeps its columns
+// of the row in registers between the dot product (wavefront reduction, no LDS) and the rank-one
+// accumulation r_l * a_l into per-lane accumulators.  Workgroups write partial sums that a small
+// second kernel adds in a fixed order (bitwise reproducible), together with the regulariser.
+// Dense rows, larger d: z = A x, then A^T r, two passes.  CSR rows: one wavefront per row,
+// gather x, scatter-add into the worker's gradient with fp32 atomics.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace ef21 {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+
+struct DensePlan {
+    int64_t rows_per_wg;
+    int64_t chunks;   // workgroups (row blocks) per worker
+};
+
+DensePlan dense_plan(int32_t n, int64_t m) {
+    int64_t rows = ((int64_t)n * m + 2047) / 2048;
+    if (rows < 8) rows = 8;
+    rows = (rows + kWaves - 1) / kWaves * kWaves;
+    return {rows, (m + rows - 1) / rows};
+}
+
+__device__ __forceinline__ float residual(float y, float z) {   // -y / (1 + exp(y z))
+    return -y / (1.0f + expf(y * z));
+}
+
+// ------------------------------------------------------------------ dense, one pass over A
+template <int VEC, int NQ>
+__global__ __launch_bounds__(kThreads) void logreg_dense_fused_kernel(const float *__restrict__ A,
+                                                                      const float *__restrict__ y,
+                                                                      const float *__restrict__ x,
+                                                                      float *__restrict__ part, int64_t m,
+                                                                      int64_t d, int64_t rows_per_wg) {
+    constexpr int kCols = NQ * kWave * VEC;   // columns covered by one wavefront
+    __shared__ float red[kCols];
+    const int64_t worker = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
+    const int wave = threadIdx.x / kWave, lane = lane_id();
+
+    float xr[NQ][VEC], acc[NQ][VEC];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int64_t c0 = ((int64_t)q * kWave + lane) * VEC;
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) {
+            xr[q][t] = (c0 + t < d) ? x[c0 + t] : 0.f;
+            acc[q][t] = 0.f;
+        }
+    }
+
+    const int64_t l0 = chunk * rows_per_wg;
+    const int64_t l1 = l0 + rows_per_wg < m ? l0 + rows_per_wg : m;
+    for (int64_t l = l0 + wave; l < l1; l += kWaves) {
+        const float *row = A + (worker * m + l) * d;
+        float av[NQ][VEC];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const int64_t c0 = ((int64_t)q * kWave + lane) * VEC;
+            if constexpr (VEC == 4) {
+                float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (c0 < d) t4 = *reinterpret_cast<const float4 *>(row + c0);
+                av[q][0] = t4.x;
+                av[q][1] = t4.y;
+                av[q][2] = t4.z;
+                av[q][3] = t4.w;
+            } else {
+                av[q][0] = (c0 < d) ? row[c0] : 0.f;
+            }
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) s = fmaf(av[q][t], xr[q][t], s);
+        s = wave_sum(s);
+        const float r = residual(y[worker * m + l], s);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) acc[q][t] = fmaf(r, av[q][t], acc[q][t]);
+    }
+
+    // add the four wavefronts' accumulators in wavefront order
+    for (int w = 0; w < kWaves; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) {
+                    const int c = (q * kWave + lane) * VEC + t;
+                    red[c] = (w == 0 ? 0.f : red[c]) + acc[q][t];
+                }
+        }
+        __syncthreads();
+    }
+    float *out = part + (worker * chunks + chunk) * d;
+    for (int c = threadIdx.x; c < kCols && c < d; c += kThreads) out[c] = red[c];
+}
+
+// ------------------------------------------------------------------ dense, any d: two passes
+__global__ __launch_bounds__(kThreads) void logreg_dense_residual_kernel(const float *__restrict__ A,
+                                                                         const float *__restrict__ y,
+                                                                         const float *__restrict__ x,
+                                                                         float *__restrict__ r, int64_t rows,
+                                                                         int64_t d) {
+    const int lane = lane_id();
+    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
+    for (int64_t l = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; l < rows; l += nwaves) {
+        const float *row = A + l * d;
+        float s = 0.f;
+        for (int64_t c = lane; c < d; c += kWave) s = fmaf(row[c], x[c], s);
+        s = wave_sum(s);
+        if (lane == 0) r[l] = residual(y[l], s);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void logreg_dense_atr_kernel(const float *__restrict__ A,
+                                                                    const float *__restrict__ r,
+                                                                    float *__restrict__ part, int64_t m, int64_t d,
+                                                                    int64_t rows_per_wg) {
+    const int64_t worker = blockIdx.z, chunk = blockIdx.y, chunks = gridDim.y;
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (c >= d) return;
+    const int64_t l0 = chunk * rows_per_wg;
+    const int64_t l1 = l0 + rows_per_wg < m ? l0 + rows_per_wg : m;
+    float acc = 0.f;
+    for (int64_t l = l0; l < l1; ++l) acc = fmaf(r[worker * m + l], A[(worker * m + l) * d + c], acc);
+    part[(worker * chunks + chunk) * d + c] = acc;
+}
+
+// grad[i][j] = (sum over row blocks, in block order) / m + regulariser gradient
+__global__ __launch_bounds__(kThreads) void logreg_dense_finish_kernel(const float *__restrict__ part,
+                                                                       const float *__restrict__ x,
+                                                                       float *__restrict__ grad, int64_t chunks,
+                                                                       int64_t m, int64_t d, float lambda) {
+    const int64_t worker = blockIdx.y;
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (c >= d) return;
+    double s = 0.0;
+    for (int64_t k = 0; k < chunks; ++k) s += (double)part[(worker * chunks + k) * d + c];
+    const double xj = (double)x[c], q = 1.0 + xj * xj;
+    grad[worker * d + c] = (float)(s / (double)m + 2.0 * (double)lambda * xj / (q * q));
+}
+
+// ------------------------------------------------------------------ CSR
+__global__ __launch_bounds__(kThreads) void logreg_csr_regulariser_kernel(const float *__restrict__ x,
+                                                                          float *__restrict__ grad, int64_t d,
+                                                                          float lambda) {
+    const int64_t worker = blockIdx.y;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x; c < d; c += stride) {
+        const float xj = x[c], q = 1.0f + xj * xj;
+        grad[worker * d + c] = 2.0f * lambda * xj / (q * q);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void logreg_csr_kernel(const int64_t *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ col,
+                                                              const float *__restrict__ val,
+                                                              const float *__restrict__ y,
+                                                              const float *__restrict__ x, float *grad, int64_t rows,
+                                                              int64_t m, int64_t d, float inv_m) {
+    const int lane = lane_id();
+    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
+    for (int64_t l = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; l < rows; l += nwaves) {
+        const int64_t p0 = rowptr[l], p1 = rowptr[l + 1];
+        float s = 0.f;
+        // a column index outside [0, d) is skipped rather than dereferenced
+        for (int64_t p = p0 + lane; p < p1; p += kWave) {
+            const uint32_t c = (uint32_t)col[p];
+            if (c < (uint64_t)d) s = fmaf(val[p], x[c], s);
+        }
+        s = wave_sum(s);
+        const float coef = residual(y[l], s) * inv_m;
+        float *g = grad + (l / m) * d;
+        for (int64_t p = p0 + lane; p < p1; p += kWave) {
+            const uint32_t c = (uint32_t)col[p];
+            if (c < (uint64_t)d) atomicAdd(g + c, coef * val[p]);
+        }
+    }
+}
+
+template <int VEC, int NQ>
+void launch_fused(const float *A, const float *y, const float *x, float *part, int32_t n, int64_t m, int64_t d,
+                  const DensePlan &pl, hipStream_t stream) {
+    hipLaunchKernelGGL((logreg_dense_fused_kernel<VEC, NQ>), dim3((unsigned)pl.chunks, (unsigned)n), dim3(kThreads),
+                       0, stream, A, y, x, part, m, d, pl.rows_per_wg);
+}
+
+}  // namespace
+
+size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d) {
+    const DensePlan pl = dense_plan(n, m);
+    return sizeof(float) * ((size_t)n * pl.chunks * d + (size_t)n * m);   // partial sums + residuals
+}
+
+hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
+                                    int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream) {
+    const DensePlan pl = dense_plan(n, m);
+    float *part = (float *)scratch;
+    float *resid = part + (size_t)n * pl.chunks * d;
+    const bool vec4 = (d % 4 == 0) && ((uintptr_t)A % 16 == 0);
+    bool fused = true;
+    if (vec4 && d <= 256) launch_fused<4, 1>(A, y, x, part, n, m, d, pl, stream);
+    else if (vec4 && d <= 512) launch_fused<4, 2>(A, y, x, part, n, m, d, pl, stream);
+    else if (vec4 && d <= 1024) launch_fused<4, 4>(A, y, x, part, n, m, d, pl, stream);
+    else if (vec4 && d <= 2048) launch_fused<4, 8>(A, y, x, part, n, m, d, pl, stream);
+    else if (vec4 && d <= 4096) launch_fused<4, 16>(A, y, x, part, n, m, d, pl, stream);
+    else if (d <= 128) launch_fused<1, 2>(A, y, x, part, n, m, d, pl, stream);
+    else if (d <= 512) launch_fused<1, 8>(A, y, x, part, n, m, d, pl, stream);
+    else if (d <= 2048) launch_fused<1, 32>(A, y, x, part, n, m, d, pl, stream);
+    else fused = false;
+    if (!fused) {
+        const int64_t rows = (int64_t)n * m;
+        int64_t blocks = (rows + kWaves - 1) / kWaves;
+        if (blocks > 16384) blocks = 16384;
+        hipLaunchKernelGGL(logreg_dense_residual_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, A, y, x,
+                           resid, rows, d);
+        hipLaunchKernelGGL(logreg_dense_atr_kernel,
+                           dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)pl.chunks, (unsigned)n),
+                           dim3(kThreads), 0, stream, A, resid, part, m, d, pl.rows_per_wg);
+    }
+    hipError_t st = hipGetLastError();
+    if (st != hipSuccess) return st;
+    hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)n),
+                       dim3(kThreads), 0, stream, part, x, grad, pl.chunks, m, d, lambda);
+    return hipGetLastError();
+}
+
+hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
+                                  const float *x, float *grad, int32_t n, int64_t m, int64_t d, float lambda,
+                                  hipStream_t stream) {
+    int64_t rb = (d + kThreads - 1) / kThreads;
+    if (rb > 1024) rb = 1024;
+    hipLaunchKernelGGL(logreg_csr_regulariser_kernel, dim3((unsigned)rb, (unsigned)n), dim3(kThreads), 0, stream, x,
+                       grad, d, lambda);
+    const int64_t rows = (int64_t)n * m;
+    int64_t blocks = (rows + kWaves - 1) / kWaves;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(logreg_csr_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, rowptr, col, val, y, x,
+                       grad, rows, m, d, 1.0f / (float)m);
+    return hipGetLastError();
+}
+
+}  // namespace ef21

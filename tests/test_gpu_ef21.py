@@ -1,0 +1,256 @@
+"""GPU parity of the EF21 iteration (ef21_step through the C ABI) against the CPU oracle.
+
+Bars: messages (positions, values) and g_i bit-exact when both sides start from the same state and
+see the same gradients; g and x within 1e-5 relative per coordinate (g is summed with fp32 atomics,
+the oracle sums in fp64); f(x^t) within 1e-4 relative over a whole run with GPU-computed gradients.
+"""
+import numpy as np
+import pytest
+
+from helpers import close_per_coordinate, same_bits
+from paper_2106_05203_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2106_05203_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    return torch, binding
+
+
+def to_gpu(torch, a, dtype=np.float32):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
+
+
+def compare_state(torch, h, st, msgs=True, rows=None):
+    x, g_i, g = (t.cpu().numpy() for t in h.get_state())
+    rows = range(h.n) if rows is None else rows
+    for i in rows:
+        assert same_bits(g_i[i], st.g_i[i].astype(np.float32)), f"g_i row {i} differs"
+    if msgs:
+        idx, val = (t.cpu().numpy() for t in h.get_messages())
+        for i in rows:
+            assert np.array_equal(idx[i], st.msg_idx[i]), f"message positions of worker {i} differ"
+            assert same_bits(val[i], st.msg_val[i].astype(np.float32)), f"message values of worker {i} differ"
+    ok, info = close_per_coordinate(g, st.g)
+    assert ok, f"g: max err, #bad = {info}"
+    ok, info = close_per_coordinate(x, st.x)
+    assert ok, f"x: max err, #bad = {info}"
+    return x, g_i, g
+
+
+@pytest.mark.parametrize("n,d,k", [(1, 1, 1), (4, 100, 1), (3, 1000, 1000), (7, 4099, 41), (20, 2000, 20),
+                                   (5, 70001, 700), (3, 300_000, 3000)])
+@pytest.mark.parametrize("order", ["grad_first", "step_first"])
+def test_single_step_from_oracle_state(gpu, oracle, n, d, k, order):
+    torch, binding = gpu
+    print(f"step case n={n} d={d} k={k} {order}", flush=True)
+    rng = np.random.default_rng(n * 1000 + d + k)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    g_i0 = rng.standard_normal((n, d)).astype(np.float32)
+    g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+    gamma = 0.25
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+        for t in range(3):
+            grads = (g_i0 + 0.3 * rng.standard_normal((n, d))).astype(np.float32)
+            if t == 1:     # exact zeros in the difference: ties at magnitude 0
+                grads[:, ::7] = st.g_i[:, ::7].astype(np.float32)
+            oracle.iteration(st, grads.astype(np.float64), k, gamma, order=order, storage_f32=True)
+            h.step(to_gpu(torch, grads), binding.ORDER_GRAD_FIRST if order == "grad_first" else binding.ORDER_STEP_FIRST)
+            torch.cuda.synchronize()
+            x, g_i, g = compare_state(torch, h, st)
+            # resynchronise g and x to the oracle's so the next step is again a single-step comparison
+            h.set_state(to_gpu(torch, st.x), None, to_gpu(torch, st.g))
+
+
+def test_first_pass_compresses_zero_vector(gpu, oracle):
+    """g_i^0 = grad: the first grad-first pass sees v = 0; k zero-valued pairs at positions 0..k-1
+    are emitted and the state does not change."""
+    torch, binding = gpu
+    n, d, k = 3, 5000, 50
+    rng = np.random.default_rng(0)
+    grads = rng.standard_normal((n, d)).astype(np.float32)
+    with binding.EF21(n, d, k, 0.5) as h:
+        h.set_state(None, to_gpu(torch, grads), None)
+        h.step(to_gpu(torch, grads))
+        torch.cuda.synchronize()
+        idx, val = (t.cpu().numpy() for t in h.get_messages())
+        assert np.array_equal(idx, np.tile(np.arange(k, dtype=np.int32), (n, 1)))
+        assert np.all(val == 0.0)
+        x, g_i, g = (t.cpu().numpy() for t in h.get_state())
+        assert same_bits(g_i, grads)
+        ok, info = close_per_coordinate(g, grads.astype(np.float64).mean(axis=0))
+        assert ok, info
+
+
+def test_k_equals_d_is_gradient_descent(gpu, oracle):
+    torch, binding = gpu
+    W = workloads.logreg_dense(n=4, d=64, m=50, seed=3)
+    P = oracle.LogRegDense(W.A, W.y, 0.1)
+    gamma = 0.5
+    x = np.zeros(P.d)
+    with binding.EF21(P.n, P.d, P.d, gamma) as h:
+        h.set_problem_dense(to_gpu(torch, W.A), to_gpu(torch, W.y), 0.1)
+        h.set_state(to_gpu(torch, x), to_gpu(torch, P.grads(x)), None)
+        for t in range(20):
+            h.step(None, binding.ORDER_STEP_FIRST)
+            x = x - gamma * P.grads(x).mean(axis=0)
+            torch.cuda.synchronize()
+            got = h.get_x().cpu().numpy()
+            assert np.max(np.abs(got - x)) <= 2e-6 * max(1.0, np.max(np.abs(x))), t
+
+
+def run_both(gpu, oracle, P, set_problem, k, gamma, iters, order="grad_first"):
+    torch, binding = gpu
+    x0 = np.zeros(P.d)
+    st = oracle.init_state(x0, P.grads(x0), k, init="grad", storage_f32=True)
+    f_ref, f_gpu, first_set_diff = [], [], None
+    with binding.EF21(P.n, P.d, k, gamma) as h:
+        set_problem(h)
+        h.set_state(to_gpu(torch, st.x), to_gpu(torch, st.g_i), to_gpu(torch, st.g))
+        flag = binding.ORDER_GRAD_FIRST if order == "grad_first" else binding.ORDER_STEP_FIRST
+        for t in range(iters):
+            oracle.iteration(st, P.grads, k, gamma, order=order, storage_f32=True)
+            h.step(None, flag)
+            xg = h.get_x().cpu().numpy().astype(np.float64)
+            f_ref.append(P.loss(st.x))
+            f_gpu.append(P.loss(xg))
+            if first_set_diff is None:
+                idx = h.get_messages()[0].cpu().numpy()
+                if not np.array_equal(idx, st.msg_idx):
+                    first_set_diff = t
+        xg, g_i, g = (a.cpu().numpy() for a in h.get_state())
+    return np.array(f_ref), np.array(f_gpu), first_set_diff, (xg, g_i, g), st
+
+
+def test_config0_hundred_steps(gpu, oracle):
+    """n = 4, d = 100, m = 250, Top-1, gamma = 0.1, 100 iterations from x = 0, g_i^0 = grad f_i(0):
+    f(x^t) on the GPU trajectory within 1e-4 relative of the oracle's at every t."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C0"]
+    W = workloads.logreg_dense(c["n"], c["d"], c["m"], seed=c["seed"])
+    P = oracle.LogRegDense(W.A, W.y, c["lam"])
+    A, y = to_gpu(torch, W.A), to_gpu(torch, W.y)
+    f_ref, f_gpu, first_diff, (xg, g_i, g), st = run_both(
+        gpu, oracle, P, lambda h: h.set_problem_dense(A, y, c["lam"]), c["k"], c["gamma"], c["iters"])
+    rel = np.abs(f_gpu - f_ref) / np.abs(f_ref)
+    print(f"C0: max rel f diff {rel.max():.3e}, first differing message set at t={first_diff}", flush=True)
+    assert rel.max() <= 1e-4
+    assert f_ref[-1] < f_ref[0]
+    # invariant of Section 3.3 on the GPU state
+    assert np.allclose(g, g_i.astype(np.float64).mean(axis=0), rtol=1e-4, atol=1e-7)
+
+
+def test_dense_medium_run(gpu, oracle):
+    """Shape class of config 2 (d = 2000, k = 1 % of d) at a size the oracle runs in seconds."""
+    torch, binding = gpu
+    W = workloads.logreg_dense(n=6, d=2000, m=300, seed=5)
+    P = oracle.LogRegDense(W.A, W.y, 0.1)
+    A, y = to_gpu(torch, W.A), to_gpu(torch, W.y)
+    f_ref, f_gpu, first_diff, (xg, g_i, g), st = run_both(
+        gpu, oracle, P, lambda h: h.set_problem_dense(A, y, 0.1), 20, 0.5, 40)
+    rel = np.abs(f_gpu - f_ref) / np.abs(f_ref)
+    print(f"dense medium: max rel f diff {rel.max():.3e}, first differing message set at t={first_diff}", flush=True)
+    assert rel.max() <= 1e-4
+    assert np.allclose(g, g_i.astype(np.float64).mean(axis=0), rtol=1e-4, atol=1e-7)
+
+
+def test_csr_medium_run(gpu, oracle):
+    """Shape class of config 3 (1 % dense CSR rows, k = 1 % of d)."""
+    torch, binding = gpu
+    W = workloads.logreg_csr(n=8, d=5000, m=300, nnz_per_row=50, seed=6)
+    P = oracle.LogRegCSR(W.rowptr, W.col, W.val, W.y, W.n, W.m, W.d, 0.1)
+    rp, col, val, y = (to_gpu(torch, W.rowptr, np.int64), to_gpu(torch, W.col, np.int32), to_gpu(torch, W.val),
+                       to_gpu(torch, W.y))
+    f_ref, f_gpu, first_diff, (xg, g_i, g), st = run_both(
+        gpu, oracle, P, lambda h: h.set_problem_csr(rp, col, val, y, W.m, 0.1), 50, 0.5, 40)
+    rel = np.abs(f_gpu - f_ref) / np.abs(f_ref)
+    print(f"csr medium: max rel f diff {rel.max():.3e}, first differing message set at t={first_diff}", flush=True)
+    assert rel.max() <= 1e-4
+    assert np.allclose(g, g_i.astype(np.float64).mean(axis=0), rtol=1e-4, atol=1e-7)
+
+
+def test_config4_scaled_run(gpu, oracle):
+    """Config 4 at d/100 (n = 8, d = 112000, k = 1120, gamma = 0.01), all 200 iterations with fresh
+    Student-t gradients each step, from the zero state: messages and g_i bit-exact throughout."""
+    torch, binding = gpu
+    n, d, k, gamma = 8, 112_000, 1120, 0.01
+    st = oracle.EF21State(np.zeros(d), np.zeros((n, d)), np.zeros(d))
+    with binding.EF21(n, d, k, gamma) as h:
+        for t in range(200):
+            grads = workloads.student_t_grads(n, d, seed=1000 + t)
+            oracle.iteration(st, grads.astype(np.float64), k, gamma, storage_f32=True)
+            h.step(to_gpu(torch, grads))
+            if t % 20 == 19 or t < 3:
+                torch.cuda.synchronize()
+                compare_state(torch, h, st)
+        torch.cuda.synchronize()
+        compare_state(torch, h, st)
+
+
+@pytest.mark.timeout(600)
+def test_config4_full_size_step(gpu, oracle):
+    """Config 4 at full size (n = 8, d = 11.2e6, k = 112000): two steps; three workers' messages and
+    g_i rows are compared one by one with the oracle, the rest through invariants."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C4"]
+    n, d, k, gamma = c["n"], c["d"], c["k"], c["gamma"]
+    rows = [0, 3, 7]
+    g_i_ref = np.zeros((n, d), dtype=np.float32)
+    with binding.EF21(n, d, k, gamma) as h:
+        for t in range(2):
+            print(f"C4 full size step {t}", flush=True)
+            grads = workloads.student_t_grads(n, d, seed=7 + t)
+            h.step(to_gpu(torch, grads))
+            torch.cuda.synchronize()
+            idx, val = (a.cpu().numpy() for a in h.get_messages())
+            x, g_i, g = (a.cpu().numpy() for a in h.get_state())
+            for i in rows:
+                v = grads[i] - g_i_ref[i]                       # fp32 subtraction, as in line 5
+                ref_idx, ref_val = oracle.topk(v.astype(np.float64), k)
+                assert np.array_equal(idx[i], ref_idx), f"step {t} worker {i}"
+                assert same_bits(val[i], ref_val.astype(np.float32))
+            # every worker: k ascending positions, values are the differences, g_i updated there only
+            assert np.all(np.diff(idx.astype(np.int64), axis=1) > 0)
+            v_all = grads - g_i_ref
+            assert same_bits(val, np.take_along_axis(v_all, idx.astype(np.int64), axis=1))
+            thr = np.abs(val).min(axis=1)
+            for i in range(n):
+                expect = g_i_ref[i].copy()
+                expect[idx[i]] = g_i_ref[i][idx[i]] + val[i]
+                assert same_bits(g_i[i], expect)
+                dropped = np.ones(d, dtype=bool)
+                dropped[idx[i]] = False
+                assert np.abs(v_all[i][dropped]).max() <= thr[i]
+            g_i_ref = g_i
+            ok, info = close_per_coordinate(g, g_i.astype(np.float64).mean(axis=0), rel=1e-5)
+            assert ok, info
+
+
+def test_get_set_state_roundtrip_and_errors(gpu):
+    torch, binding = gpu
+    with binding.EF21(3, 17, 4, 0.1) as h:
+        x = torch.randn(17, device="cuda")
+        g_i = torch.randn(3, 17, device="cuda")
+        h.set_state(x, g_i, None)
+        x2, g_i2, g2 = h.get_state()
+        torch.cuda.synchronize()
+        assert torch.equal(x, x2) and torch.equal(g_i, g_i2)
+        assert torch.allclose(g2, g_i.double().mean(0).float(), rtol=1e-6, atol=1e-7)
+        with pytest.raises(binding.EF21Error) as e:
+            h.step(None)                       # no problem attached
+        assert e.value.code == binding.EF21_ESTATE
+        with pytest.raises(binding.EF21Error) as e:
+            h.local_grad()
+        assert e.value.code == binding.EF21_ESTATE
+        with pytest.raises(ValueError):
+            h.step(torch.zeros(2, 17, device="cuda"))
+    for bad in [(0, 5, 1, 0.1), (2, 5, 6, 0.1), (2, 5, 1, -1.0)]:
+        with pytest.raises(binding.EF21Error):
+            binding.EF21(*bad)

@@ -1,0 +1,115 @@
+"""GPU parity of the batched Top-k (ef21_topk through the C ABI) against the CPU oracle:
+positions bit-exact, values bit-exact (they are copies of the inputs)."""
+import numpy as np
+import pytest
+
+from helpers import same_bits
+from paper_2106_05203_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2106_05203_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    return torch, binding
+
+
+def run_gpu(gpu, V, k):
+    torch, binding = gpu
+    t = torch.from_numpy(np.ascontiguousarray(V, dtype=np.float32)).cuda()
+    idx, val = binding.ef21_topk(t, k)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), val.cpu().numpy()
+
+
+def check(gpu, oracle, V, k, rows=None):
+    print(f"topk case n={V.shape[0]} d={V.shape[1]} k={k}", flush=True)
+    idx, val = run_gpu(gpu, V, k)
+    rows = range(V.shape[0]) if rows is None else rows
+    for i in rows:
+        ref_idx, ref_val = oracle.topk(V[i].astype(np.float64), k)
+        assert np.array_equal(idx[i], ref_idx), f"row {i}: positions differ"
+        assert same_bits(val[i], ref_val.astype(np.float32)), f"row {i}: values differ"
+    # properties that hold for every row at any size
+    assert np.all(np.diff(idx.astype(np.int64), axis=1) > 0)
+    assert np.all((idx >= 0) & (idx < V.shape[1]))
+    assert same_bits(val, np.take_along_axis(V, idx.astype(np.int64), axis=1))
+    return idx, val
+
+
+def test_tiny_patterns(gpu, oracle):
+    pats = [
+        [0.0], [-3.0], [0.0, 0.0, 0.0, 0.0], [0.0, -0.0, 0.0, -0.0, 1.0],
+        [1.0, -1.0, 1.0, -1.0, 1.0], [3, -5, 1, 5, -2], [5, 4, 3, 2, 1, 0, -1, -2, -3, -4, -5],
+        [1e-45, -1e-45, 0.0, 2e-45], [np.inf, -np.inf, 1.0, 3e38],
+    ]
+    for v in pats:
+        v = np.array(v, dtype=np.float32)
+        for k in range(1, v.size + 1):
+            check(gpu, oracle, v[None, :].repeat(3, axis=0), k)
+
+
+@pytest.mark.parametrize("d", [1, 2, 63, 64, 65, 127, 1000, 1023, 1024, 1025, 4096, 5000, 16385, 40000])
+def test_random_small_rows(gpu, oracle, d):
+    rng = np.random.default_rng(d)
+    V = rng.standard_normal((5, d)).astype(np.float32)
+    V[1] = np.round(V[1] * 2) / 2                      # heavy ties
+    V[2] = 0.0                                         # all equal
+    V[3, ::3] = -V[3, (d // 2) % d]                    # one value repeated with flipped sign
+    V[4] *= np.float32(1e-41)                          # subnormals
+    for k in sorted({1, 2, max(1, d // 100), max(1, d // 2), d - 1 if d > 1 else 1, d}):
+        check(gpu, oracle, V, k)
+
+
+@pytest.mark.parametrize("d,k", [(70001, 700), (262144, 5), (300007, 3000), (1_000_003, 999)])
+def test_long_rows_ragged(gpu, oracle, d, k):
+    V = workloads.topk_rows(3, d, seed=d % 1000)
+    check(gpu, oracle, V, k)
+    W = workloads.force_threshold_ties(V, k, copies=8, seed=1)
+    check(gpu, oracle, W, k)
+
+
+def test_long_rows_degenerate(gpu, oracle):
+    d = 200_000
+    V = np.zeros((4, d), dtype=np.float32)
+    V[1] = 1.5
+    V[1, ::2] = -1.5
+    V[2, 1000:] = np.float32(2.0) ** -130               # subnormal plateau
+    V[3] = np.arange(d, dtype=np.float32)[::-1]
+    for k in (1, 777, d // 2, d):
+        check(gpu, oracle, V, k)
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("k", [1, 1000, 10000])
+def test_config1_full_size(gpu, oracle, k):
+    """n = 20 rows of 10^6 N(0,1) values with 1 % exact duplicates (+a / -a), the size the
+    throughput is quoted on, and the variant whose threshold magnitude is tied."""
+    V = workloads.topk_rows(20, 1_000_000, seed=0)
+    check(gpu, oracle, V, k)
+    W = workloads.force_threshold_ties(V[:4], k, copies=8, seed=2)
+    check(gpu, oracle, W, k)
+
+
+def test_deterministic(gpu):
+    torch, binding = gpu
+    V = torch.from_numpy(workloads.topk_rows(6, 300_000, seed=9)).cuda()
+    a = binding.ef21_topk(V, 3000)
+    b = binding.ef21_topk(V, 3000)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+def test_error_codes(gpu):
+    torch, binding = gpu
+    V = torch.zeros((2, 10), device="cuda")
+    for k in (0, 11):
+        with pytest.raises(binding.EF21Error) as e:
+            binding.ef21_topk(V, k)
+        assert e.value.code == binding.EF21_EINVAL
+    with pytest.raises(TypeError):
+        binding.ef21_topk(V.double(), 1)
