@@ -7,7 +7,7 @@ the oracle sums in fp64); f(x^t) within 1e-4 relative over a whole run with GPU-
 import numpy as np
 import pytest
 
-from helpers import close_per_coordinate, same_bits
+from helpers import RoundingBudget, close_per_coordinate, same_bits
 from paper_2106_05203_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -26,7 +26,22 @@ def to_gpu(torch, a, dtype=np.float32):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
 
 
-def compare_state(torch, h, st, msgs=True, rows=None):
+def oracle_step(oracle, st, budget, grads, k, gamma, order="grad_first"):
+    """One oracle iteration (supplied gradients or a callable), charging the rounding budget."""
+    if order == "step_first":
+        budget.model_step(st.x.copy(), st.g)
+        oracle.model_step(st, gamma, True)
+    g_before = st.g.copy()
+    oracle.compress_update(st, grads(st.x) if callable(grads) else grads, k, True)
+    budget.compress_update(g_before, st.msg_idx, st.msg_val)
+    if order == "grad_first":
+        budget.model_step(st.x.copy(), st.g)
+        oracle.model_step(st, gamma, True)
+
+
+def compare_state(torch, h, st, budget, msgs=True, rows=None):
+    """g_i and the messages bit for bit; g and x within 1e-5 relative per coordinate plus the
+    rounding budget of fp32 arithmetic (see helpers.RoundingBudget)."""
     x, g_i, g = (t.cpu().numpy() for t in h.get_state())
     rows = range(h.n) if rows is None else rows
     for i in rows:
@@ -36,9 +51,9 @@ def compare_state(torch, h, st, msgs=True, rows=None):
         for i in rows:
             assert np.array_equal(idx[i], st.msg_idx[i]), f"message positions of worker {i} differ"
             assert same_bits(val[i], st.msg_val[i].astype(np.float32)), f"message values of worker {i} differ"
-    ok, info = close_per_coordinate(g, st.g)
+    ok, info = budget.check(g, st.g, "g")
     assert ok, f"g: max err, #bad = {info}"
-    ok, info = close_per_coordinate(x, st.x)
+    ok, info = budget.check(x, st.x, "x")
     assert ok, f"x: max err, #bad = {info}"
     return x, g_i, g
 
@@ -55,18 +70,20 @@ def test_single_step_from_oracle_state(gpu, oracle, n, d, k, order):
     g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
     gamma = 0.25
     st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    budget = RoundingBudget(n, d, gamma)
     with binding.EF21(n, d, k, gamma) as h:
         h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
         for t in range(3):
             grads = (g_i0 + 0.3 * rng.standard_normal((n, d))).astype(np.float32)
             if t == 1:     # exact zeros in the difference: ties at magnitude 0
                 grads[:, ::7] = st.g_i[:, ::7].astype(np.float32)
-            oracle.iteration(st, grads.astype(np.float64), k, gamma, order=order, storage_f32=True)
+            oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma, order)
             h.step(to_gpu(torch, grads), binding.ORDER_GRAD_FIRST if order == "grad_first" else binding.ORDER_STEP_FIRST)
             torch.cuda.synchronize()
-            x, g_i, g = compare_state(torch, h, st)
+            x, g_i, g = compare_state(torch, h, st, budget)
             # resynchronise g and x to the oracle's so the next step is again a single-step comparison
             h.set_state(to_gpu(torch, st.x), None, to_gpu(torch, st.g))
+            budget.reset()
 
 
 def test_first_pass_compresses_zero_vector(gpu, oracle):
@@ -182,16 +199,17 @@ def test_config4_scaled_run(gpu, oracle):
     torch, binding = gpu
     n, d, k, gamma = 8, 112_000, 1120, 0.01
     st = oracle.EF21State(np.zeros(d), np.zeros((n, d)), np.zeros(d))
+    budget = RoundingBudget(n, d, gamma)
     with binding.EF21(n, d, k, gamma) as h:
         for t in range(200):
             grads = workloads.student_t_grads(n, d, seed=1000 + t)
-            oracle.iteration(st, grads.astype(np.float64), k, gamma, storage_f32=True)
+            oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma)
             h.step(to_gpu(torch, grads))
             if t % 20 == 19 or t < 3:
                 torch.cuda.synchronize()
-                compare_state(torch, h, st)
+                compare_state(torch, h, st, budget)
         torch.cuda.synchronize()
-        compare_state(torch, h, st)
+        compare_state(torch, h, st, budget)
 
 
 @pytest.mark.timeout(600)
@@ -203,6 +221,7 @@ def test_config4_full_size_step(gpu, oracle):
     n, d, k, gamma = c["n"], c["d"], c["k"], c["gamma"]
     rows = [0, 3, 7]
     g_i_ref = np.zeros((n, d), dtype=np.float32)
+    budget, line6, g_prev = RoundingBudget(n, d, gamma), np.zeros(d), np.zeros(d)
     with binding.EF21(n, d, k, gamma) as h:
         for t in range(2):
             print(f"C4 full size step {t}", flush=True)
@@ -229,8 +248,13 @@ def test_config4_full_size_step(gpu, oracle):
                 dropped[idx[i]] = False
                 assert np.abs(v_all[i][dropped]).max() <= thr[i]
             g_i_ref = g_i
-            ok, info = close_per_coordinate(g, g_i.astype(np.float64).mean(axis=0), rel=1e-5)
-            assert ok, info
+            # invariant g = mean_i g_i up to the fp32 roundings made so far: those of line 8
+            # (budget.g) and those of line 6 (one per kept entry, relative to the new g_i)
+            budget.compress_update(g_prev, idx, val)
+            line6 += 2.0 ** -24 * np.abs(g_i).astype(np.float64).mean(axis=0)
+            mean = g_i.astype(np.float64).mean(axis=0)
+            assert np.all(np.abs(g - mean) <= 1e-5 * np.abs(mean) + budget.g + line6)
+            g_prev = g.astype(np.float64)
 
 
 def test_get_set_state_roundtrip_and_errors(gpu):

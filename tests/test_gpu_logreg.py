@@ -1,9 +1,10 @@
 """GPU parity of the local gradients (ef21_local_grad through the C ABI) against the CPU oracle:
-1e-5 relative per coordinate (fp32 kernels, fp64 oracle)."""
+1e-5 relative per coordinate (fp32 kernels, fp64 oracle) plus the first-order rounding floor of the
+fp32 sums (helpers.gradient_rounding_floor), which matters only where a coordinate cancels."""
 import numpy as np
 import pytest
 
-from helpers import close_per_coordinate
+from helpers import gradient_rounding_floor
 from paper_2106_05203_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -20,6 +21,24 @@ def gpu():
 
 def to_gpu(torch, a, dtype=np.float32):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
+
+
+def assert_grads_close(got, ref, A_dense, y, x, dot_depth, sum_depth, what):
+    """got, ref: [n][d]; A_dense: [n][m][d]."""
+    for i in range(ref.shape[0]):
+        bound = 1e-5 * np.abs(ref[i]) + gradient_rounding_floor(A_dense[i], y[i], x, dot_depth, sum_depth)
+        err = np.abs(got[i].astype(np.float64) - ref[i])
+        assert np.all(err <= bound), f"{what}, worker {i}: max err {err.max():.3e}, {int((err > bound).sum())} bad"
+        # the floor must stay a floor: tiny next to the gradient's scale
+        assert np.median(bound) <= 5e-5 * np.max(np.abs(ref[i])), f"{what}: tolerance too loose"
+
+
+def densify(W):
+    D = np.zeros((W.n * W.m, W.d), np.float32)
+    for r in range(W.n * W.m):
+        s, e = W.rowptr[r], W.rowptr[r + 1]
+        D[r, W.col[s:e]] = W.val[s:e]
+    return D.reshape(W.n, W.m, W.d)
 
 
 # d: vector path (d % 4 == 0) at each register tiling, scalar path, two-pass path for long rows
@@ -40,8 +59,7 @@ def test_dense_gradient(gpu, oracle, n, d, m):
             again = h.local_grad(to_gpu(torch, x))
             torch.cuda.synchronize()
             ref = P.grads(x.astype(np.float64))
-            ok, info = close_per_coordinate(got.cpu().numpy(), ref)
-            assert ok, f"scale {scale}: max err, #bad = {info}"
+            assert_grads_close(got.cpu().numpy(), ref, W.A, W.y, x, d / 64 + 8, 16, f"scale {scale}")
             assert torch.equal(got, again), "the dense gradient is bitwise reproducible"
         # x = NULL uses the handle's iterate
         h.set_state(to_gpu(torch, x), None, None)
@@ -54,6 +72,7 @@ def test_csr_gradient(gpu, oracle, n, d, m, nnz):
     print(f"csr grad case n={n} d={d} m={m} nnz/row={nnz}", flush=True)
     W = workloads.logreg_csr(n, d, m, nnz, seed=d + nnz)
     P = oracle.LogRegCSR(W.rowptr, W.col, W.val, W.y, n, m, d, 0.1)
+    D = densify(W)
     rng = np.random.default_rng(2)
     with binding.EF21(n, d, 1, 0.1) as h:
         h.set_problem_csr(to_gpu(torch, W.rowptr, np.int64), to_gpu(torch, W.col, np.int32), to_gpu(torch, W.val),
@@ -62,8 +81,8 @@ def test_csr_gradient(gpu, oracle, n, d, m, nnz):
             x = (rng.standard_normal(d) * scale).astype(np.float32)
             got = h.local_grad(to_gpu(torch, x))
             torch.cuda.synchronize()
-            ok, info = close_per_coordinate(got.cpu().numpy(), P.grads(x.astype(np.float64)))
-            assert ok, f"scale {scale}: max err, #bad = {info}"
+            assert_grads_close(got.cpu().numpy(), P.grads(x.astype(np.float64)), D, W.y, x, nnz / 64 + 8, 32,
+                               f"scale {scale}")
 
 
 def test_csr_ragged_rows(gpu, oracle):
@@ -84,5 +103,8 @@ def test_csr_ragged_rows(gpu, oracle):
                           to_gpu(torch, y), m, 0.1)
         got = h.local_grad(to_gpu(torch, x))
         torch.cuda.synchronize()
-    ok, info = close_per_coordinate(got.cpu().numpy(), P.grads(x.astype(np.float64)))
-    assert ok, info
+    D = np.zeros((n * m, d), np.float32)
+    for r in range(n * m):
+        D[r, col[rowptr[r]:rowptr[r + 1]]] = val[rowptr[r]:rowptr[r + 1]]
+    assert_grads_close(got.cpu().numpy(), P.grads(x.astype(np.float64)), D.reshape(n, m, d), y, x, 200 / 64 + 8, 64,
+                       "ragged")
