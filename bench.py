@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Throughput of the EF21 hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only C2]
+
+A step is one EF21 iteration (Algorithm 2: local gradients, Top-k of the difference, update of
+g_i and g, model step) over the synthetic workload.  The headline line is configuration C2
+(n = 20 workers, d = 2000, m = 5000 dense rows each, k = 20), the one that exercises every stage;
+the other configurations (C0, C1 Top-k alone, C3 CSR, C4 supplied gradients at network scale) are
+reported inside "workloads" of the same JSON line.  Inputs are resident in HBM before timing starts.
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def timed_loop(torch, fn, steps: int, warmup: int):
+    """warmup untimed calls, then exactly `steps` calls between synchronisations; (ms per step by the
+    host clock, ms per step by HIP events on the current stream)."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms / steps, e0.elapsed_time(e1) / steps
+
+
+def kernel_times(torch, h, fn, steps: int):
+    """Per-kernel-class average duration (ms per launch) from HIP events inside the library."""
+    h.set_timing(True)
+    for i in range(steps):
+        fn(i)
+    t = h.get_timing(reset=True)
+    h.set_timing(False)
+    return {name: ms / cnt for name, (ms, cnt) in t.items()}, {name: cnt / steps for name, (ms, cnt) in t.items()}
+
+
+def roofline(bytes_per_launch: float, ms: float, kernel: str, traffic=None) -> dict:
+    achieved = bytes_per_launch / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "algorithmic_bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(ms, 5)}
+
+
+def dev(torch, a, dtype=None):
+    import numpy as np
+    return torch.from_numpy(np.ascontiguousarray(a if dtype is None else a.astype(dtype))).cuda()
+
+
+# ------------------------------------------------------------------------------------------ workloads
+def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
+    import numpy as np
+    c = workloads.CONFIGS[name]
+    n, d, m, k = c["n"], c["d"], c["m"], c["k"]
+    log(f"{name}: generating dense logistic regression n={n} d={d} m={m}")
+    W = workloads.logreg_dense(n, d, m, seed=c["seed"])
+    A, y = dev(torch, W.A), dev(torch, W.y)
+    h = binding.EF21(n, d, k, c["gamma"])
+    h.set_problem_dense(A, y, c["lam"])
+    x0 = torch.zeros(d, device="cuda")
+    h.set_state(x0, h.local_grad(x0), None)          # g_i^0 = grad f_i(x^0)
+    wall, ev = timed_loop(torch, lambda i: h.step(), steps, warmup)
+    per_kernel, launches = kernel_times(torch, h, lambda i: h.step(), steps)
+    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", "ms_per_step": round(wall, 5),
+           "ms_per_step_events": round(ev, 5), "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()},
+           "iteration_algorithmic_bytes": 4 * n * m * d + 4 * n * m + 12 * n * d + 24 * n * k + 12 * d}
+    out["roofline"] = roofline(4.0 * n * m * d + 4.0 * n * m + 4.0 * d, per_kernel["grad_main"],
+                               "logreg_dense_fused_kernel (grad_main)")
+    out["iteration_frac_of_hbm_peak"] = round(out["iteration_algorithmic_bytes"] / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    return out, (W, h)
+
+
+def bench_topk(torch, binding, workloads, steps: int, warmup: int):
+    c = workloads.CONFIGS["C1"]
+    n, d = c["n"], c["d"]
+    log(f"C1: generating 4 x [{n}][{d}] Top-k inputs")
+    pool = [dev(torch, workloads.topk_rows(n, d, seed=s)) for s in range(4)]     # 320 MB > 256 MB cache
+    res = {}
+    for k in c["ks"]:
+        idx = torch.empty((n, k), dtype=torch.int32, device="cuda")
+        val = torch.empty((n, k), dtype=torch.float32, device="cuda")
+        wall, ev = timed_loop(torch, lambda i: binding.ef21_topk(pool[i % 4], k, idx, val), steps, warmup)
+        wall_hot, ev_hot = timed_loop(torch, lambda i: binding.ef21_topk(pool[0], k, idx, val), steps, warmup)
+        bytes_call = 4.0 * n * d + 8.0 * n * k
+        res[f"k={k}"] = {
+            "value": round(n * d / (ev * 1e-3), 1), "unit": "Top-k elements/s", "ms_per_call": round(ev, 5),
+            "ms_per_call_host_clock": round(wall, 5),
+            "call_frac_of_hbm_peak": round(bytes_call / (ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "same_buffer_every_call": {"value": round(n * d / (ev_hot * 1e-3), 1), "ms_per_call": round(ev_hot, 5)},
+        }
+    return res
+
+
+def bench_csr(torch, binding, workloads, steps: int, warmup: int):
+    import numpy as np
+    c = workloads.CONFIGS["C3"]
+    n, d, m, k, nnz = c["n"], c["d"], c["m"], c["k"], c["nnz_per_row"]
+    log(f"C3: generating CSR logistic regression n={n} d={d} m={m} nnz/row={nnz}")
+    W = workloads.logreg_csr(n, d, m, nnz, seed=c["seed"])
+    rp, col, val, y = dev(torch, W.rowptr), dev(torch, W.col), dev(torch, W.val), dev(torch, W.y)
+    h = binding.EF21(n, d, k, c["gamma"])
+    h.set_problem_csr(rp, col, val, y, m, c["lam"])
+    x0 = torch.zeros(d, device="cuda")
+    h.set_state(x0, h.local_grad(x0), None)
+    wall, ev = timed_loop(torch, lambda i: h.step(), steps, warmup)
+    per_kernel, _ = kernel_times(torch, h, lambda i: h.step(), steps)
+    total_nnz = n * m * nnz
+    it_bytes = 8 * total_nnz + 8 * (n * m + 1) + 4 * n * m + 12 * n * d + 24 * n * k + 12 * d
+    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", "ms_per_step": round(wall, 5),
+           "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()}, "iteration_algorithmic_bytes": it_bytes,
+           "iteration_frac_of_hbm_peak": round(it_bytes / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    out["roofline"] = roofline(8.0 * total_nnz + 8.0 * (n * m + 1) + 4.0 * n * m + 4.0 * n * d, per_kernel["grad_main"],
+                               "logreg_csr_kernel (grad_main)")
+    h.close()
+    return out
+
+
+def bench_grads(torch, binding, workloads, steps: int, warmup: int):
+    c = workloads.CONFIGS["C4"]
+    n, d, k = c["n"], c["d"], c["k"]
+    log(f"C4: generating Student-t gradients n={n} d={d}")
+    base = dev(torch, workloads.student_t_grads(n, d, seed=c["seed"]))
+    # four distinct gradient sets (1.4 GB in all): the host-drawn set, and copies of it rotated along
+    # the coordinate axis and across workers -- same distribution, different values at every position
+    pool = [base] + [torch.roll(base, shifts=(j, 1_000_003 * j), dims=(0, 1)).contiguous() for j in (1, 2, 3)]
+    h = binding.EF21(n, d, k, c["gamma"])
+    wall, ev = timed_loop(torch, lambda i: h.step(pool[i % 4]), steps, warmup)
+    per_kernel, launches = kernel_times(torch, h, lambda i: h.step(pool[i % 4]), steps)
+    it_bytes = 8 * n * d + 12 * d + 24 * n * k
+    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s (gradients supplied)", "ms_per_step": round(wall, 5),
+           "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()}, "iteration_algorithmic_bytes": it_bytes,
+           "iteration_frac_of_hbm_peak": round(it_bytes / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "topk_elements_per_s": round(n * d / (sum(v for k_, v in per_kernel.items() if k_.startswith("topk")) * 1e-3), 1)}
+    dom = "topk_collect" if "topk_collect" in per_kernel else "topk_row"
+    out["roofline"] = roofline(8.0 * n * d, per_kernel[dom], f"{dom} (reads grad and g_i once)")
+    h.close()
+    return out
+
+
+def cpu_baseline_dense(workloads, W, name: str, budget_s: float = 12.0):
+    """The oracle as it stands, single-threaded, on full-size inputs of the headline workload."""
+    import numpy as np
+    from oracle import ef21_oracle as oracle
+    c = workloads.CONFIGS[name]
+    P = oracle.LogRegDense(W.A, W.y, c["lam"])
+    x0 = np.zeros(P.d)
+    st = oracle.init_state(x0, P.grads(x0), c["k"], init="grad", storage_f32=True)
+    t0 = time.perf_counter()
+    its = 0
+    while True:
+        oracle.iteration(st, P.grads, c["k"], c["gamma"], storage_f32=True)
+        its += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or its >= c["iters"]:
+            break
+    return {"value": round(its / el, 4), "unit": "EF21 iterations/s", "cores": 1, "kind": "oracle",
+            "sample": f"{its} of the {c['iters']} iterations of {name} at full size ({el:.1f} s)"}
+
+
+def cpu_baseline_topk(workloads):
+    import numpy as np
+    from oracle import ef21_oracle as oracle
+    c = workloads.CONFIGS["C1"]
+    V = workloads.topk_rows(2, c["d"], seed=0).astype(np.float64)
+    t0 = time.perf_counter()
+    for row in V:
+        oracle.topk(row, 1000)
+    el = time.perf_counter() - t0
+    return {"value": round(2 * c["d"] / el, 1), "unit": "Top-k elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"2 of the 20 rows of C1 (d = {c['d']}), k = 1000 ({el:.1f} s)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--only", default="", help="comma list of C0,C1,C2,C3,C4 (C2, the headline, always runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (workers are rows of a batch; there are no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2106_05203_amd import binding, workloads
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    binding.load_library()
+    which = set(filter(None, args.only.split(","))) or {"C0", "C1", "C2", "C3", "C4"}
+    K, Wm = args.steps, args.warmup
+
+    head, (W2, h2) = bench_dense(torch, binding, workloads, "C2", K, Wm)
+    extra = {}
+    cpu = None
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on C2")
+        cpu = cpu_baseline_dense(workloads, W2, "C2")
+    h2.close()
+    del W2
+    if "C0" in which:
+        extra["C0"], (_, h0) = bench_dense(torch, binding, workloads, "C0", K, Wm)
+        h0.close()
+    if "C1" in which:
+        extra["C1"] = bench_topk(torch, binding, workloads, K, Wm)
+        if not args.no_cpu_baseline:
+            extra["C1"]["cpu_baseline"] = cpu_baseline_topk(workloads)
+    if "C3" in which:
+        extra["C3"] = bench_csr(torch, binding, workloads, K, Wm)
+    if "C4" in which:
+        extra["C4"] = bench_grads(torch, binding, workloads, K, Wm)
+
+    c2 = workloads.CONFIGS["C2"]
+    line = {
+        "metric": "EF21 iterations/s (whole iteration: local gradients, Top-k, state update, aggregation, model step)",
+        "value": head["value"], "unit": "iterations/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"C2: EF21, logistic regression + nonconvex regulariser, n={c2['n']} workers, "
+                               f"d={c2['d']}, m={c2['m']} dense fp32 rows per worker, Top-k k={c2['k']}, "
+                               f"gamma={c2['gamma']}, lambda={c2['lam']}", "n": c2["n"], "d": c2["d"], "m": c2["m"],
+                   "k": c2["k"]},
+        "roofline": head["roofline"],
+        "cpu_baseline": cpu,
+        "kernel_ms": head["kernel_ms"],
+        "iteration_frac_of_hbm_peak": head["iteration_frac_of_hbm_peak"],
+        "workloads": extra,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

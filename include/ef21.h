@@ -132,6 +132,21 @@ int ef21_local_grad(ef21_handle h, const float *x, float *out_grad);
  */
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags);
 
+/*
+ * Per-kernel timing, for measurement only (not part of the paper's method).  While enabled,
+ * ef21_step and ef21_local_grad record one HIP event on the handle's stream after each kernel
+ * they launch; the time between consecutive events is charged to the class of the later kernel.
+ * ef21_set_timing and ef21_get_timing wait for the stream.  ms[EF21_K_COUNT] receives the
+ * accumulated milliseconds per class and launches[EF21_K_COUNT] the number of intervals (either
+ * may be NULL); reset != 0 clears the sums.  Classes, in order (names from ef21_kernel_name):
+ * grad_main, grad_aux, topk_row, topk_hist, topk_collect, topk_refine, topk_count, topk_emit,
+ * model_step.
+ */
+enum { EF21_K_COUNT = 9 };
+int ef21_set_timing(ef21_handle h, int enabled);
+int ef21_get_timing(ef21_handle h, double *ms, int64_t *launches, int reset);
+const char *ef21_kernel_name(int kernel_class);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,8 +21,9 @@ ORDER_GRAD_FIRST, ORDER_STEP_FIRST = 0, 1
 SYMBOLS = (
     "ef21_last_error", "ef21_create", "ef21_destroy", "ef21_set_stream", "ef21_topk",
     "ef21_set_problem_dense", "ef21_set_problem_csr", "ef21_set_state", "ef21_get_state",
-    "ef21_get_messages", "ef21_local_grad", "ef21_step",
+    "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
 )
+K_COUNT = 9
 
 
 class EF21Error(RuntimeError):
@@ -59,8 +60,12 @@ def load_library() -> C.CDLL:
     lib.ef21_get_messages.argtypes = [p, p, p]
     lib.ef21_local_grad.argtypes = [p, p, p]
     lib.ef21_step.argtypes = [p, p, u32]
+    lib.ef21_set_timing.argtypes = [p, C.c_int]
+    lib.ef21_get_timing.argtypes = [p, p, p, C.c_int]
+    lib.ef21_kernel_name.argtypes = [C.c_int]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = C.c_int
+    lib.ef21_kernel_name.restype = C.c_char_p
     _lib = lib
     return lib
 
@@ -190,6 +195,19 @@ class EF21:
         with torch.cuda.device(self.device):
             _check(self._lib.ef21_get_messages(self._h, idx.data_ptr(), val.data_ptr()))
         return idx, val
+
+    # -- measurement
+    def set_timing(self, enabled: bool) -> None:
+        with torch.cuda.device(self.device):
+            _check(self._lib.ef21_set_timing(self._h, int(bool(enabled))))
+
+    def get_timing(self, reset: bool = True) -> dict:
+        """{kernel class: (milliseconds, launches)} accumulated while timing was enabled."""
+        ms = (C.c_double * K_COUNT)()
+        cnt = (C.c_int64 * K_COUNT)()
+        with torch.cuda.device(self.device):
+            _check(self._lib.ef21_get_timing(self._h, C.addressof(ms), C.addressof(cnt), int(reset)))
+        return {self._lib.ef21_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(K_COUNT) if cnt[i]}
 
     # -- the hot path
     def local_grad(self, x: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:

@@ -4,6 +4,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "../../include/ef21.h"
 #include "kernels.h"
@@ -27,6 +28,8 @@ int fail_hip(hipError_t st, const char *what) {
         if (st__ != hipSuccess) return fail_hip(st__, #call);    \
     } while (0)
 
+static_assert((int)ef21::K_COUNT == (int)EF21_K_COUNT, "kernel classes of kernels.h and ef21.h must agree");
+
 enum ProblemKind { kNone = 0, kDense = 1, kCSR = 2 };
 
 // Rows at least this long are selected with many workgroups per row.
@@ -39,10 +42,26 @@ struct SharedWorkspace {
     std::mutex mu;
     void *ptr[64] = {};
     size_t bytes[64] = {};
+    int32_t last_n[64] = {};      // shape of the last call: the layout inside the workspace depends on it
+    int64_t last_d[64] = {};
 };
 SharedWorkspace g_topk_ws;
 
 }  // namespace
+
+// Optional per-kernel timing of a handle: one HIP event after every kernel launch of ef21_step /
+// ef21_local_grad; the time between consecutive events is charged to the later kernel's class.
+struct Timing {
+    struct Rec {
+        int kernel;          // -1 marks the start of a call
+        hipEvent_t ev;
+    };
+    bool on = false;
+    std::vector<hipEvent_t> pool;
+    std::vector<Rec> recs;
+    double ms[ef21::K_COUNT] = {};
+    int64_t launches[ef21::K_COUNT] = {};
+};
 
 struct ef21_ctx {
     int32_t n = 0;
@@ -66,6 +85,7 @@ struct ef21_ctx {
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
     void *topk_ws = nullptr;
+    Timing timing;
 };
 
 namespace {
@@ -85,8 +105,53 @@ int check_topk_sizes(int32_t n, int64_t d, int64_t k) {
     return EF21_OK;
 }
 
+void record_mark(void *user, int kernel_id) {
+    ef21_ctx *c = (ef21_ctx *)user;
+    Timing &t = c->timing;
+    if (!t.on) return;
+    hipEvent_t ev = nullptr;
+    if (!t.pool.empty()) {
+        ev = t.pool.back();
+        t.pool.pop_back();
+    } else if (hipEventCreate(&ev) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+    }
+    (void)hipEventRecord(ev, c->stream);
+    t.recs.push_back({kernel_id, ev});
+}
+
+ef21::Marker marker_of(ef21_ctx *c) {
+    ef21::Marker m;
+    if (c->timing.on) {
+        m.fn = record_mark;
+        m.user = c;
+    }
+    return m;
+}
+
+// Folds the recorded events into the per-class sums.  The stream must be idle.
+void drain_timing(ef21_ctx *c) {
+    Timing &t = c->timing;
+    for (size_t i = 0; i < t.recs.size(); ++i) {
+        if (i > 0 && t.recs[i].kernel >= 0) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, t.recs[i - 1].ev, t.recs[i].ev) == hipSuccess) {
+                t.ms[t.recs[i].kernel] += ms;
+                t.launches[t.recs[i].kernel] += 1;
+            } else {
+                (void)hipGetLastError();
+            }
+        }
+    }
+    for (auto &r : t.recs) t.pool.push_back(r.ev);
+    t.recs.clear();
+}
+
 void free_ctx(ef21_ctx *c) {
     if (!c) return;
+    for (auto &r : c->timing.recs) (void)hipEventDestroy(r.ev);
+    for (auto ev : c->timing.pool) (void)hipEventDestroy(ev);
     (void)hipFree(c->x);
     (void)hipFree(c->g);
     (void)hipFree(c->g_i);
@@ -117,20 +182,40 @@ int ensure_problem_buffers(ef21_ctx *c, size_t scratch_bytes) {
 
 int enqueue_local_grad(ef21_ctx *c, const float *x, float *out) {
     hipError_t st;
+    const ef21::Marker mk = marker_of(c);
     if (c->kind == kDense)
-        st = ef21::launch_logreg_grad_dense(c->A, c->y, x, out, c->n, c->m, c->d, c->lambda, c->scratch, c->stream);
+        st = ef21::launch_logreg_grad_dense(c->A, c->y, x, out, c->n, c->m, c->d, c->lambda, c->scratch, c->stream,
+                                            mk);
     else
         st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->lambda,
-                                          c->stream);
+                                          c->stream, mk);
     if (st != hipSuccess) return fail_hip(st, "gradient kernel launch");
     return EF21_OK;
 }
 
-int enqueue_topk(const ef21::TopkArgs &p, void *workspace, hipStream_t stream) {
-    hipError_t st = (use_split(p.d) && workspace) ? ef21::launch_topk_split(p, workspace, stream)
-                                                  : ef21::launch_topk_row(p, stream);
+int enqueue_topk(const ef21::TopkArgs &p, void *workspace, hipStream_t stream, const ef21::Marker &mk) {
+    hipError_t st;
+    if (use_split(p.d) && workspace) {
+        st = ef21::launch_topk_split(p, workspace, stream, mk);
+    } else {
+        st = ef21::launch_topk_row(p, stream);
+        mk(ef21::K_TOPK_ROW);
+    }
     if (st != hipSuccess) return fail_hip(st, "Top-k kernel launch");
     return EF21_OK;
+}
+
+// The long-row workspace of a handle keeps one layout for life: zero its control part once.
+hipError_t alloc_split_workspace(void **ptr, size_t bytes, int32_t n, int64_t d) {
+    hipError_t st = hipMalloc(ptr, bytes);
+    if (st != hipSuccess) return st;
+    st = ef21::launch_topk_split_reset(*ptr, n, d, nullptr);
+    if (st == hipSuccess) st = hipDeviceSynchronize();
+    if (st != hipSuccess) {
+        (void)hipFree(*ptr);
+        *ptr = nullptr;
+    }
+    return st;
 }
 
 }  // namespace
@@ -165,7 +250,8 @@ ef21_handle ef21_create(int32_t n, int64_t d, int64_t k, float gamma) {
               hipMalloc((void **)&c->g_i, sizeof(float) * nd) == hipSuccess &&
               hipMalloc((void **)&c->msg_idx, sizeof(int32_t) * nk) == hipSuccess &&
               hipMalloc((void **)&c->msg_val, sizeof(float) * nk) == hipSuccess;
-    if (ok && use_split(d)) ok = hipMalloc(&c->topk_ws, ef21::topk_split_workspace_bytes(n, d, k)) == hipSuccess;
+    if (ok && use_split(d))
+        ok = alloc_split_workspace(&c->topk_ws, ef21::topk_split_workspace_bytes(n, d, k), n, d) == hipSuccess;
     if (ok)
         ok = hipMemset(c->x, 0, sizeof(float) * d) == hipSuccess && hipMemset(c->g, 0, sizeof(float) * d) == hipSuccess &&
              hipMemset(c->g_i, 0, sizeof(float) * nd) == hipSuccess &&
@@ -216,11 +302,18 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
                 return fail(EF21_ENOMEM, "hipMalloc of the Top-k workspace failed");
             }
             g_topk_ws.bytes[dev] = need;
+            g_topk_ws.last_n[dev] = 0;
         }
         ws = g_topk_ws.ptr[dev];
+        if (g_topk_ws.last_n[dev] != n || g_topk_ws.last_d[dev] != d) {
+            hipError_t st = ef21::launch_topk_split_reset(ws, n, d, stream);
+            if (st != hipSuccess) return fail_hip(st, "workspace reset launch");
+            g_topk_ws.last_n[dev] = n;
+            g_topk_ws.last_d[dev] = d;
+        }
     }
     ef21::TopkArgs p{rows, nullptr, n, d, k, out_idx, out_val, nullptr, nullptr, 0.f};
-    return enqueue_topk(p, ws, stream);
+    return enqueue_topk(p, ws, stream, ef21::Marker());
 }
 
 int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_t m, float lambda) {
@@ -289,6 +382,7 @@ int ef21_local_grad(ef21_handle h, const float *x, float *out_grad) {
     if (int rc = check_handle(h)) return rc;
     if (!out_grad) return fail(EF21_EINVAL, "out_grad must not be NULL");
     if (h->kind == kNone) return fail(EF21_ESTATE, "no problem attached (ef21_set_problem_dense / _csr)");
+    record_mark(h, -1);
     return enqueue_local_grad(h, x ? x : h->x, out_grad);
 }
 
@@ -298,8 +392,11 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
     if (!grads && h->kind == kNone)
         return fail(EF21_ESTATE, "grads is NULL and no problem is attached to compute them from");
     const bool step_first = flags == EF21_ORDER_STEP_FIRST;
+    const ef21::Marker mk = marker_of(h);
+    mk(-1);
     if (step_first) {   // Algorithm 2, line 3
         hipError_t st = ef21::launch_model_step(h->x, h->g, h->d, h->gamma, h->stream);
+        mk(ef21::K_MODEL_STEP);
         if (st != hipSuccess) return fail_hip(st, "model step launch");
     }
     if (!grads) {
@@ -308,12 +405,42 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
     }
     // lines 5, 6, 8: Top-k of grads - g_i, fused with the update of g_i and g
     ef21::TopkArgs p{grads, h->g_i, h->n, h->d, h->k, h->msg_idx, h->msg_val, h->g_i, h->g, 1.0f / (float)h->n};
-    if (int rc = enqueue_topk(p, h->topk_ws, h->stream)) return rc;
+    if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk)) return rc;
     if (!step_first) {
         hipError_t st = ef21::launch_model_step(h->x, h->g, h->d, h->gamma, h->stream);
+        mk(ef21::K_MODEL_STEP);
         if (st != hipSuccess) return fail_hip(st, "model step launch");
     }
     return EF21_OK;
+}
+
+int ef21_set_timing(ef21_handle h, int enabled) {
+    if (int rc = check_handle(h)) return rc;
+    EF21_HIP(hipStreamSynchronize(h->stream));
+    drain_timing(h);
+    h->timing.on = enabled != 0;
+    return EF21_OK;
+}
+
+int ef21_get_timing(ef21_handle h, double *ms, int64_t *launches, int reset) {
+    if (int rc = check_handle(h)) return rc;
+    EF21_HIP(hipStreamSynchronize(h->stream));
+    drain_timing(h);
+    for (int i = 0; i < EF21_K_COUNT; ++i) {
+        if (ms) ms[i] = h->timing.ms[i];
+        if (launches) launches[i] = h->timing.launches[i];
+        if (reset) {
+            h->timing.ms[i] = 0.0;
+            h->timing.launches[i] = 0;
+        }
+    }
+    return EF21_OK;
+}
+
+const char *ef21_kernel_name(int kernel_class) {
+    static const char *names[EF21_K_COUNT] = {"grad_main", "grad_aux",   "topk_row",  "topk_hist", "topk_collect",
+                                              "topk_refine", "topk_count", "topk_emit", "model_step"};
+    return (kernel_class >= 0 && kernel_class < EF21_K_COUNT) ? names[kernel_class] : "";
 }
 
 }  // extern "C"

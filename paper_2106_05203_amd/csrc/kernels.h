@@ -6,6 +6,30 @@
 
 namespace ef21 {
 
+// Kernel classes for the optional per-kernel timing of a handle (EF21_K_* in include/ef21.h).
+enum KernelId {
+    K_GRAD_MAIN = 0,   // the pass(es) over the problem data
+    K_GRAD_AUX,        // partial-sum reduction / regulariser
+    K_TOPK_ROW,        // one-workgroup-per-row Top-k (+ fused update)
+    K_TOPK_HIST,       // long rows: first-digit histogram
+    K_TOPK_COLLECT,    // long rows: candidate collection
+    K_TOPK_REFINE,     // long rows: threshold refinement on candidates
+    K_TOPK_COUNT,      // long rows: per-slot counts and offsets
+    K_TOPK_EMIT,       // long rows: ordered emission (+ fused update)
+    K_MODEL_STEP,      // x <- x - gamma g
+    K_COUNT
+};
+
+// Called after each kernel launch with the class of the kernel just enqueued; a default-constructed
+// Marker does nothing.
+struct Marker {
+    void (*fn)(void *user, int kernel_id) = nullptr;
+    void *user = nullptr;
+    void operator()(int kernel_id) const {
+        if (fn) fn(user, kernel_id);
+    }
+};
+
 // Arguments of one batched Top-k (Section 2.1) over n rows of length d.
 //   a, b      v = a - b if b != nullptr (the difference of Algorithm 2, line 5), else v = a
 //   out_idx, out_val   [n][k] ascending positions and signed values
@@ -31,7 +55,10 @@ hipError_t launch_topk_row(const TopkArgs &p, hipStream_t stream);
 
 // Many workgroups per row for long rows.  Workspace layout and size: topk_split_workspace_bytes.
 size_t topk_split_workspace_bytes(int32_t n, int64_t d, int64_t k);
-hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t stream);
+hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t stream, const Marker &mk = Marker());
+// The kernels keep the workspace's histograms and tickets zeroed as long as (n, d) stay the same.
+// A workspace that is new, or was last used with another (n, d), needs this reset first.
+hipError_t launch_topk_split_reset(void *workspace, int32_t n, int64_t d, hipStream_t stream);
 
 // Algorithm 2, line 3: x <- x - gamma g.
 hipError_t launch_model_step(float *x, const float *g, int64_t d, float gamma, hipStream_t stream);
@@ -42,11 +69,12 @@ hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hi
 // Gradient of eq. (9) for all workers, dense rows.  scratch: logreg_dense_scratch_bytes.
 size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d);
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
-                                    int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream);
+                                    int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
+                                    const Marker &mk = Marker());
 
 // Gradient of eq. (9) for all workers, CSR rows.
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, float lambda,
-                                  hipStream_t stream);
+                                  hipStream_t stream, const Marker &mk = Marker());
 
 }  // namespace ef21

@@ -205,7 +205,8 @@ size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d) {
 }
 
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
-                                    int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream) {
+                                    int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
+                                    const Marker &mk) {
     const DensePlan pl = dense_plan(n, m);
     float *part = (float *)scratch;
     float *resid = part + (size_t)n * pl.chunks * d;
@@ -230,25 +231,29 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
                            dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)pl.chunks, (unsigned)n),
                            dim3(kThreads), 0, stream, A, resid, part, m, d, pl.rows_per_wg);
     }
+    mk(K_GRAD_MAIN);
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;
     hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)n),
                        dim3(kThreads), 0, stream, part, x, grad, pl.chunks, m, d, lambda);
+    mk(K_GRAD_AUX);
     return hipGetLastError();
 }
 
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, float lambda,
-                                  hipStream_t stream) {
+                                  hipStream_t stream, const Marker &mk) {
     int64_t rb = (d + kThreads - 1) / kThreads;
     if (rb > 1024) rb = 1024;
     hipLaunchKernelGGL(logreg_csr_regulariser_kernel, dim3((unsigned)rb, (unsigned)n), dim3(kThreads), 0, stream, x,
                        grad, d, lambda);
+    mk(K_GRAD_AUX);
     const int64_t rows = (int64_t)n * m;
     int64_t blocks = (rows + kWaves - 1) / kWaves;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(logreg_csr_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, rowptr, col, val, y, x,
                        grad, rows, m, d, 1.0f / (float)m);
+    mk(K_GRAD_MAIN);
     return hipGetLastError();
 }
 
