@@ -138,18 +138,28 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_atr_kernel(const float 
     part[(worker * chunks + chunk) * d + c] = acc;
 }
 
-// grad[i][j] = (sum over row blocks, in block order) / m + regulariser gradient
+// grad[i][j] = (sum over row blocks, in a fixed order) / m + regulariser gradient.
+// A workgroup covers 64 columns; its four wavefronts each add every fourth row block (fp64), and
+// the four sums are combined in wavefront order.
 __global__ __launch_bounds__(kThreads) void logreg_dense_finish_kernel(const float *__restrict__ part,
                                                                        const float *__restrict__ x,
                                                                        float *__restrict__ grad, int64_t chunks,
                                                                        int64_t m, int64_t d, float lambda) {
+    __shared__ double red[kWaves][kWave];
     const int64_t worker = blockIdx.y;
-    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (c >= d) return;
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int64_t c = (int64_t)blockIdx.x * kWave + lane;
     double s = 0.0;
-    for (int64_t k = 0; k < chunks; ++k) s += (double)part[(worker * chunks + k) * d + c];
-    const double xj = (double)x[c], q = 1.0 + xj * xj;
-    grad[worker * d + c] = (float)(s / (double)m + 2.0 * (double)lambda * xj / (q * q));
+    if (c < d)
+        for (int64_t k = wave; k < chunks; k += kWaves) s += (double)part[(worker * chunks + k) * d + c];
+    red[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && c < d) {
+        double t = red[0][lane];
+        for (int w = 1; w < kWaves; ++w) t += red[w][lane];
+        const double xj = (double)x[c], q = 1.0 + xj * xj;
+        grad[worker * d + c] = (float)(t / (double)m + 2.0 * (double)lambda * xj / (q * q));
+    }
 }
 
 // ------------------------------------------------------------------ CSR
@@ -234,7 +244,7 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
     mk(K_GRAD_MAIN);
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;
-    hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)n),
+    hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kWave - 1) / kWave), (unsigned)n),
                        dim3(kThreads), 0, stream, part, x, grad, pl.chunks, m, d, lambda);
     mk(K_GRAD_AUX);
     return hipGetLastError();

@@ -1,0 +1,169 @@
+// One-workgroup-per-row radix select (Section 2.1 of the EF21 paper: keep the k entries of largest
+// magnitude), as device functions shared by the kernels that run it: the stand-alone row kernel
+// and the long-row path's per-row select / rescue kernels.  1024 threads per workgroup.
+//
+// The k largest magnitudes of a row are found on the 31-bit magnitude key (fp32 bits with the sign
+// cleared): three histogram passes (12 + 10 + 9 bits, LDS histograms) fix the key T of the k-th
+// largest magnitude and the number q of entries equal to T that are still needed; an ordered
+// emission then writes every entry with key > T and the first q entries with key == T, in
+// ascending position order (ties go to the lower index).
+#pragma once
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace ef21 {
+
+constexpr int kRowThreads = 1024;
+constexpr int kRowWaves = kRowThreads / kWave;
+constexpr int kBits1 = 12, kBits2 = 10, kBits3 = 9;   // 31 key bits
+static_assert(kBits1 + kBits2 + kBits3 == 31, "digits must cover the magnitude key");
+
+struct RowShared {
+    uint32_t hist[1 << kBits1];
+    uint32_t wave_a[kRowWaves];
+    uint32_t wave_b[kRowWaves];
+    uint32_t bin;     // selected digit
+    uint32_t need;    // entries still needed from inside the selected bin
+};
+
+template <bool DIFF>
+__device__ __forceinline__ float load_v(const float *a, const float *b, int64_t e) {
+    float v = a[e];
+    if (DIFF) v = v - b[e];
+    return v;
+}
+
+// Histogram of digit ((key >> shift) & (nbins-1)) over the entries whose key >> pshift == prefix.
+template <bool DIFF>
+__device__ void hist_pass(RowShared &s, const float *a, const float *b, int64_t d, int pshift, uint32_t prefix,
+                          int shift, int nbins) {
+    for (int i = threadIdx.x; i < nbins; i += kRowThreads) s.hist[i] = 0u;
+    __syncthreads();
+    const uint32_t mask = (uint32_t)nbins - 1u;
+    for (int64_t e = threadIdx.x; e < d; e += kRowThreads) {
+        const uint32_t key = mag_key(load_v<DIFF>(a, b, e));
+        if ((key >> pshift) == prefix) atomicAdd(&s.hist[(key >> shift) & mask], 1u);
+    }
+    __syncthreads();
+}
+
+// Largest bin b with  count(bins > b) < need <= count(bins >= b).  Leaves b in s.bin and
+// need - count(bins > b) in s.need.  Requires need <= total count.
+__device__ void select_bin(RowShared &s, int nbins, uint32_t need) {
+    const int tid = threadIdx.x;
+    const int per = nbins >= kRowThreads ? nbins / kRowThreads : 1;   // bins per thread, from the top
+    const int active = nbins / per;
+    uint32_t mine = 0u;
+    if (tid < active)
+        for (int j = 0; j < per; ++j) mine += s.hist[nbins - 1 - (tid * per + j)];
+    const uint32_t incl = wave_inclusive_scan(mine);
+    const int wave = tid / kWave;
+    if (lane_id() == kWave - 1) s.wave_a[wave] = incl;
+    __syncthreads();
+    uint32_t above = incl - mine;
+    for (int w = 0; w < wave; ++w) above += s.wave_a[w];
+    if (tid < active && above < need && need <= above + mine) {   // exactly one thread
+        uint32_t c = above;
+        for (int j = 0; j < per; ++j) {
+            const int bin = nbins - 1 - (tid * per + j);
+            const uint32_t h = s.hist[bin];
+            if (need <= c + h) {
+                s.bin = (uint32_t)bin;
+                s.need = need - c;
+                break;
+            }
+            c += h;
+        }
+    }
+    __syncthreads();
+}
+
+// Whole Top-k of one row by the calling workgroup (all kRowThreads threads must call).
+// With UPDATE the emission also applies lines 6 and 8 of Algorithm 2.
+template <bool DIFF, bool UPDATE>
+__device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
+    const int64_t d = p.d;
+    const float *a = p.a + row * d;
+    const float *b = DIFF ? p.b + row * d : nullptr;
+
+    // ---- threshold key T and tie quota q ------------------------------------------------
+    hist_pass<DIFF>(s, a, b, d, 31, 0u, kBits2 + kBits3, 1 << kBits1);
+    select_bin(s, 1 << kBits1, (uint32_t)p.k);
+    const uint32_t d1 = s.bin;
+    uint32_t need = s.need;
+    hist_pass<DIFF>(s, a, b, d, kBits2 + kBits3, d1, kBits3, 1 << kBits2);
+    select_bin(s, 1 << kBits2, need);
+    const uint32_t d12 = (d1 << kBits2) | s.bin;
+    need = s.need;
+    hist_pass<DIFF>(s, a, b, d, kBits3, d12, 0, 1 << kBits3);
+    select_bin(s, 1 << kBits3, need);
+    const uint32_t T = (d12 << kBits3) | s.bin;
+    const uint32_t q = s.need;   // 1 <= q <= number of entries with key == T
+
+    // ---- ordered emission: each wavefront owns a contiguous piece of the row -------------
+    const int wave = threadIdx.x / kWave;
+    const int lane = lane_id();
+    int64_t piece = (d + kRowWaves - 1) / kRowWaves;
+    piece = (piece + kWave - 1) / kWave * kWave;
+    const int64_t lo = wave * piece < d ? wave * piece : d;
+    const int64_t hi = lo + piece < d ? lo + piece : d;
+
+    uint32_t n_gt = 0u, n_eq = 0u;
+    for (int64_t base = lo; base < hi; base += kWave) {
+        const int64_t e = base + lane;
+        uint32_t key = 0u;
+        const bool in = e < hi;
+        if (in) key = mag_key(load_v<DIFF>(a, b, e));
+        n_gt += popc64(__ballot(in && key > T));
+        n_eq += popc64(__ballot(in && key == T));
+    }
+    if (lane == 0) {
+        s.wave_a[wave] = n_gt;
+        s.wave_b[wave] = n_eq;
+    }
+    __syncthreads();
+    uint32_t gt_before = 0u, eq_run = 0u;
+    for (int w = 0; w < wave; ++w) {
+        gt_before += s.wave_a[w];
+        eq_run += s.wave_b[w];
+    }
+    uint32_t out_run = gt_before + (eq_run < q ? eq_run : q);
+
+    int32_t *out_idx = p.out_idx + row * p.k;
+    float *out_val = p.out_val + row * p.k;
+    float *g_i = UPDATE ? p.g_i + row * d : nullptr;
+    for (int64_t base = lo; base < hi; base += kWave) {
+        const int64_t e = base + lane;
+        const bool in = e < hi;
+        float v = 0.f, bv = 0.f;
+        if (in) {
+            v = a[e];
+            if (DIFF) {
+                bv = b[e];
+                v = v - bv;
+            }
+        }
+        const uint32_t key = mag_key(v);
+        const bool gt = in && key > T;
+        const bool eq = in && key == T;
+        const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
+        const uint32_t eq_below = eq_run + lanes_below(m_eq);   // ties before this lane, whole row
+        const uint32_t ties_taken_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
+        const bool keep = gt || (eq && eq_below < q);
+        if (keep) {
+            const uint32_t pos = out_run + lanes_below(m_gt) + ties_taken_before;
+            out_idx[pos] = (int32_t)e;
+            out_val[pos] = v;
+            if (UPDATE) {
+                g_i[e] = bv + v;                       // Algorithm 2, line 6
+                atomicAdd(p.g + e, v * p.inv_n);       // Algorithm 2, line 8
+            }
+        }
+        const uint32_t eq_next = eq_run + popc64(m_eq);
+        out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
+        eq_run = eq_next;
+    }
+}
+
+
+}  // namespace ef21
