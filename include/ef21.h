@@ -139,7 +139,7 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags);
  * ef21_set_timing and ef21_get_timing wait for the stream.  ms[EF21_K_COUNT] receives the
  * accumulated milliseconds per class and launches[EF21_K_COUNT] the number of intervals (either
  * may be NULL); reset != 0 clears the sums.  Classes, in order (names from ef21_kernel_name):
- * grad_main, grad_aux, topk_row, topk_hist, topk_collect, topk_refine, topk_count, topk_emit,
+ * grad_main, grad_aux, topk_row, topk_collect, topk_select, topk_refine, topk_count, topk_emit,
  * model_step.
  */
 enum { EF21_K_COUNT = 9 };

@@ -438,7 +438,7 @@ int ef21_get_timing(ef21_handle h, double *ms, int64_t *launches, int reset) {
 }
 
 const char *ef21_kernel_name(int kernel_class) {
-    static const char *names[EF21_K_COUNT] = {"grad_main", "grad_aux",   "topk_row",  "topk_hist", "topk_collect",
+    static const char *names[EF21_K_COUNT] = {"grad_main",   "grad_aux",   "topk_row",  "topk_collect", "topk_select",
                                               "topk_refine", "topk_count", "topk_emit", "model_step"};
     return (kernel_class >= 0 && kernel_class < EF21_K_COUNT) ? names[kernel_class] : "";
 }

@@ -11,11 +11,11 @@ enum KernelId {
     K_GRAD_MAIN = 0,   // the pass(es) over the problem data
     K_GRAD_AUX,        // partial-sum reduction / regulariser
     K_TOPK_ROW,        // one-workgroup-per-row Top-k (+ fused update)
-    K_TOPK_HIST,       // long rows: first-digit histogram
-    K_TOPK_COLLECT,    // long rows: candidate collection
-    K_TOPK_REFINE,     // long rows: threshold refinement on candidates
-    K_TOPK_COUNT,      // long rows: per-slot counts and offsets
-    K_TOPK_EMIT,       // long rows: ordered emission (+ fused update)
+    K_TOPK_COLLECT,    // long rows: the pass over the row that collects candidates
+    K_TOPK_SELECT,     // long rows, small k: per-row select + emission on the candidates (+ fused update)
+    K_TOPK_REFINE,     // long rows, large k: one digit of the radix select on the candidates
+    K_TOPK_COUNT,      // long rows, large k: per-slot counts
+    K_TOPK_EMIT,       // long rows, large k: ordered emission (+ fused update)
     K_MODEL_STEP,      // x <- x - gamma g
     K_COUNT
 };
