@@ -4,7 +4,7 @@
 // Same selection rule as the one-workgroup kernel (31-bit magnitude key, ties to the lower index,
 // ascending output).  Pipeline:
 //
-//   collect   Every workgroup first looks at the same fixed sample of its row (64 evenly spaced
+//   collect   Every workgroup first looks at the same fixed sample of its row (32 evenly spaced
 //             pieces of 256 entries), finds in LDS a key `key_lo` that, with overwhelming
 //             probability, at least k entries of the row reach, and then streams its part of the
 //             row.  Each wavefront owns a contiguous piece of the row and appends the entries
@@ -30,14 +30,15 @@ namespace {
 
 constexpr int kBlk = kRowThreads;            // collect / select / rescue workgroups
 constexpr int kBlkWaves = kBlk / kWave;
-constexpr int kSample = 16384;               // sampled entries per row
+constexpr int kSample = 8192;                // sampled entries per row
 constexpr int kSamplePer = kSample / kBlk;
 constexpr int kPieceLen = 256, kPieces = kSample / kPieceLen;
 constexpr int kMaxSlots = 4096;              // slots (wavefront pieces) per row
 constexpr int kSelCap = 28672;               // candidate keys the select kernel holds in LDS
-constexpr int kCandThreads = 256;            // candidate-stage workgroups (large k)
+constexpr int kCandThreads = 256;            // count / emit workgroups (large k): one wavefront per slot
 constexpr int kCandWaves = kCandThreads / kWave;
-constexpr int kCandBlocks = 16;              // per row: 64 wavefronts, one slot each per round
+constexpr int kHistThreads = 512;            // candidate histogram workgroups (large k)
+constexpr int kCandBlocks = 16;              // ... of which each row gets this many
 constexpr int kBins1 = 1 << kBits1, kBins2 = 1 << kBits2, kBins3 = 1 << kBits3;
 
 struct RowInfo {
@@ -69,7 +70,7 @@ void plan(int32_t n, int64_t d, Ws *w) {
     if (g < 1) g = 1;
     const int64_t pieces = g * kBlkWaves;
     int64_t L = (d + pieces - 1) / pieces;
-    L = (L + 255) / 256 * 256;
+    L = (L + 1023) / 1024 * 1024;            // whole load groups (4 steps of 64 lanes x 4 entries)
     w->L = L;
     w->nslot = (d + L - 1) / L;
     w->G = (w->nslot + kBlkWaves - 1) / kBlkWaves;
@@ -158,37 +159,78 @@ __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b
     return key_lo;
 }
 
-// A wavefront walks its piece in steps of 64*VEC entries.  VEC = 4 needs 16-byte aligned rows.
-// Entry order inside a step: lane-major, then the VEC entries of the lane.
-template <int VEC, bool DIFF>
-struct Step {
-    float v[VEC];
-    __device__ __forceinline__ void load(const float *a, const float *b, int64_t e0, int64_t end) {
-        if constexpr (VEC == 4) {
-            if (e0 + 3 < end) {
-                const float4 t = *reinterpret_cast<const float4 *>(a + e0);
-                v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-                if constexpr (DIFF) {
-                    const float4 u = *reinterpret_cast<const float4 *>(b + e0);
-                    v[0] -= u.x; v[1] -= u.y; v[2] -= u.z; v[3] -= u.w;
-                }
-                return;
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < VEC; ++t) {
-            v[t] = 0.f;
-            if (e0 + t < end) {
-                v[t] = a[e0 + t];
-                if constexpr (DIFF) v[t] -= b[e0 + t];
-            }
-        }
-    }
+// Per-wavefront staging ring in LDS: candidates are appended here and leave for the slot in global
+// memory 64 at a time, as one full-width store per array, instead of as many scattered 4-byte stores.
+struct StageRing {
+    int32_t idx[128];
+    float val[128];
 };
 
+// Writes the entries [flushed, flushed + count) of the ring (count <= 64) to the slot.
+__device__ __forceinline__ void ring_to_slot(const StageRing &ring, uint32_t flushed, uint32_t count, int lane,
+                                             int32_t *slot_idx, float *slot_val) {
+    if ((uint32_t)lane < count) {
+        slot_idx[flushed + lane] = ring.idx[(flushed + lane) & 127u];
+        slot_val[flushed + lane] = ring.val[(flushed + lane) & 127u];
+    }
+}
+
+// Appends the candidates among one step's entries (VEC per lane, lane-major order) to the slot.
+// FULL: every entry of the step lies inside the piece, no bounds checks.
+// cnt = candidates so far, flushed = how many of them are already in global memory (cnt - flushed < 64
+// between calls; both are uniform over the wavefront).
+template <int VEC, bool FULL>
+__device__ __forceinline__ void append_candidates(const float (&v)[VEC], int64_t e0, int64_t hi, uint32_t key_lo,
+                                                  StageRing &ring, int lane, int32_t *slot_idx, float *slot_val,
+                                                  uint32_t &cnt, uint32_t &flushed) {
+    bool c[VEC];
+    uint32_t below = 0, all = 0;
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) {
+        c[t] = (FULL || e0 + t < hi) && mag_key(v[t]) >= key_lo;
+        const uint64_t m = __ballot(c[t]);
+        below += lanes_below(m);
+        all += popc64(m);
+    }
+    if (all == 0) return;
+    uint32_t pos = cnt + below;
+    if (all > 64) {        // a dense step would not fit the ring: drain it, then store directly
+        ring_to_slot(ring, flushed, cnt - flushed, lane, slot_idx, slot_val);
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) {
+            if (c[t]) {
+                slot_idx[pos] = (int32_t)(e0 + t);
+                slot_val[pos] = v[t];
+                ++pos;
+            }
+        }
+        cnt += all;
+        flushed = cnt;
+        return;
+    }
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) {
+        if (c[t]) {
+            ring.idx[pos & 127u] = (int32_t)(e0 + t);
+            ring.val[pos & 127u] = v[t];
+            ++pos;
+        }
+    }
+    cnt += all;
+    if (cnt - flushed >= 64) {
+        __builtin_amdgcn_wave_barrier();
+        ring_to_slot(ring, flushed, 64, lane, slot_idx, slot_val);
+        flushed += 64;
+    }
+}
+
+// A wavefront walks its piece in steps of 64*VEC entries (VEC = 4 needs 16-byte aligned rows), four
+// steps per group.  Whole groups are loaded without any bounds check so that all loads of a group
+// are in flight together; only the last piece of a row has a checked tail.
 template <int VEC, bool DIFF>
 __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
     __shared__ RowShared s;
+    __shared__ StageRing rings[kBlkWaves];
     const int64_t row = blockIdx.y, d = p.d;
     const float *a = p.a + row * d;
     const float *b = DIFF ? p.b + row * d : nullptr;
@@ -197,42 +239,54 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const int64_t slot = (int64_t)blockIdx.x * kBlkWaves + wave;
     if (slot >= w.nslot) return;
+    StageRing &ring = rings[wave];
     const int64_t lo = slot * w.L;
     const int64_t hi = lo + w.L < d ? lo + w.L : d;
     int32_t *slot_idx = w.cand_idx + (row * w.nslot + slot) * w.L;
     float *slot_val = w.cand_val + (row * w.nslot + slot) * w.L;
-    uint32_t cnt = 0;
-    constexpr int kStep = kWave * VEC, kUnroll = 4;
-    for (int64_t base = lo; base < hi; base += kStep * kUnroll) {
-        Step<VEC, DIFF> st[kUnroll];
+    uint32_t cnt = 0, flushed = 0;
+    constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
+    int64_t base = lo;
+    for (; base + kGroup <= hi; base += kGroup) {
+        float v[kUnroll][VEC];
+        if constexpr (VEC == 4) {
+            float4 va[kUnroll], vb[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) st[u].load(a, b, base + u * kStep + lane * VEC, hi);
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t e0 = base + u * kStep + lane * VEC;
-            bool c[VEC];
-            uint32_t below = 0, all = 0;
-#pragma unroll
-            for (int t = 0; t < VEC; ++t) {
-                c[t] = (e0 + t < hi) && mag_key(st[u].v[t]) >= key_lo;
-                const uint64_t m = __ballot(c[t]);
-                below += lanes_below(m);
-                all += popc64(m);
+            for (int u = 0; u < kUnroll; ++u) {
+                va[u] = *reinterpret_cast<const float4 *>(a + base + u * kStep + lane * 4);
+                if constexpr (DIFF) vb[u] = *reinterpret_cast<const float4 *>(b + base + u * kStep + lane * 4);
             }
-            if (all) {
-                uint32_t pos = cnt + below;
 #pragma unroll
-                for (int t = 0; t < VEC; ++t) {
-                    if (c[t]) {
-                        slot_idx[pos] = (int32_t)(e0 + t);
-                        slot_val[pos] = st[u].v[t];
-                        ++pos;
-                    }
+            for (int u = 0; u < kUnroll; ++u) {
+                v[u][0] = va[u].x; v[u][1] = va[u].y; v[u][2] = va[u].z; v[u][3] = va[u].w;
+                if constexpr (DIFF) {
+                    v[u][0] -= vb[u].x; v[u][1] -= vb[u].y; v[u][2] -= vb[u].z; v[u][3] -= vb[u].w;
                 }
-                cnt += all;
             }
+        } else {
+            float va[kUnroll], vb[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                va[u] = a[base + u * kStep + lane];
+                if constexpr (DIFF) vb[u] = b[base + u * kStep + lane];
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) v[u][0] = DIFF ? va[u] - vb[u] : va[u];
         }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            append_candidates<VEC, true>(v[u], base + u * kStep + lane * VEC, hi, key_lo, ring, lane, slot_idx,
+                                         slot_val, cnt, flushed);
     }
+    for (; base < hi; base += kStep) {           // checked tail, entry by entry
+        const int64_t e0 = base + lane * VEC;
+        float v[VEC];
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) v[t] = e0 + t < hi ? load_v<DIFF>(a, b, e0 + t) : 0.f;
+        append_candidates<VEC, false>(v, e0, hi, key_lo, ring, lane, slot_idx, slot_val, cnt, flushed);
+    }
+    __builtin_amdgcn_wave_barrier();
+    ring_to_slot(ring, flushed, cnt - flushed, lane, slot_idx, slot_val);
     if (lane == 0) w.slot_cnt[row * w.nslot + slot] = cnt;
 }
 
@@ -287,9 +341,22 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
     };
     const float *cand_val = w.cand_val + row * w.nslot * w.L;
     const int32_t *cand_idx = w.cand_idx + row * w.nslot * w.L;
-    for (uint32_t j = tid; j < M; j += kBlk) {
+    // flat position j -> address in the slots; kBatch independent loads in flight per thread
+    constexpr int kBatch = 8;
+    auto address_of = [&](uint32_t j) {
         const int sl = slot_of(j);
-        keys[j] = mag_key(cand_val[(int64_t)sl * w.L + (j - off[sl])]);
+        return (int64_t)sl * w.L + (int64_t)(j - off[sl]);
+    };
+    for (uint32_t j0 = tid; j0 < M; j0 += kBlk * kBatch) {
+        int64_t at[kBatch];
+        float v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) at[u] = j0 + u * kBlk < M ? address_of(j0 + u * kBlk) : -1;
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) v[u] = at[u] >= 0 ? cand_val[at[u]] : 0.f;
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            if (at[u] >= 0) keys[j0 + u * kBlk] = mag_key(v[u]);
     }
     __syncthreads();
 
@@ -338,8 +405,8 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
         eq_run += s.wave_b[v];
     }
     uint32_t out_run = gt_before + (eq_run < q ? eq_run : q);
-    int32_t *out_idx = p.out_idx + row * p.k;
-    float *out_val = p.out_val + row * p.k;
+    // first the output position of every kept candidate (LDS only; keys[j] is replaced by it) ...
+    constexpr uint32_t kDropped = 0xffffffffu;
     for (uint32_t base = lo; base < hi; base += kWave) {
         const uint32_t j = base + lane;
         const bool in = j < hi;
@@ -348,36 +415,57 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
         const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
         const uint32_t eq_below = eq_run + lanes_below(m_eq);
         const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
-        if (gt || (eq && eq_below < q)) {
-            const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
-            const int sl = slot_of(j);
-            const int64_t at = (int64_t)sl * w.L + (j - off[sl]);
-            const int32_t e = cand_idx[at];
-            const float v = cand_val[at];
-            out_idx[pos] = e;
-            out_val[pos] = v;
-            if (UPDATE) {
-                float *g_i = p.g_i + row * p.d;
-                g_i[e] = g_i[e] + v;                   // Algorithm 2, line 6 (g_i still holds its old value)
-                atomicAdd(p.g + e, v * p.inv_n);       // Algorithm 2, line 8
-            }
-        }
+        const bool keep = gt || (eq && eq_below < q);
+        if (in) keys[j] = keep ? out_run + lanes_below(m_gt) + ties_before : kDropped;
         const uint32_t eq_next = eq_run + popc64(m_eq);
         out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
         eq_run = eq_next;
+    }
+    __syncthreads();
+    // ... then the gather of (position, value) from the slots, kBatch loads in flight per thread
+    int32_t *out_idx = p.out_idx + row * p.k;
+    float *out_val = p.out_val + row * p.k;
+    for (uint32_t j0 = tid; j0 < M; j0 += kBlk * kBatch) {
+        int64_t at[kBatch];
+        uint32_t pos[kBatch];
+        int32_t e[kBatch];
+        float v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const uint32_t j = j0 + u * kBlk;
+            pos[u] = j < M ? keys[j] : kDropped;
+            at[u] = pos[u] != kDropped ? address_of(j) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            e[u] = at[u] >= 0 ? cand_idx[at[u]] : 0;
+            v[u] = at[u] >= 0 ? cand_val[at[u]] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (at[u] < 0) continue;
+            out_idx[pos[u]] = e[u];
+            out_val[pos[u]] = v[u];
+            if (UPDATE) {
+                float *g_i = p.g_i + row * p.d;
+                g_i[e[u]] = g_i[e[u]] + v[u];              // Algorithm 2, line 6 (g_i still holds its old value)
+                atomicAdd(p.g + e[u], v[u] * p.inv_n);     // Algorithm 2, line 8
+            }
+        }
     }
 }
 
 // ---------------------------------------------------------------- candidate stages (large k)
 // exclusive prefix sum over the workgroup's threads; total returned through *total
-__device__ uint32_t cand_block_scan(uint32_t v, uint32_t *lds_wave /*[kCandWaves]*/, uint32_t *total) {
+template <int THREADS>
+__device__ uint32_t cand_block_scan(uint32_t v, uint32_t *lds_wave /*[THREADS / 64]*/, uint32_t *total) {
     const uint32_t incl = wave_inclusive_scan(v);
     const int wave = threadIdx.x / kWave;
     __syncthreads();                       // lds_wave may still be in use by a previous scan
     if (lane_id() == kWave - 1) lds_wave[wave] = incl;
     __syncthreads();
     uint32_t before = 0, all = 0;
-    for (int v2 = 0; v2 < kCandWaves; ++v2) {
+    for (int v2 = 0; v2 < THREADS / kWave; ++v2) {
         const uint32_t t = lds_wave[v2];
         if (v2 < wave) before += t;
         all += t;
@@ -388,20 +476,21 @@ __device__ uint32_t cand_block_scan(uint32_t v, uint32_t *lds_wave /*[kCandWaves
 
 // Digit selection over the row's merged histogram (written by the previous kernel): largest bin b
 // with count(bins > b) < need <= count(bins >= b).  lds_out[0] = b, lds_out[1] = need - count(bins > b).
-template <int NBINS>
+template <int NBINS, int THREADS>
 __device__ void select_digit(const uint32_t *hist, uint32_t need, uint32_t *lds_wave, uint32_t *lds_out) {
-    constexpr int PER = NBINS / kCandThreads;      // bins per thread, walked from the top
-    static_assert(PER >= 1 && PER * kCandThreads == NBINS, "histogram size must be a multiple of the workgroup");
+    constexpr int PER = NBINS >= THREADS ? NBINS / THREADS : 1;      // bins per thread, walked from the top
+    static_assert(NBINS % PER == 0 && NBINS / PER <= THREADS, "histogram must divide over the workgroup");
+    const bool active = (int)threadIdx.x < NBINS / PER;
     uint32_t h[PER];
     uint32_t mine = 0;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        h[j] = hist[NBINS - 1 - ((int)threadIdx.x * PER + j)];
+        h[j] = active ? hist[NBINS - 1 - ((int)threadIdx.x * PER + j)] : 0u;
         mine += h[j];
     }
     uint32_t total;
-    const uint32_t above = cand_block_scan(mine, lds_wave, &total);
-    if (above < need && need <= above + mine) {
+    const uint32_t above = cand_block_scan<THREADS>(mine, lds_wave, &total);
+    if (active && above < need && need <= above + mine) {
         uint32_t c = above;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
@@ -415,32 +504,21 @@ __device__ void select_digit(const uint32_t *hist, uint32_t need, uint32_t *lds_
     __syncthreads();
 }
 
-template <int NBINS>
-__device__ void zero_lds_hist(uint32_t *hist) {
-    for (int i = threadIdx.x; i < NBINS; i += kCandThreads) hist[i] = 0u;
-    __syncthreads();
-}
-
-// Adds a workgroup's LDS histogram into the row's global one (non-empty bins only).
-template <int NBINS>
-__device__ void flush_hist(const uint32_t *lds_hist, uint32_t *global_hist) {
-    __syncthreads();
-    for (int b = threadIdx.x; b < NBINS; b += kCandThreads) {
-        const uint32_t c = lds_hist[b];
-        if (c) atomicAdd(global_hist + b, c);
-    }
-}
-
 __device__ void zero_global_hist(uint32_t *hist, int bins) {
-    for (int i = threadIdx.x; i < bins; i += kCandThreads) hist[i] = 0u;
+    for (int i = threadIdx.x; i < bins; i += blockDim.x) hist[i] = 0u;
 }
 
-// Digit STAGE (1, 2 or 3) of the radix select over the candidates.  Prologue: the result of the
-// previous stage from the merged histogram; body: histogram of this stage's digit.
+// Digit STAGE (1, 2 or 3) of the radix select over the candidates, kCandBlocks workgroups per row
+// (few, so that the merge below costs a few atomics per bin).  Prologue: the result of the previous
+// stage from the merged histogram.  Body: LDS histogram of this stage's digit over the workgroup's
+// slots, four slots in flight per wavefront, then merged into the row's global histogram.
 template <int STAGE>
-__global__ __launch_bounds__(kCandThreads) void cand_hist_kernel(TopkArgs p, Ws w) {
-    __shared__ uint32_t hist[STAGE == 1 ? kBins1 : (STAGE == 2 ? kBins2 : kBins3)];
-    __shared__ uint32_t lds_wave[kCandWaves], lds_out[2];
+__global__ __launch_bounds__(kHistThreads) void cand_hist_kernel(TopkArgs p, Ws w) {
+    constexpr int NB = STAGE == 1 ? kBins1 : (STAGE == 2 ? kBins2 : kBins3);
+    constexpr int SHIFT = STAGE == 1 ? kBits2 + kBits3 : (STAGE == 2 ? kBits3 : 0);
+    constexpr int PSHIFT = STAGE == 1 ? 31 : (STAGE == 2 ? kBits2 + kBits3 : kBits3);
+    __shared__ uint32_t hist[NB];
+    __shared__ uint32_t lds_wave[kHistThreads / kWave], lds_out[2];
     const int64_t row = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     RowInfo *info = w.info + row;
@@ -448,8 +526,8 @@ __global__ __launch_bounds__(kCandThreads) void cand_hist_kernel(TopkArgs p, Ws 
     uint32_t prefix = 0;    // digits known so far
     if constexpr (STAGE == 1) {
         uint32_t mine = 0, M;
-        for (int64_t sl = threadIdx.x; sl < w.nslot; sl += kCandThreads) mine += slot_cnt[sl];
-        (void)cand_block_scan(mine, lds_wave, &M);
+        for (int64_t sl = threadIdx.x; sl < w.nslot; sl += kHistThreads) mine += slot_cnt[sl];
+        (void)cand_block_scan<kHistThreads>(mine, lds_wave, &M);
         const bool failed = M < (uint32_t)p.k;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             info->failed = failed ? 1u : 0u;
@@ -459,14 +537,14 @@ __global__ __launch_bounds__(kCandThreads) void cand_hist_kernel(TopkArgs p, Ws 
     } else {
         if (info->failed) return;
         if constexpr (STAGE == 2) {
-            select_digit<kBins1>(w.hist1 + row * kBins1, (uint32_t)p.k, lds_wave, lds_out);
+            select_digit<kBins1, kHistThreads>(w.hist1 + row * kBins1, (uint32_t)p.k, lds_wave, lds_out);
             prefix = lds_out[0];
             if (blockIdx.x == 0 && threadIdx.x == 0) {
                 info->d1 = lds_out[0];
                 info->need1 = lds_out[1];
             }
         } else {
-            select_digit<kBins2>(w.hist2 + row * kBins2, info->need1, lds_wave, lds_out);
+            select_digit<kBins2, kHistThreads>(w.hist2 + row * kBins2, info->need1, lds_wave, lds_out);
             prefix = (info->d1 << kBits2) | lds_out[0];
             if (blockIdx.x == 0 && threadIdx.x == 0) {
                 info->p22 = prefix;
@@ -475,31 +553,48 @@ __global__ __launch_bounds__(kCandThreads) void cand_hist_kernel(TopkArgs p, Ws 
             if (blockIdx.x == 0) zero_global_hist(w.hist1 + row * kBins1, kBins1);   // consumed by stage 2
         }
     }
-    constexpr int NB = STAGE == 1 ? kBins1 : (STAGE == 2 ? kBins2 : kBins3);
-    constexpr int SHIFT = STAGE == 1 ? kBits2 + kBits3 : (STAGE == 2 ? kBits3 : 0);
-    constexpr int PSHIFT = STAGE == 1 ? 31 : (STAGE == 2 ? kBits2 + kBits3 : kBits3);
-    zero_lds_hist<NB>(hist);
-    for (int64_t sl = (int64_t)blockIdx.x * kCandWaves + wave; sl < w.nslot; sl += kCandBlocks * kCandWaves) {
-        const uint32_t cnt = slot_cnt[sl];
-        const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
-        for (uint32_t j = lane; j < cnt; j += kWave) {
-            const uint32_t key = mag_key(slot_val[j]);
-            if ((key >> PSHIFT) == prefix) atomicAdd(&hist[(key >> SHIFT) & (NB - 1)], 1u);
+    for (int i = threadIdx.x; i < NB; i += kHistThreads) hist[i] = 0u;
+    __syncthreads();
+    constexpr int kInFlight = 4;
+    const int64_t stride = (int64_t)kCandBlocks * (kHistThreads / kWave);
+    for (int64_t sl0 = (int64_t)blockIdx.x * (kHistThreads / kWave) + wave; sl0 < w.nslot; sl0 += stride * kInFlight) {
+        uint32_t cnt[kInFlight], most = 0;
+        const float *val[kInFlight];
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const int64_t sl = sl0 + u * stride;
+            cnt[u] = sl < w.nslot ? slot_cnt[sl] : 0u;
+            val[u] = w.cand_val + (row * w.nslot + (sl < w.nslot ? sl : 0)) * w.L;
+            most = cnt[u] > most ? cnt[u] : most;
+        }
+        for (uint32_t j = lane; j < most; j += kWave) {
+            float v[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) v[u] = j < cnt[u] ? val[u][j] : 0.f;
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const uint32_t key = mag_key(v[u]);
+                if (j < cnt[u] && (key >> PSHIFT) == prefix) atomicAdd(&hist[(key >> SHIFT) & (NB - 1)], 1u);
+            }
         }
     }
+    __syncthreads();
     uint32_t *merged = STAGE == 1 ? w.hist1 + row * kBins1 : (STAGE == 2 ? w.hist2 + row * kBins2 : w.hist3 + row * kBins3);
-    flush_hist<NB>(hist, merged);
+    for (int b = threadIdx.x; b < NB; b += kHistThreads) {
+        const uint32_t c = hist[b];
+        if (c) atomicAdd(merged + b, c);
+    }
 }
 
-// Prologue: threshold key T and tie quota q from the third digit's histogram.  Body: per slot, the
-// number of candidates above T and equal to T.
+// One wavefront per slot.  Prologue: threshold key T and tie quota q from the third digit's
+// histogram.  Body: the slot's number of candidates above T and equal to T.
 __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws w) {
     __shared__ uint32_t lds_wave[kCandWaves], lds_out[2];
     const int64_t row = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     RowInfo *info = w.info + row;
     if (info->failed) return;
-    select_digit<kBins3>(w.hist3 + row * kBins3, info->need2, lds_wave, lds_out);
+    select_digit<kBins3, kCandThreads>(w.hist3 + row * kBins3, info->need2, lds_wave, lds_out);
     const uint32_t T = (info->p22 << kBits3) | lds_out[0];
     if (blockIdx.x == 0) {
         if (threadIdx.x == 0) {
@@ -508,75 +603,74 @@ __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws
         }
         zero_global_hist(w.hist2 + row * kBins2, kBins2);     // consumed by stage 3
     }
-    for (int64_t sl = (int64_t)blockIdx.x * kCandWaves + wave; sl < w.nslot; sl += kCandBlocks * kCandWaves) {
-        const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
-        const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
-        uint32_t n_gt = 0, n_eq = 0;
-        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
-            const uint32_t j = j0 + lane;
-            const uint32_t key = j < cnt ? mag_key(slot_val[j]) : 0u;
-            n_gt += popc64(__ballot(j < cnt && key > T));
-            n_eq += popc64(__ballot(j < cnt && key == T));
-        }
-        if (lane == 0) {
-            w.slot_gt[row * w.nslot + sl] = n_gt;
-            w.slot_eq[row * w.nslot + sl] = n_eq;
-        }
+    const int64_t sl = (int64_t)blockIdx.x * kCandWaves + wave;
+    if (sl >= w.nslot) return;
+    const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
+    const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
+    uint32_t n_gt = 0, n_eq = 0;
+    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+        const uint32_t j = j0 + lane;
+        const uint32_t key = j < cnt ? mag_key(slot_val[j]) : 0u;
+        n_gt += popc64(__ballot(j < cnt && key > T));
+        n_eq += popc64(__ballot(j < cnt && key == T));
+    }
+    if (lane == 0) {
+        w.slot_gt[row * w.nslot + sl] = n_gt;
+        w.slot_eq[row * w.nslot + sl] = n_eq;
     }
     (void)p;
 }
 
-// Ordered emission.  A wavefront handles slots sl, sl + 64, sl + 128, ... and carries the number of
-// kept entries and of ties in all earlier slots along, 64 slot counts per round.
+// Ordered emission, one wavefront per slot.  The wavefront first adds up the counts of all earlier
+// slots of its row (at most kMaxSlots of them, 64 per load), which gives its output offset and the
+// number of ties already used.
 template <bool UPDATE>
 __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws w) {
-    static_assert(kCandBlocks * kCandWaves == kWave, "a wavefront advances by one lane-width of slots per round");
     const int64_t row = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const RowInfo *info = w.info + row;
     if (info->failed) return;
     if (blockIdx.x == 0) zero_global_hist(w.hist3 + row * kBins3, kBins3);       // consumed by count
+    const int64_t sl = (int64_t)blockIdx.x * kCandWaves + wave;
+    if (sl >= w.nslot) return;
     const uint32_t T = info->T, q = info->q;
     const uint32_t *slot_gt = w.slot_gt + row * w.nslot, *slot_eq = w.slot_eq + row * w.nslot;
-    const int64_t first = (int64_t)blockIdx.x * kCandWaves + wave;              // < 64
-    uint32_t gt_run = wave_sum_u32(lane < first && lane < w.nslot ? slot_gt[lane] : 0u);
-    uint32_t eq_run = wave_sum_u32(lane < first && lane < w.nslot ? slot_eq[lane] : 0u);
+    uint32_t gt_mine = 0, eq_mine = 0;
+    for (int64_t t = lane; t < sl; t += kWave) {
+        gt_mine += slot_gt[t];
+        eq_mine += slot_eq[t];
+    }
+    const uint32_t gt_run = wave_sum_u32(gt_mine);
+    uint32_t eq_run = wave_sum_u32(eq_mine);
+    uint32_t out_run = gt_run + (eq_run < q ? eq_run : q);
+    const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
+    const int32_t *slot_idx = w.cand_idx + (row * w.nslot + sl) * w.L;
+    const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
     int32_t *out_idx = p.out_idx + row * p.k;
     float *out_val = p.out_val + row * p.k;
-    for (int64_t sl = first; sl < w.nslot; sl += kWave) {
-        const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
-        const int32_t *slot_idx = w.cand_idx + (row * w.nslot + sl) * w.L;
-        const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
-        uint32_t out_run = gt_run + (eq_run < q ? eq_run : q);
-        uint32_t eq_in = eq_run;
-        for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
-            const uint32_t j = j0 + lane;
-            const bool in = j < cnt;
-            const float v = in ? slot_val[j] : 0.f;
-            const uint32_t key = mag_key(v);
-            const bool gt = in && key > T, eq = in && key == T;
-            const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
-            const uint32_t eq_below = eq_in + lanes_below(m_eq);
-            const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_in < q ? eq_in : q);
-            if (gt || (eq && eq_below < q)) {
-                const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
-                const int32_t e = slot_idx[j];
-                out_idx[pos] = e;
-                out_val[pos] = v;
-                if (UPDATE) {
-                    float *g_i = p.g_i + row * p.d;
-                    g_i[e] = g_i[e] + v;                   // Algorithm 2, line 6
-                    atomicAdd(p.g + e, v * p.inv_n);       // Algorithm 2, line 8
-                }
+    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
+        const uint32_t j = j0 + lane;
+        const bool in = j < cnt;
+        const float v = in ? slot_val[j] : 0.f;
+        const int32_t e = in ? slot_idx[j] : 0;
+        const uint32_t key = mag_key(v);
+        const bool gt = in && key > T, eq = in && key == T;
+        const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
+        const uint32_t eq_below = eq_run + lanes_below(m_eq);
+        const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
+        if (gt || (eq && eq_below < q)) {
+            const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
+            out_idx[pos] = e;
+            out_val[pos] = v;
+            if (UPDATE) {
+                float *g_i = p.g_i + row * p.d;
+                g_i[e] = g_i[e] + v;                   // Algorithm 2, line 6 (g_i still holds its old value)
+                atomicAdd(p.g + e, v * p.inv_n);       // Algorithm 2, line 8
             }
-            const uint32_t eq_next = eq_in + popc64(m_eq);
-            out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_in < q ? eq_in : q));
-            eq_in = eq_next;
         }
-        // advance the running counts over slots sl .. sl+63
-        const int64_t t = sl + lane;
-        gt_run += wave_sum_u32(t < w.nslot ? slot_gt[t] : 0u);
-        eq_run += wave_sum_u32(t < w.nslot ? slot_eq[t] : 0u);
+        const uint32_t eq_next = eq_run + popc64(m_eq);
+        out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
+        eq_run = eq_next;
     }
 }
 
@@ -657,13 +751,14 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
         mk(K_TOPK_SELECT);
         return st;
     }
-    const dim3 grid(kCandBlocks, (unsigned)p.n), block(kCandThreads);
-    hipLaunchKernelGGL(cand_hist_kernel<1>, grid, block, 0, stream, p, w);
+    const dim3 hgrid(kCandBlocks, (unsigned)p.n), hblock(kHistThreads);
+    hipLaunchKernelGGL(cand_hist_kernel<1>, hgrid, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
-    hipLaunchKernelGGL(cand_hist_kernel<2>, grid, block, 0, stream, p, w);
+    hipLaunchKernelGGL(cand_hist_kernel<2>, hgrid, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
-    hipLaunchKernelGGL(cand_hist_kernel<3>, grid, block, 0, stream, p, w);
+    hipLaunchKernelGGL(cand_hist_kernel<3>, hgrid, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
+    const dim3 grid((unsigned)((w.nslot + kCandWaves - 1) / kCandWaves), (unsigned)p.n), block(kCandThreads);
     hipLaunchKernelGGL(cand_count_kernel, grid, block, 0, stream, p, w);
     mk(K_TOPK_COUNT);
     if (upd) hipLaunchKernelGGL(cand_emit_kernel<true>, grid, block, 0, stream, p, w);
