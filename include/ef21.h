@@ -92,7 +92,11 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
  *   csr:    one CSR over all n*m rows, worker i owning rows i*m .. (i+1)*m-1:
  *           rowptr [n*m+1] int64, col [nnz] int32 in [0, d), val [nnz] fp32, y [n][m]
  * The arrays are BORROWED: they must stay valid and unchanged while the handle uses them.
- * Allocates a gradient buffer [n][d] and scratch on first use.
+ * Allocates a gradient buffer [n][d] and scratch on first use.  The csr call also reads rowptr
+ * and col once (it waits for the stream): if every row's columns are strictly ascending and
+ * inside [0, d) it builds a small per-row index of column ranges, which the fast two-pass
+ * gradient kernels need; otherwise a slower kernel based on global atomics is used, in which
+ * columns outside [0, d) are skipped.
  */
 int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_t m, float lambda);
 int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *col, const float *val,

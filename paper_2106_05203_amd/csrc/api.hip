@@ -85,6 +85,8 @@ struct ef21_ctx {
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
     void *topk_ws = nullptr;
+    void *csr_index = nullptr;      // column-range index of the attached CSR problem
+    bool csr_indexed = false;
     Timing timing;
 };
 
@@ -160,6 +162,7 @@ void free_ctx(ef21_ctx *c) {
     (void)hipFree(c->grad);
     (void)hipFree(c->scratch);
     (void)hipFree(c->topk_ws);
+    (void)hipFree(c->csr_index);
     delete c;
 }
 
@@ -188,7 +191,7 @@ int enqueue_local_grad(ef21_ctx *c, const float *x, float *out) {
                                             mk);
     else
         st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->lambda,
-                                          c->stream, mk);
+                                          c->csr_indexed ? c->csr_index : nullptr, c->stream, mk);
     if (st != hipSuccess) return fail_hip(st, "gradient kernel launch");
     return EF21_OK;
 }
@@ -337,6 +340,18 @@ int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *co
     if (m < 1 || m >= ((int64_t)1 << 31)) return fail(EF21_EINVAL, "m must be in [1, 2^31)");
     if (!(lambda >= 0.f) || !std::isfinite(lambda)) return fail(EF21_EINVAL, "lambda must be finite and >= 0");
     if (int rc = ensure_problem_buffers(h, 0)) return rc;
+    EF21_HIP(hipStreamSynchronize(h->stream));
+    (void)hipFree(h->csr_index);
+    h->csr_index = nullptr;
+    h->csr_indexed = false;
+    const size_t index_bytes = ef21::logreg_csr_index_bytes(h->n, m, h->d);
+    if (index_bytes) {
+        if (hipMalloc(&h->csr_index, index_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(EF21_ENOMEM, "hipMalloc of the CSR column-range index failed");
+        }
+        EF21_HIP(ef21::logreg_csr_build_index(rowptr, col, h->n, m, h->d, h->csr_index, h->stream, &h->csr_indexed));
+    }
     h->kind = kCSR;
     h->rowptr = rowptr;
     h->col = col;

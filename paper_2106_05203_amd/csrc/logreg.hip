@@ -8,8 +8,7 @@
 // of the row in registers between the dot product (wavefront reduction, no LDS) and the rank-one
 // accumulation r_l * a_l into per-lane accumulators.  Workgroups write partial sums that a small
 // second kernel adds in a fixed order (bitwise reproducible), together with the regulariser.
-// Dense rows, larger d: z = A x, then A^T r, two passes.  CSR rows: one wavefront per row,
-// gather x, scatter-add into the worker's gradient with fp32 atomics.
+// Dense rows, larger d: z = A x, then A^T r, two passes.  (CSR rows: logreg_csr.hip.)
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -162,44 +161,6 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_finish_kernel(const flo
     }
 }
 
-// ------------------------------------------------------------------ CSR
-__global__ __launch_bounds__(kThreads) void logreg_csr_regulariser_kernel(const float *__restrict__ x,
-                                                                          float *__restrict__ grad, int64_t d,
-                                                                          float lambda) {
-    const int64_t worker = blockIdx.y;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x; c < d; c += stride) {
-        const float xj = x[c], q = 1.0f + xj * xj;
-        grad[worker * d + c] = 2.0f * lambda * xj / (q * q);
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void logreg_csr_kernel(const int64_t *__restrict__ rowptr,
-                                                              const int32_t *__restrict__ col,
-                                                              const float *__restrict__ val,
-                                                              const float *__restrict__ y,
-                                                              const float *__restrict__ x, float *grad, int64_t rows,
-                                                              int64_t m, int64_t d, float inv_m) {
-    const int lane = lane_id();
-    const int64_t nwaves = (int64_t)gridDim.x * kWaves;
-    for (int64_t l = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; l < rows; l += nwaves) {
-        const int64_t p0 = rowptr[l], p1 = rowptr[l + 1];
-        float s = 0.f;
-        // a column index outside [0, d) is skipped rather than dereferenced
-        for (int64_t p = p0 + lane; p < p1; p += kWave) {
-            const uint32_t c = (uint32_t)col[p];
-            if (c < (uint64_t)d) s = fmaf(val[p], x[c], s);
-        }
-        s = wave_sum(s);
-        const float coef = residual(y[l], s) * inv_m;
-        float *g = grad + (l / m) * d;
-        for (int64_t p = p0 + lane; p < p1; p += kWave) {
-            const uint32_t c = (uint32_t)col[p];
-            if (c < (uint64_t)d) atomicAdd(g + c, coef * val[p]);
-        }
-    }
-}
-
 template <int VEC, int NQ>
 void launch_fused(const float *A, const float *y, const float *x, float *part, int32_t n, int64_t m, int64_t d,
                   const DensePlan &pl, hipStream_t stream) {
@@ -247,23 +208,6 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
     hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kWave - 1) / kWave), (unsigned)n),
                        dim3(kThreads), 0, stream, part, x, grad, pl.chunks, m, d, lambda);
     mk(K_GRAD_AUX);
-    return hipGetLastError();
-}
-
-hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
-                                  const float *x, float *grad, int32_t n, int64_t m, int64_t d, float lambda,
-                                  hipStream_t stream, const Marker &mk) {
-    int64_t rb = (d + kThreads - 1) / kThreads;
-    if (rb > 1024) rb = 1024;
-    hipLaunchKernelGGL(logreg_csr_regulariser_kernel, dim3((unsigned)rb, (unsigned)n), dim3(kThreads), 0, stream, x,
-                       grad, d, lambda);
-    mk(K_GRAD_AUX);
-    const int64_t rows = (int64_t)n * m;
-    int64_t blocks = (rows + kWaves - 1) / kWaves;
-    if (blocks > 16384) blocks = 16384;
-    hipLaunchKernelGGL(logreg_csr_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, rowptr, col, val, y, x,
-                       grad, rows, m, d, 1.0f / (float)m);
-    mk(K_GRAD_MAIN);
     return hipGetLastError();
 }
 

@@ -108,3 +108,26 @@ def test_csr_ragged_rows(gpu, oracle):
         D[r, col[rowptr[r]:rowptr[r + 1]]] = val[rowptr[r]:rowptr[r + 1]]
     assert_grads_close(got.cpu().numpy(), P.grads(x.astype(np.float64)), D.reshape(n, m, d), y, x, 200 / 64 + 8, 64,
                        "ragged")
+
+
+def test_csr_unsorted_columns(gpu, oracle):
+    """Columns in arbitrary order inside the rows: the library must notice and take its kernel that
+    does not rely on ascending columns; same gradients."""
+    torch, binding = gpu
+    n, d, m, nnz = 3, 20_000, 60, 90
+    W = workloads.logreg_csr(n, d, m, nnz, seed=12)
+    rng = np.random.default_rng(5)
+    col = W.col.reshape(n * m, nnz).copy()
+    val = W.val.reshape(n * m, nnz).copy()
+    for r in range(n * m):
+        perm = rng.permutation(nnz)
+        col[r], val[r] = col[r, perm], val[r, perm]
+    P = oracle.LogRegCSR(W.rowptr, W.col, W.val, W.y, n, m, d, 0.1)
+    x = rng.standard_normal(d).astype(np.float32)
+    with binding.EF21(n, d, 1, 0.1) as h:
+        h.set_problem_csr(to_gpu(torch, W.rowptr, np.int64), to_gpu(torch, col.reshape(-1), np.int32),
+                          to_gpu(torch, val.reshape(-1)), to_gpu(torch, W.y), m, 0.1)
+        got = h.local_grad(to_gpu(torch, x))
+        torch.cuda.synchronize()
+    assert_grads_close(got.cpu().numpy(), P.grads(x.astype(np.float64)), densify(W), W.y, x, nnz / 64 + 8, 64,
+                       "unsorted")
