@@ -33,7 +33,7 @@ static_assert((int)ef21::K_COUNT == (int)EF21_K_COUNT, "kernel classes of kernel
 enum ProblemKind { kNone = 0, kDense = 1, kCSR = 2 };
 
 // Rows at least this long are selected with many workgroups per row.
-constexpr int64_t kSplitMinRow = 1 << 16;
+constexpr int64_t kSplitMinRow = 1 << 14;
 
 bool use_split(int64_t d) { return d >= kSplitMinRow; }
 
