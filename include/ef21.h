@@ -131,8 +131,9 @@ int ef21_local_grad(ef21_handle h, const float *x, float *out_grad);
  *   flags: EF21_ORDER_GRAD_FIRST or EF21_ORDER_STEP_FIRST.  With supplied gradients and
  *   STEP_FIRST the caller must have evaluated them at x - gamma*g.
  * The difference in line 5 is one fp32 subtraction; line 6 is one fp32 addition per kept
- * entry; line 8 adds val/n per message with floating-point atomics (g is reproducible to
- * rounding, g_i and the messages bitwise); line 3 is one fused multiply-add per coordinate.
+ * entry; line 8 adds the messages per coordinate in worker order in fp32 and applies
+ * g + sum * (1/n) as one fused multiply-add; line 3 is one fused multiply-add per coordinate.
+ * With supplied gradients every result (messages, g_i, g, x) is bitwise reproducible.
  */
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags);
 

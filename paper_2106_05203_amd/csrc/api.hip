@@ -85,6 +85,7 @@ struct ef21_ctx {
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
     void *topk_ws = nullptr;
+    void *agg_index = nullptr;      // runs of the messages per coordinate sub-block (scratch of line 8)
     void *csr_index = nullptr;      // column-range index of the attached CSR problem
     bool csr_indexed = false;
     Timing timing;
@@ -163,6 +164,7 @@ void free_ctx(ef21_ctx *c) {
     (void)hipFree(c->scratch);
     (void)hipFree(c->topk_ws);
     (void)hipFree(c->csr_index);
+    (void)hipFree(c->agg_index);
     delete c;
 }
 
@@ -253,6 +255,7 @@ ef21_handle ef21_create(int32_t n, int64_t d, int64_t k, float gamma) {
               hipMalloc((void **)&c->g_i, sizeof(float) * nd) == hipSuccess &&
               hipMalloc((void **)&c->msg_idx, sizeof(int32_t) * nk) == hipSuccess &&
               hipMalloc((void **)&c->msg_val, sizeof(float) * nk) == hipSuccess;
+    if (ok) ok = hipMalloc(&c->agg_index, ef21::aggregate_index_bytes(n, d)) == hipSuccess;
     if (ok && use_split(d))
         ok = alloc_split_workspace(&c->topk_ws, ef21::topk_split_workspace_bytes(n, d, k), n, d) == hipSuccess;
     if (ok)
@@ -315,7 +318,7 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
             g_topk_ws.last_d[dev] = d;
         }
     }
-    ef21::TopkArgs p{rows, nullptr, n, d, k, out_idx, out_val, nullptr, nullptr, 0.f};
+    ef21::TopkArgs p{rows, nullptr, n, d, k, out_idx, out_val, nullptr};
     return enqueue_topk(p, ws, stream, ef21::Marker());
 }
 
@@ -418,14 +421,14 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
         if (int rc = enqueue_local_grad(h, h->x, h->grad)) return rc;
         grads = h->grad;
     }
-    // lines 5, 6, 8: Top-k of grads - g_i, fused with the update of g_i and g
-    ef21::TopkArgs p{grads, h->g_i, h->n, h->d, h->k, h->msg_idx, h->msg_val, h->g_i, h->g, 1.0f / (float)h->n};
+    // lines 5 and 6: Top-k of grads - g_i, fused with the update of g_i
+    ef21::TopkArgs p{grads, h->g_i, h->n, h->d, h->k, h->msg_idx, h->msg_val, h->g_i};
     if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk)) return rc;
-    if (!step_first) {
-        hipError_t st = ef21::launch_model_step(h->x, h->g, h->d, h->gamma, h->stream);
-        mk(ef21::K_MODEL_STEP);
-        if (st != hipSuccess) return fail_hip(st, "model step launch");
-    }
+    // line 8 from the messages, and (default order) line 3 in the same pass over the coordinates
+    hipError_t st = ef21::launch_aggregate(h->msg_idx, h->msg_val, h->n, h->k, h->d, h->g, step_first ? nullptr : h->x,
+                                           h->gamma, h->agg_index, h->stream);
+    mk(ef21::K_MODEL_STEP);
+    if (st != hipSuccess) return fail_hip(st, "aggregation launch");
     return EF21_OK;
 }
 

@@ -16,7 +16,7 @@ enum KernelId {
     K_TOPK_REFINE,     // long rows, large k: one digit of the radix select on the candidates
     K_TOPK_COUNT,      // long rows, large k: per-slot counts
     K_TOPK_EMIT,       // long rows, large k: ordered emission (+ fused update)
-    K_MODEL_STEP,      // x <- x - gamma g
+    K_MODEL_STEP,      // g <- g + mean of the messages and / or x <- x - gamma g
     K_COUNT
 };
 
@@ -33,8 +33,8 @@ struct Marker {
 // Arguments of one batched Top-k (Section 2.1) over n rows of length d.
 //   a, b      v = a - b if b != nullptr (the difference of Algorithm 2, line 5), else v = a
 //   out_idx, out_val   [n][k] ascending positions and signed values
-//   g_i, g    if g_i != nullptr the kept entries also update the EF21 state in place
-//             (lines 6 and 8 of Algorithm 2): g_i[row][j] = b[row][j] + v,  g[j] += v * inv_n
+//   g_i       if != nullptr (then b must be the same array) the kept entries also update the workers'
+//             estimators in place (Algorithm 2, line 6): g_i[row][j] = b[row][j] + v
 struct TopkArgs {
     const float *a;
     const float *b;
@@ -44,8 +44,6 @@ struct TopkArgs {
     int32_t *out_idx;
     float *out_val;
     float *g_i;
-    float *g;
-    float inv_n;
 };
 
 // One workgroup per row, four radix passes over the row plus an ordered emission.  Needs no
@@ -62,6 +60,14 @@ hipError_t launch_topk_split_reset(void *workspace, int32_t n, int64_t d, hipStr
 
 // Algorithm 2, line 3: x <- x - gamma g.
 hipError_t launch_model_step(float *x, const float *g, int64_t d, float gamma, hipStream_t stream);
+
+// Algorithm 2, line 8: g <- g + (1/n) sum_i c_i from the messages (idx, val) [n][k] (positions ascending
+// and distinct inside a row), summed in worker order, without atomics; if x != nullptr followed, in the
+// same pass over the coordinates, by line 3 with the new g.  `index`: aggregate_index_bytes(n, d) bytes
+// of scratch, overwritten by every call.
+size_t aggregate_index_bytes(int32_t n, int64_t d);
+hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int64_t k, int64_t d, float *g, float *x,
+                            float gamma, void *index, hipStream_t stream);
 
 // g = (1/n) sum_i g_i (input line of Algorithm 2), summed in worker order.
 hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hipStream_t stream);

@@ -5,7 +5,7 @@
 // fix the key T of the k-th largest magnitude and the number q of entries equal to T that are
 // still needed; an ordered emission then writes every entry with key > T and the first q
 // entries with key == T, in ascending position order (ties go to the lower index).
-// With `g_i != nullptr` the emission also applies lines 6 and 8 of Algorithm 2.
+// With `g_i != nullptr` the emission also applies line 6 of Algorithm 2.
 #include "topk_row_impl.h"
 
 namespace ef21 {

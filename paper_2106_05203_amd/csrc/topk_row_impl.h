@@ -79,7 +79,7 @@ __device__ void select_bin(RowShared &s, int nbins, uint32_t need) {
 }
 
 // Whole Top-k of one row by the calling workgroup (all kRowThreads threads must call).
-// With UPDATE the emission also applies lines 6 and 8 of Algorithm 2.
+// With UPDATE the emission also applies line 6 of Algorithm 2.
 template <bool DIFF, bool UPDATE>
 __device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
     const int64_t d = p.d;
@@ -154,10 +154,7 @@ __device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
             const uint32_t pos = out_run + lanes_below(m_gt) + ties_taken_before;
             out_idx[pos] = (int32_t)e;
             out_val[pos] = v;
-            if (UPDATE) {
-                g_i[e] = bv + v;                       // Algorithm 2, line 6
-                atomicAdd(p.g + e, v * p.inv_n);       // Algorithm 2, line 8
-            }
+            if (UPDATE) g_i[e] = bv + v;               // Algorithm 2, line 6
         }
         const uint32_t eq_next = eq_run + popc64(m_eq);
         out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));

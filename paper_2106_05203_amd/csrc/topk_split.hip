@@ -12,7 +12,7 @@
 //             its own slot of the workspace.  No atomics, no fences, no inter-workgroup traffic.
 //   then, on the candidates only, either
 //   select    (small k) one workgroup per row: candidate keys into LDS, radix select there, ordered
-//             emission of the k kept entries (+ lines 6 and 8 of Algorithm 2); or
+//             emission of the k kept entries (+ line 6 of Algorithm 2); or
 //   hist x3, count, emit, rescue   (large k) the same steps spread over 16 workgroups per row,
 //             chained by kernel boundaries: a kernel merges its LDS histograms into the row's
 //             global one with a few atomics per bin, the NEXT kernel's workgroups each scan the
@@ -54,6 +54,7 @@ struct Ws {
     uint32_t *slot_cnt, *slot_gt, *slot_eq;   // [n][nslot]
     int32_t *cand_idx;                    // [n][nslot][L]
     float *cand_val;
+    float *cand_new;                      // [n][nslot][L]  b + v of the candidate (new g_i entry if kept)
     int64_t L;                            // entries per wavefront piece = slot capacity
     int64_t nslot;                        // pieces per row
     int64_t G;                            // collect workgroups per row
@@ -93,12 +94,13 @@ size_t layout(int32_t n, int64_t d, char *base, Ws *w) {
     char *s0 = take(slots), *s1 = take(slots), *s2 = take(slots);
     char *ci = take(sizeof(int32_t) * (size_t)n * tmp.nslot * tmp.L);
     char *cv = take(sizeof(float) * (size_t)n * tmp.nslot * tmp.L);
+    char *cn = take(sizeof(float) * (size_t)n * tmp.nslot * tmp.L);
     if (w) {
         *w = tmp;
         w->hist1 = (uint32_t *)h1; w->hist2 = (uint32_t *)h2; w->hist3 = (uint32_t *)h3;
         w->info = (RowInfo *)inf;
         w->slot_cnt = (uint32_t *)s0; w->slot_gt = (uint32_t *)s1; w->slot_eq = (uint32_t *)s2;
-        w->cand_idx = (int32_t *)ci; w->cand_val = (float *)cv;
+        w->cand_idx = (int32_t *)ci; w->cand_val = (float *)cv; w->cand_new = (float *)cn;
     }
     return off;
 }
@@ -161,28 +163,38 @@ __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b
 
 // Per-wavefront staging ring in LDS: candidates are appended here and leave for the slot in global
 // memory 64 at a time, as one full-width store per array, instead of as many scattered 4-byte stores.
+// With UPDATE a candidate also carries b + v, the value g_i takes at its position if it is kept.
 struct StageRing {
     int32_t idx[128];
     float val[128];
+    float nxt[128];
+};
+
+struct SlotPtrs {
+    int32_t *idx;
+    float *val;
+    float *nxt;
 };
 
 // Writes the entries [flushed, flushed + count) of the ring (count <= 64) to the slot.
+template <bool UPDATE>
 __device__ __forceinline__ void ring_to_slot(const StageRing &ring, uint32_t flushed, uint32_t count, int lane,
-                                             int32_t *slot_idx, float *slot_val) {
+                                             const SlotPtrs &slot) {
     if ((uint32_t)lane < count) {
-        slot_idx[flushed + lane] = ring.idx[(flushed + lane) & 127u];
-        slot_val[flushed + lane] = ring.val[(flushed + lane) & 127u];
+        slot.idx[flushed + lane] = ring.idx[(flushed + lane) & 127u];
+        slot.val[flushed + lane] = ring.val[(flushed + lane) & 127u];
+        if (UPDATE) slot.nxt[flushed + lane] = ring.nxt[(flushed + lane) & 127u];
     }
 }
 
 // Appends the candidates among one step's entries (VEC per lane, lane-major order) to the slot.
-// FULL: every entry of the step lies inside the piece, no bounds checks.
+// FULL: every entry of the step lies inside the piece, no bounds checks.  bv: the subtracted values.
 // cnt = candidates so far, flushed = how many of them are already in global memory (cnt - flushed < 64
 // between calls; both are uniform over the wavefront).
-template <int VEC, bool FULL>
-__device__ __forceinline__ void append_candidates(const float (&v)[VEC], int64_t e0, int64_t hi, uint32_t key_lo,
-                                                  StageRing &ring, int lane, int32_t *slot_idx, float *slot_val,
-                                                  uint32_t &cnt, uint32_t &flushed) {
+template <int VEC, bool FULL, bool UPDATE>
+__device__ __forceinline__ void append_candidates(const float (&v)[VEC], const float (&bv)[VEC], int64_t e0,
+                                                  int64_t hi, uint32_t key_lo, StageRing &ring, int lane,
+                                                  const SlotPtrs &slot, uint32_t &cnt, uint32_t &flushed) {
     bool c[VEC];
     uint32_t below = 0, all = 0;
 #pragma unroll
@@ -195,12 +207,13 @@ __device__ __forceinline__ void append_candidates(const float (&v)[VEC], int64_t
     if (all == 0) return;
     uint32_t pos = cnt + below;
     if (all > 64) {        // a dense step would not fit the ring: drain it, then store directly
-        ring_to_slot(ring, flushed, cnt - flushed, lane, slot_idx, slot_val);
+        ring_to_slot<UPDATE>(ring, flushed, cnt - flushed, lane, slot);
 #pragma unroll
         for (int t = 0; t < VEC; ++t) {
             if (c[t]) {
-                slot_idx[pos] = (int32_t)(e0 + t);
-                slot_val[pos] = v[t];
+                slot.idx[pos] = (int32_t)(e0 + t);
+                slot.val[pos] = v[t];
+                if (UPDATE) slot.nxt[pos] = bv[t] + v[t];
                 ++pos;
             }
         }
@@ -213,13 +226,14 @@ __device__ __forceinline__ void append_candidates(const float (&v)[VEC], int64_t
         if (c[t]) {
             ring.idx[pos & 127u] = (int32_t)(e0 + t);
             ring.val[pos & 127u] = v[t];
+            if (UPDATE) ring.nxt[pos & 127u] = bv[t] + v[t];
             ++pos;
         }
     }
     cnt += all;
     if (cnt - flushed >= 64) {
         __builtin_amdgcn_wave_barrier();
-        ring_to_slot(ring, flushed, 64, lane, slot_idx, slot_val);
+        ring_to_slot<UPDATE>(ring, flushed, 64, lane, slot);
         flushed += 64;
     }
 }
@@ -227,8 +241,9 @@ __device__ __forceinline__ void append_candidates(const float (&v)[VEC], int64_t
 // A wavefront walks its piece in steps of 64*VEC entries (VEC = 4 needs 16-byte aligned rows), four
 // steps per group.  Whole groups are loaded without any bounds check so that all loads of a group
 // are in flight together; only the last piece of a row has a checked tail.
-template <int VEC, bool DIFF>
+template <int VEC, bool DIFF, bool UPDATE>
 __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
+    static_assert(DIFF || !UPDATE, "the update needs the subtracted g_i");
     __shared__ RowShared s;
     __shared__ StageRing rings[kBlkWaves];
     const int64_t row = blockIdx.y, d = p.d;
@@ -237,18 +252,18 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
     const uint32_t key_lo = estimate_key_lo<DIFF>(s, a, b, d, p.k);
 
     const int wave = threadIdx.x / kWave, lane = lane_id();
-    const int64_t slot = (int64_t)blockIdx.x * kBlkWaves + wave;
-    if (slot >= w.nslot) return;
+    const int64_t slot_no = (int64_t)blockIdx.x * kBlkWaves + wave;
+    if (slot_no >= w.nslot) return;
     StageRing &ring = rings[wave];
-    const int64_t lo = slot * w.L;
+    const int64_t lo = slot_no * w.L;
     const int64_t hi = lo + w.L < d ? lo + w.L : d;
-    int32_t *slot_idx = w.cand_idx + (row * w.nslot + slot) * w.L;
-    float *slot_val = w.cand_val + (row * w.nslot + slot) * w.L;
+    const int64_t slot_at = (row * w.nslot + slot_no) * w.L;
+    const SlotPtrs slot{w.cand_idx + slot_at, w.cand_val + slot_at, w.cand_new + slot_at};
     uint32_t cnt = 0, flushed = 0;
     constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
     int64_t base = lo;
     for (; base + kGroup <= hi; base += kGroup) {
-        float v[kUnroll][VEC];
+        float v[kUnroll][VEC], bv[kUnroll][VEC];
         if constexpr (VEC == 4) {
             float4 va[kUnroll], vb[kUnroll];
 #pragma unroll
@@ -260,34 +275,41 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
             for (int u = 0; u < kUnroll; ++u) {
                 v[u][0] = va[u].x; v[u][1] = va[u].y; v[u][2] = va[u].z; v[u][3] = va[u].w;
                 if constexpr (DIFF) {
-                    v[u][0] -= vb[u].x; v[u][1] -= vb[u].y; v[u][2] -= vb[u].z; v[u][3] -= vb[u].w;
+                    bv[u][0] = vb[u].x; bv[u][1] = vb[u].y; bv[u][2] = vb[u].z; bv[u][3] = vb[u].w;
                 }
             }
         } else {
-            float va[kUnroll], vb[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                va[u] = a[base + u * kStep + lane];
-                if constexpr (DIFF) vb[u] = b[base + u * kStep + lane];
+                v[u][0] = a[base + u * kStep + lane];
+                if constexpr (DIFF) bv[u][0] = b[base + u * kStep + lane];
             }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) v[u][0] = DIFF ? va[u] - vb[u] : va[u];
         }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            append_candidates<VEC, true>(v[u], base + u * kStep + lane * VEC, hi, key_lo, ring, lane, slot_idx,
-                                         slot_val, cnt, flushed);
+        for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) {
+                if constexpr (DIFF) v[u][t] -= bv[u][t];
+                else bv[u][t] = 0.f;
+            }
+            append_candidates<VEC, true, UPDATE>(v[u], bv[u], base + u * kStep + lane * VEC, hi, key_lo, ring, lane,
+                                                 slot, cnt, flushed);
+        }
     }
     for (; base < hi; base += kStep) {           // checked tail, entry by entry
         const int64_t e0 = base + lane * VEC;
-        float v[VEC];
+        float v[VEC], bv[VEC];
 #pragma unroll
-        for (int t = 0; t < VEC; ++t) v[t] = e0 + t < hi ? load_v<DIFF>(a, b, e0 + t) : 0.f;
-        append_candidates<VEC, false>(v, e0, hi, key_lo, ring, lane, slot_idx, slot_val, cnt, flushed);
+        for (int t = 0; t < VEC; ++t) {
+            v[t] = e0 + t < hi ? a[e0 + t] : 0.f;
+            bv[t] = DIFF && e0 + t < hi ? b[e0 + t] : 0.f;
+            v[t] -= bv[t];
+        }
+        append_candidates<VEC, false, UPDATE>(v, bv, e0, hi, key_lo, ring, lane, slot, cnt, flushed);
     }
     __builtin_amdgcn_wave_barrier();
-    ring_to_slot(ring, flushed, cnt - flushed, lane, slot_idx, slot_val);
-    if (lane == 0) w.slot_cnt[row * w.nslot + slot] = cnt;
+    ring_to_slot<UPDATE>(ring, flushed, cnt - flushed, lane, slot);
+    if (lane == 0) w.slot_cnt[row * w.nslot + slot_no] = cnt;
 }
 
 // ---------------------------------------------------------------- select (small k): one workgroup per row
@@ -341,6 +363,7 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
     };
     const float *cand_val = w.cand_val + row * w.nslot * w.L;
     const int32_t *cand_idx = w.cand_idx + row * w.nslot * w.L;
+    const float *cand_new = w.cand_new + row * w.nslot * w.L;
     // flat position j -> address in the slots; kBatch independent loads in flight per thread
     constexpr int kBatch = 8;
     auto address_of = [&](uint32_t j) {
@@ -429,7 +452,7 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
         int64_t at[kBatch];
         uint32_t pos[kBatch];
         int32_t e[kBatch];
-        float v[kBatch];
+        float v[kBatch], nx[kBatch];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             const uint32_t j = j0 + u * kBlk;
@@ -440,17 +463,14 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
         for (int u = 0; u < kBatch; ++u) {
             e[u] = at[u] >= 0 ? cand_idx[at[u]] : 0;
             v[u] = at[u] >= 0 ? cand_val[at[u]] : 0.f;
+            nx[u] = UPDATE && at[u] >= 0 ? cand_new[at[u]] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             if (at[u] < 0) continue;
             out_idx[pos[u]] = e[u];
             out_val[pos[u]] = v[u];
-            if (UPDATE) {
-                float *g_i = p.g_i + row * p.d;
-                g_i[e[u]] = g_i[e[u]] + v[u];              // Algorithm 2, line 6 (g_i still holds its old value)
-                atomicAdd(p.g + e[u], v[u] * p.inv_n);     // Algorithm 2, line 8
-            }
+            if (UPDATE) (p.g_i + row * p.d)[e[u]] = nx[u];      // Algorithm 2, line 6
         }
     }
 }
@@ -646,6 +666,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
     const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
     const int32_t *slot_idx = w.cand_idx + (row * w.nslot + sl) * w.L;
     const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
+    const float *slot_new = w.cand_new + (row * w.nslot + sl) * w.L;
     int32_t *out_idx = p.out_idx + row * p.k;
     float *out_val = p.out_val + row * p.k;
     for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
@@ -662,11 +683,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
             const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
             out_idx[pos] = e;
             out_val[pos] = v;
-            if (UPDATE) {
-                float *g_i = p.g_i + row * p.d;
-                g_i[e] = g_i[e] + v;                   // Algorithm 2, line 6 (g_i still holds its old value)
-                atomicAdd(p.g + e, v * p.inv_n);       // Algorithm 2, line 8
-            }
+            if (UPDATE) (p.g_i + row * p.d)[e] = slot_new[j];   // Algorithm 2, line 6
         }
         const uint32_t eq_next = eq_run + popc64(m_eq);
         out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
@@ -687,10 +704,10 @@ __global__ __launch_bounds__(kCandThreads) void zero_words_kernel(uint32_t *p, s
     for (size_t i = (size_t)blockIdx.x * kCandThreads + threadIdx.x; i < words; i += stride) p[i] = 0u;
 }
 
-template <int VEC, bool DIFF>
+template <int VEC, bool DIFF, bool UPDATE>
 void launch_collect(const TopkArgs &p, const Ws &w, hipStream_t stream) {
-    hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF>), dim3((unsigned)w.G, (unsigned)p.n), dim3(kBlk), 0, stream, p,
-                       w);
+    hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, UPDATE>), dim3((unsigned)w.G, (unsigned)p.n), dim3(kBlk), 0,
+                       stream, p, w);
 }
 
 template <bool DIFF, bool UPDATE>
@@ -736,10 +753,12 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
     const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
     if (upd && !diff) return hipErrorInvalidValue;
     const bool vec4 = (p.d % 4 == 0) && ((uintptr_t)p.a % 16 == 0) && (!diff || (uintptr_t)p.b % 16 == 0);
-    if (vec4 && diff) launch_collect<4, true>(p, w, stream);
-    else if (vec4) launch_collect<4, false>(p, w, stream);
-    else if (diff) launch_collect<1, true>(p, w, stream);
-    else launch_collect<1, false>(p, w, stream);
+    if (vec4 && upd) launch_collect<4, true, true>(p, w, stream);
+    else if (vec4 && diff) launch_collect<4, true, false>(p, w, stream);
+    else if (vec4) launch_collect<4, false, false>(p, w, stream);
+    else if (upd) launch_collect<1, true, true>(p, w, stream);
+    else if (diff) launch_collect<1, true, false>(p, w, stream);
+    else launch_collect<1, false, false>(p, w, stream);
     mk(K_TOPK_COLLECT);
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;

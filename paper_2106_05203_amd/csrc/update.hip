@@ -1,5 +1,5 @@
-// Dense vector kernels of Algorithm 2: the model step (line 3) and the mean of the workers'
-// estimators (input line, g^0 = (1/n) sum_i g_i^0).
+// Vector kernels of Algorithm 2: the model step (line 3), the master's aggregation of the messages
+// (line 8), and the mean of the workers' estimators (input line, g^0 = (1/n) sum_i g_i^0).
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -42,6 +42,139 @@ __global__ __launch_bounds__(kThreads) void mean_rows_kernel(const float *__rest
     }
 }
 
+// ---- Algorithm 2, line 8 (and line 3) without atomics ------------------------------------------
+// The coordinates are cut into sub-blocks of kAggSub.  A worker's message is sorted by position, so
+// its entries inside a sub-block are one contiguous run [start[w][b], start[w][b+1]); the runs are
+// recorded by message_index_kernel.  aggregate_kernel gives each sub-block to ONE wavefront, which
+// adds the workers' runs one after the other into its LDS accumulator (positions inside a message are
+// distinct, so a plain read-add-write is enough, and a single wavefront needs no barrier between
+// workers): the sum runs in worker order, g is bitwise reproducible, and no global atomic is issued.
+constexpr int kAggSub = 2048;
+constexpr int kAggWaves = kThreads / kWave;
+
+__global__ __launch_bounds__(kThreads) void message_index_kernel(const int32_t *__restrict__ idx, int64_t k,
+                                                                 int64_t nblk, int32_t *__restrict__ start) {
+    const int64_t w = blockIdx.y;
+    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (p >= k) return;
+    const int32_t *row = idx + w * k;
+    int32_t *out = start + w * (nblk + 1);
+    const int64_t b_cur = row[p] / kAggSub;
+    const int64_t b_prev = p > 0 ? row[p - 1] / kAggSub : -1;
+    for (int64_t b = b_prev + 1; b <= b_cur; ++b) out[b] = (int32_t)p;     // first entry of sub-block b
+    if (p == k - 1)
+        for (int64_t b = b_cur + 1; b <= nblk; ++b) out[b] = (int32_t)k;
+}
+
+template <bool STEP, bool VEC4>
+__global__ __launch_bounds__(kThreads) void aggregate_kernel(const int32_t *__restrict__ idx,
+                                                             const float *__restrict__ val,
+                                                             const int32_t *__restrict__ start, int32_t n, int64_t k,
+                                                             int64_t d, int64_t nblk, float *__restrict__ g,
+                                                             float *__restrict__ x, float inv_n, float neg_gamma) {
+    __shared__ float lds[kAggWaves][kAggSub];
+    const int wave = threadIdx.x / kWave, lane = lane_id();
+    const int64_t b = (int64_t)blockIdx.x * kAggWaves + wave;
+    if (b >= nblk) return;
+    float *acc = lds[wave];
+    const int64_t c0 = b * kAggSub;
+    const int64_t c1 = c0 + kAggSub < d ? c0 + kAggSub : d;
+    for (int j = lane; j < kAggSub; j += kWave) acc[j] = 0.f;
+    constexpr int kInFlight = 8;                     // workers whose runs are loaded together
+    for (int32_t w0 = 0; w0 < n; w0 += kWave) {
+        const int32_t w = w0 + lane;
+        const int32_t s0 = w < n ? start[(int64_t)w * (nblk + 1) + b] : 0;
+        const int32_t s1 = w < n ? start[(int64_t)w * (nblk + 1) + b + 1] : 0;
+        const int32_t tile = n - w0 < kWave ? n - w0 : kWave;
+        for (int32_t t0 = 0; t0 < tile; t0 += kInFlight) {
+            int32_t e[kInFlight], len[kInFlight];
+            int64_t base[kInFlight];
+            float v[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int src = t0 + u < tile ? t0 + u : 0;
+                const int32_t lo = __shfl(s0, src, kWave), hi = __shfl(s1, src, kWave);
+                len[u] = t0 + u < tile ? hi - lo : 0;
+                base[u] = (int64_t)(w0 + src) * k + lo;
+                const int64_t at = lane < len[u] ? base[u] + lane : 0;     // unconditional loads, no branch
+                e[u] = idx[at];
+                v[u] = val[at];
+                if (lane >= len[u]) e[u] = -1;
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {     // worker order
+                if (e[u] >= 0) acc[e[u] - c0] += v[u];
+                for (int32_t j = lane + kWave; j < len[u]; j += kWave) acc[idx[base[u] + j] - c0] += val[base[u] + j];
+            }
+        }
+    }
+    if (VEC4) {
+        for (int64_t j = c0 + lane * 4; j < c1; j += kWave * 4) {
+            const float4 a4 = *reinterpret_cast<const float4 *>(acc + (j - c0));
+            float4 g4 = *reinterpret_cast<const float4 *>(g + j);
+            g4.x = fmaf(a4.x, inv_n, g4.x);
+            g4.y = fmaf(a4.y, inv_n, g4.y);
+            g4.z = fmaf(a4.z, inv_n, g4.z);
+            g4.w = fmaf(a4.w, inv_n, g4.w);
+            *reinterpret_cast<float4 *>(g + j) = g4;
+            if (STEP) {
+                float4 x4 = *reinterpret_cast<const float4 *>(x + j);
+                x4.x = fmaf(neg_gamma, g4.x, x4.x);
+                x4.y = fmaf(neg_gamma, g4.y, x4.y);
+                x4.z = fmaf(neg_gamma, g4.z, x4.z);
+                x4.w = fmaf(neg_gamma, g4.w, x4.w);
+                *reinterpret_cast<float4 *>(x + j) = x4;
+            }
+        }
+    } else {
+        for (int64_t j = c0 + lane; j < c1; j += kWave) {
+            const float gj = fmaf(acc[j - c0], inv_n, g[j]);
+            g[j] = gj;
+            if (STEP) x[j] = fmaf(neg_gamma, gj, x[j]);
+        }
+    }
+}
+
+// Small problems (d <= kSmallD, n * k <= kSmallEntries, n <= kSmallWorkers): one workgroup, one launch.
+// Every thread keeps up to 8 message entries in registers; the workers' entries are then added to the
+// LDS accumulator worker by worker (a barrier between workers, no memory access in that loop).
+constexpr int kSmallThreads = 1024, kSmallPer = 8;
+constexpr int kSmallD = 16384, kSmallEntries = kSmallThreads * kSmallPer, kSmallWorkers = 256;
+
+template <bool STEP>
+__global__ __launch_bounds__(kSmallThreads) void aggregate_small_kernel(const int32_t *__restrict__ idx,
+                                                                        const float *__restrict__ val, int32_t n,
+                                                                        int64_t k, int64_t d, float *__restrict__ g,
+                                                                        float *__restrict__ x, float inv_n,
+                                                                        float neg_gamma) {
+    __shared__ float acc[kSmallD];
+    const int tid = threadIdx.x;
+    const int64_t total = (int64_t)n * k;
+    int32_t e[kSmallPer], wk[kSmallPer];
+    float v[kSmallPer];
+#pragma unroll
+    for (int u = 0; u < kSmallPer; ++u) {
+        const int64_t t = tid + (int64_t)u * kSmallThreads;
+        const int64_t at = t < total ? t : 0;
+        e[u] = idx[at];
+        v[u] = val[at];
+        wk[u] = t < total ? (int32_t)(t / k) : -1;
+    }
+    for (int64_t j = tid; j < d; j += kSmallThreads) acc[j] = 0.f;
+    __syncthreads();
+    for (int32_t w = 0; w < n; ++w) {           // worker order; positions inside a message are distinct
+#pragma unroll
+        for (int u = 0; u < kSmallPer; ++u)
+            if (wk[u] == w) acc[e[u]] += v[u];
+        __syncthreads();
+    }
+    for (int64_t j = tid; j < d; j += kSmallThreads) {
+        const float gj = fmaf(acc[j], inv_n, g[j]);
+        g[j] = gj;
+        if (STEP) x[j] = fmaf(neg_gamma, gj, x[j]);
+    }
+}
+
 unsigned grid_for(int64_t items, int64_t cap) {
     int64_t blocks = (items + kThreads - 1) / kThreads;
     if (blocks > cap) blocks = cap;
@@ -60,6 +193,43 @@ hipError_t launch_model_step(float *x, const float *g, int64_t d, float gamma, h
         hipLaunchKernelGGL(model_step_kernel, dim3(grid_for(d, 8192)), dim3(kThreads), 0, stream, x, g, d,
                            -gamma);
     }
+    return hipGetLastError();
+}
+
+size_t aggregate_index_bytes(int32_t n, int64_t d) {
+    return sizeof(int32_t) * (size_t)n * ((size_t)((d + kAggSub - 1) / kAggSub) + 1);
+}
+
+hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int64_t k, int64_t d, float *g, float *x,
+                            float gamma, void *index, hipStream_t stream) {
+    const float inv_n = 1.0f / (float)n;
+    if (d <= kSmallD && (int64_t)n * k <= kSmallEntries && n <= kSmallWorkers) {
+        if (x)
+            hipLaunchKernelGGL(aggregate_small_kernel<true>, dim3(1), dim3(kSmallThreads), 0, stream, idx, val, n, k, d,
+                               g, x, inv_n, -gamma);
+        else
+            hipLaunchKernelGGL(aggregate_small_kernel<false>, dim3(1), dim3(kSmallThreads), 0, stream, idx, val, n, k,
+                               d, g, x, inv_n, -gamma);
+        return hipGetLastError();
+    }
+    const int64_t nblk = (d + kAggSub - 1) / kAggSub;
+    int32_t *start = (int32_t *)index;
+    hipLaunchKernelGGL(message_index_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads), (unsigned)n),
+                       dim3(kThreads), 0, stream, idx, k, nblk, start);
+    const dim3 grid((unsigned)((nblk + kAggWaves - 1) / kAggWaves)), block(kThreads);
+    const bool vec4 = (d % 4 == 0) && (((uintptr_t)g | (uintptr_t)(x ? x : g)) % 16 == 0);
+    if (x && vec4)
+        hipLaunchKernelGGL((aggregate_kernel<true, true>), grid, block, 0, stream, idx, val, start, n, k, d, nblk, g, x,
+                           inv_n, -gamma);
+    else if (x)
+        hipLaunchKernelGGL((aggregate_kernel<true, false>), grid, block, 0, stream, idx, val, start, n, k, d, nblk, g, x,
+                           inv_n, -gamma);
+    else if (vec4)
+        hipLaunchKernelGGL((aggregate_kernel<false, true>), grid, block, 0, stream, idx, val, start, n, k, d, nblk, g, x,
+                           inv_n, -gamma);
+    else
+        hipLaunchKernelGGL((aggregate_kernel<false, false>), grid, block, 0, stream, idx, val, start, n, k, d, nblk, g,
+                           x, inv_n, -gamma);
     return hipGetLastError();
 }
 
