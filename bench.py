@@ -24,6 +24,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
 
+# HBM bytes per launch of the dominant kernels, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+# scaled by a plain 1 GiB copy's readings (summaries and commands under profiles/); not measured live.
+MEASURED_TRAFFIC_BYTES = {
+    "C2/grad_main": 817.1e6,       # profiles/ef21_step_C2_hbm_traffic_pmc.md
+}
+
 
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -86,7 +92,7 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
            "ms_per_step_events": round(ev, 5), "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()},
            "iteration_algorithmic_bytes": 4 * n * m * d + 4 * n * m + 12 * n * d + 24 * n * k + 12 * d}
     out["roofline"] = roofline(4.0 * n * m * d + 4.0 * n * m + 4.0 * d, per_kernel["grad_main"],
-                               "logreg_dense_fused_kernel (grad_main)")
+                               "logreg_dense_fused_kernel (grad_main)", MEASURED_TRAFFIC_BYTES.get(f"{name}/grad_main"))
     out["iteration_frac_of_hbm_peak"] = round(out["iteration_algorithmic_bytes"] / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     return out, (W, h)
 
@@ -198,6 +204,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--only", default="", help="comma list of C0,C1,C2,C3,C4 (C2, the headline, always runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run five plain device-to-device copies of 1 GiB (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (workers are rows of a batch; there are no collectives); "
@@ -209,6 +217,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.calibrate_copy:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 device-to-device copies", "bytes_read_each": src.numel() * 4,
+                          "bytes_written_each": src.numel() * 4}), flush=True)
+        return 0
     binding.load_library()
     which = set(filter(None, args.only.split(","))) or {"C0", "C1", "C2", "C3", "C4"}
     K, Wm = args.steps, args.warmup
