@@ -23,10 +23,13 @@ struct DensePlan {
     int64_t chunks;   // workgroups (row blocks) per worker
 };
 
+// About 2048 workgroups in all (two rounds of four 256-thread workgroups per CU on 256 CUs), at least
+// 8 rows each.
 DensePlan dense_plan(int32_t n, int64_t m) {
-    int64_t rows = ((int64_t)n * m + 2047) / 2048;
+    int64_t target = 2048 / n;
+    if (target < 1) target = 1;
+    int64_t rows = (m + target - 1) / target;
     if (rows < 8) rows = 8;
-    rows = (rows + kWaves - 1) / kWaves * kWaves;
     return {rows, (m + rows - 1) / rows};
 }
 
@@ -35,7 +38,7 @@ __device__ __forceinline__ float residual(float y, float z) {   // -y / (1 + exp
 }
 
 // ------------------------------------------------------------------ dense, one pass over A
-template <int VEC, int NQ>
+template <int VEC, int NQ, int ROWS>
 __global__ __launch_bounds__(kThreads) void logreg_dense_fused_kernel(const float *__restrict__ A,
                                                                       const float *__restrict__ y,
                                                                       const float *__restrict__ x,
@@ -57,36 +60,50 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_fused_kernel(const floa
         }
     }
 
+    // ROWS rows per wavefront and trip: their loads are all issued before the first dot product.  A row
+    // index past the block is clamped to the block's last row and its coefficient set to zero.
     const int64_t l0 = chunk * rows_per_wg;
     const int64_t l1 = l0 + rows_per_wg < m ? l0 + rows_per_wg : m;
-    for (int64_t l = l0 + wave; l < l1; l += kWaves) {
-        const float *row = A + (worker * m + l) * d;
-        float av[NQ][VEC];
+    for (int64_t l = l0 + wave * ROWS; l < l1; l += kWaves * ROWS) {
+        float av[ROWS][NQ][VEC], yl[ROWS], s[ROWS];
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const int64_t c0 = ((int64_t)q * kWave + lane) * VEC;
-            if constexpr (VEC == 4) {
-                float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (c0 < d) t4 = *reinterpret_cast<const float4 *>(row + c0);
-                av[q][0] = t4.x;
-                av[q][1] = t4.y;
-                av[q][2] = t4.z;
-                av[q][3] = t4.w;
-            } else {
-                av[q][0] = (c0 < d) ? row[c0] : 0.f;
+        for (int r = 0; r < ROWS; ++r) {
+            const int64_t lr = l + r < l1 ? l + r : l1 - 1;
+            const float *row = A + (worker * m + lr) * d;
+            yl[r] = y[worker * m + lr];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const int64_t c0 = ((int64_t)q * kWave + lane) * VEC;
+                if constexpr (VEC == 4) {
+                    float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (c0 < d) t4 = *reinterpret_cast<const float4 *>(row + c0);
+                    av[r][q][0] = t4.x;
+                    av[r][q][1] = t4.y;
+                    av[r][q][2] = t4.z;
+                    av[r][q][3] = t4.w;
+                } else {
+                    av[r][q][0] = (c0 < d) ? row[c0] : 0.f;
+                }
             }
         }
-        float s = 0.f;
 #pragma unroll
-        for (int q = 0; q < NQ; ++q)
+        for (int r = 0; r < ROWS; ++r) {
+            s[r] = 0.f;
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) s = fmaf(av[q][t], xr[q][t], s);
-        s = wave_sum(s);
-        const float r = residual(y[worker * m + l], s);
+            for (int q = 0; q < NQ; ++q)
 #pragma unroll
-        for (int q = 0; q < NQ; ++q)
+                for (int t = 0; t < VEC; ++t) s[r] = fmaf(av[r][q][t], xr[q][t], s[r]);
+        }
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) acc[q][t] = fmaf(r, av[q][t], acc[q][t]);
+        for (int r = 0; r < ROWS; ++r) s[r] = wave_sum(s[r]);
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const float coef = l + r < l1 ? residual(yl[r], s[r]) : 0.f;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) acc[q][t] = fmaf(coef, av[r][q][t], acc[q][t]);
+        }
     }
 
     // add the four wavefronts' accumulators in wavefront order
@@ -164,8 +181,9 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_finish_kernel(const flo
 template <int VEC, int NQ>
 void launch_fused(const float *A, const float *y, const float *x, float *part, int32_t n, int64_t m, int64_t d,
                   const DensePlan &pl, hipStream_t stream) {
-    hipLaunchKernelGGL((logreg_dense_fused_kernel<VEC, NQ>), dim3((unsigned)pl.chunks, (unsigned)n), dim3(kThreads),
-                       0, stream, A, y, x, part, m, d, pl.rows_per_wg);
+    constexpr int ROWS = NQ * VEC <= 32 ? 2 : 1;     // two rows in flight while their registers fit
+    hipLaunchKernelGGL((logreg_dense_fused_kernel<VEC, NQ, ROWS>), dim3((unsigned)pl.chunks, (unsigned)n),
+                       dim3(kThreads), 0, stream, A, y, x, part, m, d, pl.rows_per_wg);
 }
 
 }  // namespace

@@ -17,15 +17,28 @@ __global__ __launch_bounds__(kRowThreads) void topk_row_kernel(TopkArgs p) {
     row_topk<DIFF, UPDATE>(s, p, blockIdx.x);
 }
 
+template <bool DIFF, bool UPDATE>
+__global__ __launch_bounds__(kRowThreads) void topk_row_cached_kernel(TopkArgs p) {
+    __shared__ RowShared s;
+    __shared__ float cache[kRowCache];
+    row_topk_cached<DIFF, UPDATE>(s, cache, p, blockIdx.x);
+}
+
 }  // namespace
 
 hipError_t launch_topk_row(const TopkArgs &p, hipStream_t stream) {
     const dim3 grid((unsigned)p.n), block(kRowThreads);
     const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
     if (upd && !diff) return hipErrorInvalidValue;   // line 6 needs the subtracted g_i
-    if (upd) hipLaunchKernelGGL((topk_row_kernel<true, true>), grid, block, 0, stream, p);
-    else if (diff) hipLaunchKernelGGL((topk_row_kernel<true, false>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((topk_row_kernel<false, false>), grid, block, 0, stream, p);
+    if (p.d <= kRowCache) {
+        if (upd) hipLaunchKernelGGL((topk_row_cached_kernel<true, true>), grid, block, 0, stream, p);
+        else if (diff) hipLaunchKernelGGL((topk_row_cached_kernel<true, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((topk_row_cached_kernel<false, false>), grid, block, 0, stream, p);
+    } else {
+        if (upd) hipLaunchKernelGGL((topk_row_kernel<true, true>), grid, block, 0, stream, p);
+        else if (diff) hipLaunchKernelGGL((topk_row_kernel<true, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((topk_row_kernel<false, false>), grid, block, 0, stream, p);
+    }
     return hipGetLastError();
 }
 

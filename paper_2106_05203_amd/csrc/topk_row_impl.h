@@ -34,14 +34,14 @@ __device__ __forceinline__ float load_v(const float *a, const float *b, int64_t 
 }
 
 // Histogram of digit ((key >> shift) & (nbins-1)) over the entries whose key >> pshift == prefix.
-template <bool DIFF>
-__device__ void hist_pass(RowShared &s, const float *a, const float *b, int64_t d, int pshift, uint32_t prefix,
-                          int shift, int nbins) {
+// value(e) yields entry e of the row.
+template <class ValueFn>
+__device__ void hist_pass(RowShared &s, int64_t d, ValueFn value, int pshift, uint32_t prefix, int shift, int nbins) {
     for (int i = threadIdx.x; i < nbins; i += kRowThreads) s.hist[i] = 0u;
     __syncthreads();
     const uint32_t mask = (uint32_t)nbins - 1u;
     for (int64_t e = threadIdx.x; e < d; e += kRowThreads) {
-        const uint32_t key = mag_key(load_v<DIFF>(a, b, e));
+        const uint32_t key = mag_key(value(e));
         if ((key >> pshift) == prefix) atomicAdd(&s.hist[(key >> shift) & mask], 1u);
     }
     __syncthreads();
@@ -79,23 +79,22 @@ __device__ void select_bin(RowShared &s, int nbins, uint32_t need) {
 }
 
 // Whole Top-k of one row by the calling workgroup (all kRowThreads threads must call).
-// With UPDATE the emission also applies line 6 of Algorithm 2.
-template <bool DIFF, bool UPDATE>
-__device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
+// value(e) yields entry e of the row (the same bits every time it is asked); with UPDATE the emission
+// also applies line 6 of Algorithm 2, g_i[e] = base(e) + value(e), base(e) being the subtracted g_i[e].
+template <bool UPDATE, class ValueFn, class BaseFn>
+__device__ void row_topk_on(RowShared &s, const TopkArgs &p, int64_t row, ValueFn value, BaseFn base_value) {
     const int64_t d = p.d;
-    const float *a = p.a + row * d;
-    const float *b = DIFF ? p.b + row * d : nullptr;
 
     // ---- threshold key T and tie quota q ------------------------------------------------
-    hist_pass<DIFF>(s, a, b, d, 31, 0u, kBits2 + kBits3, 1 << kBits1);
+    hist_pass(s, d, value, 31, 0u, kBits2 + kBits3, 1 << kBits1);
     select_bin(s, 1 << kBits1, (uint32_t)p.k);
     const uint32_t d1 = s.bin;
     uint32_t need = s.need;
-    hist_pass<DIFF>(s, a, b, d, kBits2 + kBits3, d1, kBits3, 1 << kBits2);
+    hist_pass(s, d, value, kBits2 + kBits3, d1, kBits3, 1 << kBits2);
     select_bin(s, 1 << kBits2, need);
     const uint32_t d12 = (d1 << kBits2) | s.bin;
     need = s.need;
-    hist_pass<DIFF>(s, a, b, d, kBits3, d12, 0, 1 << kBits3);
+    hist_pass(s, d, value, kBits3, d12, 0, 1 << kBits3);
     select_bin(s, 1 << kBits3, need);
     const uint32_t T = (d12 << kBits3) | s.bin;
     const uint32_t q = s.need;   // 1 <= q <= number of entries with key == T
@@ -113,7 +112,7 @@ __device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
         const int64_t e = base + lane;
         uint32_t key = 0u;
         const bool in = e < hi;
-        if (in) key = mag_key(load_v<DIFF>(a, b, e));
+        if (in) key = mag_key(value(e));
         n_gt += popc64(__ballot(in && key > T));
         n_eq += popc64(__ballot(in && key == T));
     }
@@ -135,14 +134,7 @@ __device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
     for (int64_t base = lo; base < hi; base += kWave) {
         const int64_t e = base + lane;
         const bool in = e < hi;
-        float v = 0.f, bv = 0.f;
-        if (in) {
-            v = a[e];
-            if (DIFF) {
-                bv = b[e];
-                v = v - bv;
-            }
-        }
+        const float v = in ? value(e) : 0.f;
         const uint32_t key = mag_key(v);
         const bool gt = in && key > T;
         const bool eq = in && key == T;
@@ -154,7 +146,7 @@ __device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
             const uint32_t pos = out_run + lanes_below(m_gt) + ties_taken_before;
             out_idx[pos] = (int32_t)e;
             out_val[pos] = v;
-            if (UPDATE) g_i[e] = bv + v;               // Algorithm 2, line 6
+            if (UPDATE) g_i[e] = base_value(e) + v;    // Algorithm 2, line 6
         }
         const uint32_t eq_next = eq_run + popc64(m_eq);
         out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
@@ -162,5 +154,27 @@ __device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
     }
 }
 
+// The row read from global memory in every pass (any d).
+template <bool DIFF, bool UPDATE>
+__device__ void row_topk(RowShared &s, const TopkArgs &p, int64_t row) {
+    const float *a = p.a + row * p.d;
+    const float *b = DIFF ? p.b + row * p.d : nullptr;
+    row_topk_on<UPDATE>(
+        s, p, row, [=](int64_t e) { return load_v<DIFF>(a, b, e); }, [=](int64_t e) { return DIFF ? b[e] : 0.f; });
+}
+
+// Rows of at most kRowCache entries: the row is formed once into LDS (`cache`), all passes read it there.
+constexpr int kRowCache = 8192;
+
+template <bool DIFF, bool UPDATE>
+__device__ void row_topk_cached(RowShared &s, float *cache, const TopkArgs &p, int64_t row) {
+    const int64_t d = p.d;
+    const float *a = p.a + row * d;
+    const float *b = DIFF ? p.b + row * d : nullptr;
+    for (int64_t e = threadIdx.x; e < d; e += kRowThreads) cache[e] = load_v<DIFF>(a, b, e);
+    __syncthreads();
+    row_topk_on<UPDATE>(
+        s, p, row, [=](int64_t e) { return cache[e]; }, [=](int64_t e) { return DIFF ? b[e] : 0.f; });
+}
 
 }  // namespace ef21

@@ -257,6 +257,27 @@ def test_config4_full_size_step(gpu, oracle):
             g_prev = g.astype(np.float64)
 
 
+@pytest.mark.parametrize("n,d,m,k", [(5, 2000, 120, 20), (3, 99, 64, 7), (2, 8192, 40, 100), (2, 8200, 40, 100)])
+def test_step_with_internal_gradient_equals_supplied_gradient(gpu, n, d, m, k):
+    """ef21_step(NULL) computes the dense gradient itself; the result must be bit for bit what
+    ef21_local_grad followed by ef21_step(grads) gives."""
+    torch, binding = gpu
+    W = workloads.logreg_dense(n, d, m, seed=d)
+    A, y = to_gpu(torch, W.A), to_gpu(torch, W.y)
+    x0 = torch.randn(d, device="cuda") * 0.3
+    g_i0 = torch.randn(n, d, device="cuda") * 0.01
+    with binding.EF21(n, d, k, 0.5) as h1, binding.EF21(n, d, k, 0.5) as h2:
+        for h in (h1, h2):
+            h.set_problem_dense(A, y, 0.1)
+            h.set_state(x0, g_i0, None)
+        for t in range(4):
+            h1.step(None)
+            h2.step(h2.local_grad())
+            torch.cuda.synchronize()
+            for a, b in zip(h1.get_state() + h1.get_messages(), h2.get_state() + h2.get_messages()):
+                assert torch.equal(a.view(torch.int32), b.view(torch.int32)), t
+
+
 def test_get_set_state_roundtrip_and_errors(gpu):
     torch, binding = gpu
     with binding.EF21(3, 17, 4, 0.1) as h:
