@@ -20,6 +20,16 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
 
 __device__ __forceinline__ uint32_t popc64(uint64_t m) { return (uint32_t)__popcll(m); }
 
+// Loads of streamed data (read once by the kernel, too large to stay in a cache): marked non-temporal
+// so that the lines are not kept.  stream_load4 needs a 16-byte aligned address.
+__device__ __forceinline__ float4 stream_load4(const float *p) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ float stream_load(const float *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ int32_t stream_load(const int32_t *p) { return __builtin_nontemporal_load(p); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -23,10 +23,11 @@ struct DensePlan {
     int64_t chunks;   // workgroups (row blocks) per worker
 };
 
-// About 2048 workgroups in all (two rounds of four 256-thread workgroups per CU on 256 CUs), at least
-// 8 rows each.
+// About two workgroups per compute unit in all (512 on 256 CUs), each streaming one long block of rows:
+// fewer, longer blocks measured faster than several rounds of short ones, and they leave fewer partial
+// sums to add.  At least 8 rows each.
 DensePlan dense_plan(int32_t n, int64_t m) {
-    int64_t target = 2048 / n;
+    int64_t target = 512 / n;
     if (target < 1) target = 1;
     int64_t rows = (m + target - 1) / target;
     if (rows < 8) rows = 8;
@@ -76,13 +77,13 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_fused_kernel(const floa
                 const int64_t c0 = ((int64_t)q * kWave + lane) * VEC;
                 if constexpr (VEC == 4) {
                     float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (c0 < d) t4 = *reinterpret_cast<const float4 *>(row + c0);
+                    if (c0 < d) t4 = stream_load4(row + c0);
                     av[r][q][0] = t4.x;
                     av[r][q][1] = t4.y;
                     av[r][q][2] = t4.z;
                     av[r][q][3] = t4.w;
                 } else {
-                    av[r][q][0] = (c0 < d) ? row[c0] : 0.f;
+                    av[r][q][0] = (c0 < d) ? stream_load(row + c0) : 0.f;
                 }
             }
         }

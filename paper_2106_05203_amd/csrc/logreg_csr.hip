@@ -172,8 +172,8 @@ __global__ __launch_bounds__(kAtrThreads) void csr_dot_kernel(const int64_t *__r
                 const int32_t len = __shfl(mine.len, u, kWave);
                 in[u] = t0 + lane < len;
                 const int64_t at = b + (in[u] ? t0 + lane : (len > 0 ? len - 1 : 0));
-                c[u] = len > 0 ? col[at] : (int32_t)c0;
-                v[u] = len > 0 ? val[at] : 0.f;
+                c[u] = len > 0 ? stream_load(col + at) : (int32_t)c0;
+                v[u] = len > 0 ? stream_load(val + at) : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < kRows; ++u) {
@@ -225,8 +225,8 @@ __global__ __launch_bounds__(kAtrThreads) void csr_atr_kernel(const int64_t *__r
                 const int32_t len = __shfl(mine.len, u, kWave);
                 in[u] = t0 + lane < len;
                 const int64_t at = b + (in[u] ? t0 + lane : (len > 0 ? len - 1 : 0));
-                c[u] = len > 0 ? col[at] : (int32_t)c0;
-                v[u] = len > 0 ? val[at] : 0.f;
+                c[u] = len > 0 ? stream_load(col + at) : (int32_t)c0;
+                v[u] = len > 0 ? stream_load(val + at) : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < kRows; ++u) {

@@ -268,8 +268,8 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
             float4 va[kUnroll], vb[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                va[u] = *reinterpret_cast<const float4 *>(a + base + u * kStep + lane * 4);
-                if constexpr (DIFF) vb[u] = *reinterpret_cast<const float4 *>(b + base + u * kStep + lane * 4);
+                va[u] = stream_load4(a + base + u * kStep + lane * 4);
+                if constexpr (DIFF) vb[u] = stream_load4(b + base + u * kStep + lane * 4);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -281,8 +281,8 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
         } else {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                v[u][0] = a[base + u * kStep + lane];
-                if constexpr (DIFF) bv[u][0] = b[base + u * kStep + lane];
+                v[u][0] = stream_load(a + base + u * kStep + lane);
+                if constexpr (DIFF) bv[u][0] = stream_load(b + base + u * kStep + lane);
             }
         }
 #pragma unroll
