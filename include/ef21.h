@@ -92,11 +92,13 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
  *   csr:    one CSR over all n*m rows, worker i owning rows i*m .. (i+1)*m-1:
  *           rowptr [n*m+1] int64, col [nnz] int32 in [0, d), val [nnz] fp32, y [n][m]
  * The arrays are BORROWED: they must stay valid and unchanged while the handle uses them.
- * Allocates a gradient buffer [n][d] and scratch on first use.  The csr call also reads rowptr
- * and col once (it waits for the stream): if every row's columns are strictly ascending and
- * inside [0, d) it builds a small per-row index of column ranges, which the fast two-pass
- * gradient kernels need; otherwise a slower kernel based on global atomics is used, in which
- * columns outside [0, d) are skipped.
+ * Allocates a gradient buffer [n][d] and scratch on first use.  The csr call also reads the matrix
+ * once (it waits for the stream): if every row's columns are strictly ascending and inside [0, d),
+ * and no worker holds 2^31 - 2^16 entries or more, it builds what the fast two-pass gradient kernels
+ * need -- a small per-row index of column ranges and a column-major copy of each worker's block
+ * (8 bytes per entry plus 4 n (d + 1) bytes of device memory, owned by the handle).  Otherwise a
+ * slower kernel based on global floating-point atomics is used, in which columns outside [0, d) are
+ * skipped.
  */
 int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_t m, float lambda);
 int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *col, const float *val,
@@ -117,9 +119,8 @@ int ef21_get_messages(ef21_handle h, int32_t *idx, float *val);
  * grad f_i(x) for all workers (derivative of eq. (9)):
  *   (1/m) sum_l  -y_il / (1 + exp(y_il a_il^T x)) a_il  +  2 lambda x_j / (1 + x_j^2)^2
  * at `x` [d] (NULL = the handle's x), written to out_grad [n][d].  EF21_ESTATE without a
- * problem.  fp32 arithmetic; partial sums over rows are combined in a fixed order for the
- * dense layout (bitwise reproducible) and with floating-point atomics for CSR (reproducible
- * to rounding).
+ * problem.  fp32 arithmetic; sums over rows are taken in a fixed order (bitwise reproducible),
+ * except in the atomics-based kernel for CSR rows with unsorted columns (reproducible to rounding).
  */
 int ef21_local_grad(ef21_handle h, const float *x, float *out_grad);
 

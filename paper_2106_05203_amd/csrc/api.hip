@@ -88,6 +88,7 @@ struct ef21_ctx {
     void *agg_index = nullptr;      // runs of the messages per coordinate sub-block (scratch of line 8)
     void *csr_index = nullptr;      // column-range index of the attached CSR problem
     bool csr_indexed = false;
+    int64_t nnz = 0;                // entries of the attached CSR problem
     Timing timing;
 };
 
@@ -192,8 +193,8 @@ int enqueue_local_grad(ef21_ctx *c, const float *x, float *out) {
         st = ef21::launch_logreg_grad_dense(c->A, c->y, x, out, c->n, c->m, c->d, c->lambda, c->scratch, c->stream,
                                             mk);
     else
-        st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->lambda,
-                                          c->csr_indexed ? c->csr_index : nullptr, c->stream, mk);
+        st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->nnz,
+                                          c->lambda, c->csr_indexed ? c->csr_index : nullptr, c->stream, mk);
     if (st != hipSuccess) return fail_hip(st, "gradient kernel launch");
     return EF21_OK;
 }
@@ -347,14 +348,19 @@ int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *co
     (void)hipFree(h->csr_index);
     h->csr_index = nullptr;
     h->csr_indexed = false;
-    const size_t index_bytes = ef21::logreg_csr_index_bytes(h->n, m, h->d);
+    int64_t nnz = 0;
+    EF21_HIP(hipMemcpy(&nnz, rowptr + (int64_t)h->n * m, sizeof(nnz), hipMemcpyDeviceToHost));
+    if (nnz < 0) return fail(EF21_EINVAL, "rowptr[n*m] (the number of entries) is negative");
+    const size_t index_bytes = ef21::logreg_csr_index_bytes(h->n, m, h->d, nnz);
     if (index_bytes) {
         if (hipMalloc(&h->csr_index, index_bytes) != hipSuccess) {
             (void)hipGetLastError();
-            return fail(EF21_ENOMEM, "hipMalloc of the CSR column-range index failed");
+            return fail(EF21_ENOMEM, "hipMalloc of the CSR index and column-major copy failed");
         }
-        EF21_HIP(ef21::logreg_csr_build_index(rowptr, col, h->n, m, h->d, h->csr_index, h->stream, &h->csr_indexed));
+        EF21_HIP(ef21::logreg_csr_build_index(rowptr, col, val, h->n, m, h->d, nnz, h->csr_index, h->stream,
+                                              &h->csr_indexed));
     }
+    h->nnz = nnz;
     h->kind = kCSR;
     h->rowptr = rowptr;
     h->col = col;

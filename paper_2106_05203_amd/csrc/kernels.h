@@ -78,15 +78,17 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
                                     int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
                                     const Marker &mk = Marker());
 
-// Gradient of eq. (9) for all workers, CSR rows.  `index` (logreg_csr_index_bytes bytes, owned by the
-// caller) is built once per problem by logreg_csr_build_index, which synchronises the stream and reports
-// whether the two-pass kernels can be used (every row's columns ascending and inside [0, d)); pass
-// index = nullptr to launch_logreg_grad_csr otherwise.
-size_t logreg_csr_index_bytes(int32_t n, int64_t m, int64_t d);
-hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, int32_t n, int64_t m, int64_t d,
-                                  void *index, hipStream_t stream, bool *usable);
+// Gradient of eq. (9) for all workers, CSR rows with nnz entries in all.  `index`
+// (logreg_csr_index_bytes bytes, owned by the caller) is built once per problem by logreg_csr_build_index
+// and holds per-row column-range offsets, a column-major copy of each worker's block (8 bytes per entry)
+// and scratch for the two-pass kernels.  The build synchronises the stream and reports whether those
+// kernels can be used (every row's columns ascending and inside [0, d), fewer than 2^31 entries per
+// worker); pass index = nullptr to launch_logreg_grad_csr otherwise.
+size_t logreg_csr_index_bytes(int32_t n, int64_t m, int64_t d, int64_t nnz);
+hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, const float *val, int32_t n, int64_t m,
+                                  int64_t d, int64_t nnz, void *index, hipStream_t stream, bool *usable);
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
-                                  const float *x, float *grad, int32_t n, int64_t m, int64_t d, float lambda,
-                                  const void *index, hipStream_t stream, const Marker &mk = Marker());
+                                  const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
+                                  float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker());
 
 }  // namespace ef21

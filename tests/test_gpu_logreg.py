@@ -110,6 +110,38 @@ def test_csr_ragged_rows(gpu, oracle):
                        "ragged")
 
 
+@pytest.mark.parametrize("n,m,d,always,extra", [(2, 1500, 200, (0, 5, 199), 6), (1, 17000, 70, (1,), 3),
+                                                (3, 100, 13000, (12287, 12288), 40)])
+def test_csr_long_columns_many_rows(gpu, oracle, n, m, d, always, extra):
+    """Columns present in every row (pieces of a column longer than a staging tile, summed by the whole
+    wavefront), more rows per worker than the in-LDS coefficient vector holds, columns next to a range
+    boundary; and the sorted-CSR gradient is bitwise reproducible."""
+    torch, binding = gpu
+    print(f"csr long columns case n={n} m={m} d={d}", flush=True)
+    rng = np.random.default_rng(m + d)
+    others = np.setdiff1d(np.arange(d), np.array(always))
+    rows = [np.sort(np.concatenate([np.array(always), rng.choice(others, size=extra, replace=False)]))
+            for _ in range(n * m)]
+    per = len(always) + extra
+    rowptr = (np.arange(n * m + 1) * per).astype(np.int64)
+    col = np.concatenate(rows).astype(np.int32)
+    val = (rng.random(col.size) * 2 - 0.5).astype(np.float32)
+    y = np.where(rng.random((n, m)) < 0.5, 1.0, -1.0).astype(np.float32)
+    P = oracle.LogRegCSR(rowptr, col, val, y, n, m, d, 0.1)
+    x = rng.standard_normal(d).astype(np.float32)
+    with binding.EF21(n, d, 1, 0.1) as h:
+        h.set_problem_csr(to_gpu(torch, rowptr, np.int64), to_gpu(torch, col, np.int32), to_gpu(torch, val),
+                          to_gpu(torch, y), m, 0.1)
+        got = h.local_grad(to_gpu(torch, x))
+        again = h.local_grad(to_gpu(torch, x))
+        torch.cuda.synchronize()
+    assert torch.equal(got, again), "the gradient from sorted CSR rows is bitwise reproducible"
+    D = np.zeros((n * m, d), np.float32)
+    D[np.repeat(np.arange(n * m), per), col] = val
+    assert_grads_close(got.cpu().numpy(), P.grads(x.astype(np.float64)), D.reshape(n, m, d), y, x, per / 64 + 8,
+                       m / 64 + 32, "long columns")
+
+
 def test_csr_unsorted_columns(gpu, oracle):
     """Columns in arbitrary order inside the rows: the library must notice and take its kernel that
     does not rely on ascending columns; same gradients."""
