@@ -27,7 +27,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
 # HBM bytes per launch of the dominant kernels, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
 # scaled by a plain 1 GiB copy's readings (summaries and commands under profiles/); not measured live.
 MEASURED_TRAFFIC_BYTES = {
-    "C2/grad_main": 817.1e6,       # profiles/ef21_step_C2_hbm_traffic_pmc.md
+    "C2/grad_main": 804.9e6,       # profiles/ef21_step_C2_hbm_traffic_pmc.md
+    "C4/topk_collect": 739.4e6,    # profiles/ef21_step_C4_hbm_traffic_pmc.md
 }
 
 
@@ -159,7 +160,8 @@ def bench_grads(torch, binding, workloads, steps: int, warmup: int):
            "iteration_frac_of_hbm_peak": round(it_bytes / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
            "topk_elements_per_s": round(n * d / (sum(v for k_, v in per_kernel.items() if k_.startswith("topk")) * 1e-3), 1)}
     dom = "topk_collect" if "topk_collect" in per_kernel else "topk_row"
-    out["roofline"] = roofline(8.0 * n * d, per_kernel[dom], f"{dom} (reads grad and g_i once)")
+    out["roofline"] = roofline(8.0 * n * d, per_kernel[dom], f"{dom} (reads grad and g_i once)",
+                               MEASURED_TRAFFIC_BYTES.get(f"C4/{dom}"))
     h.close()
     return out
 

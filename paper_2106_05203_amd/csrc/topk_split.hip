@@ -164,10 +164,14 @@ __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b
 // Per-wavefront staging ring in LDS: candidates are appended here and leave for the slot in global
 // memory 64 at a time, as one full-width store per array, instead of as many scattered 4-byte stores.
 // With UPDATE a candidate also carries b + v, the value g_i takes at its position if it is kept.
+#ifndef EF21_RING
+#define EF21_RING 128
+#endif
+constexpr uint32_t kRing = EF21_RING;        // entries of a staging ring (power of two, >= 128)
 struct StageRing {
-    int32_t idx[128];
-    float val[128];
-    float nxt[128];
+    int32_t idx[kRing];
+    float val[kRing];
+    float nxt[kRing];
 };
 
 struct SlotPtrs {
@@ -181,9 +185,9 @@ template <bool UPDATE>
 __device__ __forceinline__ void ring_to_slot(const StageRing &ring, uint32_t flushed, uint32_t count, int lane,
                                              const SlotPtrs &slot) {
     if ((uint32_t)lane < count) {
-        slot.idx[flushed + lane] = ring.idx[(flushed + lane) & 127u];
-        slot.val[flushed + lane] = ring.val[(flushed + lane) & 127u];
-        if (UPDATE) slot.nxt[flushed + lane] = ring.nxt[(flushed + lane) & 127u];
+        slot.idx[flushed + lane] = ring.idx[(flushed + lane) & (kRing - 1)];
+        slot.val[flushed + lane] = ring.val[(flushed + lane) & (kRing - 1)];
+        if (UPDATE) slot.nxt[flushed + lane] = ring.nxt[(flushed + lane) & (kRing - 1)];
     }
 }
 
@@ -224,18 +228,27 @@ __device__ __forceinline__ void append_candidates(const float (&v)[VEC], const f
 #pragma unroll
     for (int t = 0; t < VEC; ++t) {
         if (c[t]) {
-            ring.idx[pos & 127u] = (int32_t)(e0 + t);
-            ring.val[pos & 127u] = v[t];
-            if (UPDATE) ring.nxt[pos & 127u] = bv[t] + v[t];
+            ring.idx[pos & (kRing - 1)] = (int32_t)(e0 + t);
+            ring.val[pos & (kRing - 1)] = v[t];
+            if (UPDATE) ring.nxt[pos & (kRing - 1)] = bv[t] + v[t];
             ++pos;
         }
     }
     cnt += all;
-    if (cnt - flushed >= 64) {
+    if (cnt - flushed > kRing - 64) {        // keep room for the next step's candidates (at most 64)
         __builtin_amdgcn_wave_barrier();
         ring_to_slot<UPDATE>(ring, flushed, 64, lane, slot);
         flushed += 64;
     }
+}
+
+// Writes what is left in the ring at the end of a piece.
+template <bool UPDATE>
+__device__ __forceinline__ void drain_ring(const StageRing &ring, uint32_t flushed, uint32_t cnt, int lane,
+                                           const SlotPtrs &slot) {
+    __builtin_amdgcn_wave_barrier();
+    for (; flushed < cnt; flushed += 64)
+        ring_to_slot<UPDATE>(ring, flushed, cnt - flushed < 64 ? cnt - flushed : 64, lane, slot);
 }
 
 // A wavefront walks its piece in steps of 64*VEC entries (VEC = 4 needs 16-byte aligned rows), four
@@ -307,8 +320,7 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
         }
         append_candidates<VEC, false, UPDATE>(v, bv, e0, hi, key_lo, ring, lane, slot, cnt, flushed);
     }
-    __builtin_amdgcn_wave_barrier();
-    ring_to_slot<UPDATE>(ring, flushed, cnt - flushed, lane, slot);
+    drain_ring<UPDATE>(ring, flushed, cnt, lane, slot);
     if (lane == 0) w.slot_cnt[row * w.nslot + slot_no] = cnt;
 }
 
