@@ -1,8 +1,8 @@
 """GPU parity of the EF21 iteration (ef21_step through the C ABI) against the CPU oracle.
 
 Bars: messages (positions, values) and g_i bit-exact when both sides start from the same state and
-see the same gradients; g and x within 1e-5 relative per coordinate (g is summed with fp32 atomics,
-the oracle sums in fp64); f(x^t) within 1e-4 relative over a whole run with GPU-computed gradients.
+see the same gradients; g and x within 1e-5 relative per coordinate (the library sums the messages
+in fp32 in worker order, the oracle in fp64); f(x^t) within 1e-4 relative over a whole run with GPU-computed gradients.
 """
 import numpy as np
 import pytest
