@@ -186,12 +186,14 @@ int ensure_problem_buffers(ef21_ctx *c, size_t scratch_bytes) {
     return EF21_OK;
 }
 
-int enqueue_local_grad(ef21_ctx *c, const float *x, float *out) {
+// defer != nullptr: the dense gradient may stay in partial sums for the row Top-k kernel to finish.
+int enqueue_local_grad(ef21_ctx *c, const float *x, float *out, ef21::GradParts *defer = nullptr) {
     hipError_t st;
     const ef21::Marker mk = marker_of(c);
+    if (defer) *defer = ef21::GradParts();
     if (c->kind == kDense)
         st = ef21::launch_logreg_grad_dense(c->A, c->y, x, out, c->n, c->m, c->d, c->lambda, c->scratch, c->stream,
-                                            mk);
+                                            mk, defer);
     else
         st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->nnz,
                                           c->lambda, c->csr_indexed ? c->csr_index : nullptr, c->stream, mk);
@@ -423,12 +425,14 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
         mk(ef21::K_MODEL_STEP);
         if (st != hipSuccess) return fail_hip(st, "model step launch");
     }
+    ef21::GradParts parts;
     if (!grads) {
-        if (int rc = enqueue_local_grad(h, h->x, h->grad)) return rc;
+        const bool row_kernel = !(use_split(h->d) && h->topk_ws);
+        if (int rc = enqueue_local_grad(h, h->x, h->grad, row_kernel ? &parts : nullptr)) return rc;
         grads = h->grad;
     }
     // lines 5 and 6: Top-k of grads - g_i, fused with the update of g_i
-    ef21::TopkArgs p{grads, h->g_i, h->n, h->d, h->k, h->msg_idx, h->msg_val, h->g_i};
+    ef21::TopkArgs p{grads, h->g_i, h->n, h->d, h->k, h->msg_idx, h->msg_val, h->g_i, parts};
     if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk)) return rc;
     // line 8 from the messages, and (default order) line 3 in the same pass over the coordinates
     hipError_t st = ef21::launch_aggregate(h->msg_idx, h->msg_val, h->n, h->k, h->d, h->g, step_first ? nullptr : h->x,

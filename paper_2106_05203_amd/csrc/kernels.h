@@ -30,6 +30,16 @@ struct Marker {
     }
 };
 
+// A dense gradient of eq. (9) left as per-row-block partial sums part[n][chunks][d]: entry (i, j) is
+// dense_grad_entry(part + i * chunks * d, chunks, d, j, x[j], m, lambda) (logreg_finish.h).
+struct GradParts {
+    const float *part = nullptr;
+    int64_t chunks = 0;
+    int64_t m = 0;
+    const float *x = nullptr;
+    float lambda = 0.f;
+};
+
 // Arguments of one batched Top-k (Section 2.1) over n rows of length d.
 //   a, b      v = a - b if b != nullptr (the difference of Algorithm 2, line 5), else v = a
 //   out_idx, out_val   [n][k] ascending positions and signed values
@@ -44,6 +54,8 @@ struct TopkArgs {
     int32_t *out_idx;
     float *out_val;
     float *g_i;
+    GradParts parts;   // if parts.part != nullptr the rows of `a` are these unreduced gradients (`a` is not read);
+                       // launch_topk_row only, d <= 8192, b != nullptr
 };
 
 // One workgroup per row, four radix passes over the row plus an ordered emission.  Needs no
@@ -72,11 +84,13 @@ hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int
 // g = (1/n) sum_i g_i (input line of Algorithm 2), summed in worker order.
 hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hipStream_t stream);
 
-// Gradient of eq. (9) for all workers, dense rows.  scratch: logreg_dense_scratch_bytes.
+// Gradient of eq. (9) for all workers, dense rows.  scratch: logreg_dense_scratch_bytes.  With defer != nullptr
+// the last reduction may be left to the consumer: then *defer describes the partial sums (they live in
+// scratch until the next call) and grad is not written; defer->part == nullptr means grad was written.
 size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d);
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
                                     int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
-                                    const Marker &mk = Marker());
+                                    const Marker &mk = Marker(), GradParts *defer = nullptr);
 
 // Gradient of eq. (9) for all workers, CSR rows with nnz entries in all.  `index`
 // (logreg_csr_index_bytes bytes, owned by the caller) is built once per problem by logreg_csr_build_index

@@ -11,6 +11,7 @@
 // Dense rows, larger d: z = A x, then A^T r, two passes.  (CSR rows: logreg_csr.hip.)
 #include "device_utils.h"
 #include "kernels.h"
+#include "logreg_finish.h"
 
 namespace ef21 {
 namespace {
@@ -155,28 +156,14 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_atr_kernel(const float 
     part[(worker * chunks + chunk) * d + c] = acc;
 }
 
-// grad[i][j] = (sum over row blocks, in a fixed order) / m + regulariser gradient.
-// A workgroup covers 64 columns; its four wavefronts each add every fourth row block (fp64), and
-// the four sums are combined in wavefront order.
+// grad[i][j] from the partial sums: one thread per (worker, column).
 __global__ __launch_bounds__(kThreads) void logreg_dense_finish_kernel(const float *__restrict__ part,
                                                                        const float *__restrict__ x,
                                                                        float *__restrict__ grad, int64_t chunks,
                                                                        int64_t m, int64_t d, float lambda) {
-    __shared__ double red[kWaves][kWave];
     const int64_t worker = blockIdx.y;
-    const int lane = lane_id(), wave = threadIdx.x / kWave;
-    const int64_t c = (int64_t)blockIdx.x * kWave + lane;
-    double s = 0.0;
-    if (c < d)
-        for (int64_t k = wave; k < chunks; k += kWaves) s += (double)part[(worker * chunks + k) * d + c];
-    red[wave][lane] = s;
-    __syncthreads();
-    if (wave == 0 && c < d) {
-        double t = red[0][lane];
-        for (int w = 1; w < kWaves; ++w) t += red[w][lane];
-        const double xj = (double)x[c], q = 1.0 + xj * xj;
-        grad[worker * d + c] = (float)(t / (double)m + 2.0 * (double)lambda * xj / (q * q));
-    }
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (c < d) grad[worker * d + c] = dense_grad_entry(part + worker * chunks * d, chunks, d, c, x[c], m, lambda);
 }
 
 template <int VEC, int NQ>
@@ -196,7 +183,8 @@ size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d) {
 
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
                                     int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
-                                    const Marker &mk) {
+                                    const Marker &mk, GradParts *defer) {
+    if (defer) *defer = GradParts();
     const DensePlan pl = dense_plan(n, m);
     float *part = (float *)scratch;
     float *resid = part + (size_t)n * pl.chunks * d;
@@ -224,7 +212,11 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
     mk(K_GRAD_MAIN);
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;
-    hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kWave - 1) / kWave), (unsigned)n),
+    if (defer && fused) {      // the consumer finishes the sums itself (dense_grad_entry)
+        *defer = GradParts{part, pl.chunks, m, x, lambda};
+        return hipSuccess;
+    }
+    hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)n),
                        dim3(kThreads), 0, stream, part, x, grad, pl.chunks, m, d, lambda);
     mk(K_GRAD_AUX);
     return hipGetLastError();

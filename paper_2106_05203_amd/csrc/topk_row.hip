@@ -24,12 +24,25 @@ __global__ __launch_bounds__(kRowThreads) void topk_row_cached_kernel(TopkArgs p
     row_topk_cached<DIFF, UPDATE>(s, cache, p, blockIdx.x);
 }
 
+template <bool UPDATE>
+__global__ __launch_bounds__(kRowThreads) void topk_row_parts_kernel(TopkArgs p) {
+    __shared__ RowShared s;
+    __shared__ float cache[kRowCache];
+    row_topk_parts<UPDATE>(s, cache, p, blockIdx.x);
+}
+
 }  // namespace
 
 hipError_t launch_topk_row(const TopkArgs &p, hipStream_t stream) {
     const dim3 grid((unsigned)p.n), block(kRowThreads);
     const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
     if (upd && !diff) return hipErrorInvalidValue;   // line 6 needs the subtracted g_i
+    if (p.parts.part) {
+        if (!diff || p.d > kRowCache) return hipErrorInvalidValue;
+        if (upd) hipLaunchKernelGGL((topk_row_parts_kernel<true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((topk_row_parts_kernel<false>), grid, block, 0, stream, p);
+        return hipGetLastError();
+    }
     if (p.d <= kRowCache) {
         if (upd) hipLaunchKernelGGL((topk_row_cached_kernel<true, true>), grid, block, 0, stream, p);
         else if (diff) hipLaunchKernelGGL((topk_row_cached_kernel<true, false>), grid, block, 0, stream, p);

@@ -10,6 +10,7 @@
 #pragma once
 #include "device_utils.h"
 #include "kernels.h"
+#include "logreg_finish.h"
 
 namespace ef21 {
 
@@ -175,6 +176,19 @@ __device__ void row_topk_cached(RowShared &s, float *cache, const TopkArgs &p, i
     __syncthreads();
     row_topk_on<UPDATE>(
         s, p, row, [=](int64_t e) { return cache[e]; }, [=](int64_t e) { return DIFF ? b[e] : 0.f; });
+}
+
+// Same, the row being grad f_i - g_i with the gradient still in partial sums (p.parts).
+template <bool UPDATE>
+__device__ void row_topk_parts(RowShared &s, float *cache, const TopkArgs &p, int64_t row) {
+    const int64_t d = p.d;
+    const float *part_w = p.parts.part + row * p.parts.chunks * d;
+    const float *b = p.b + row * d;
+    for (int64_t e = threadIdx.x; e < d; e += kRowThreads)
+        cache[e] = dense_grad_entry(part_w, p.parts.chunks, d, e, p.parts.x[e], p.parts.m, p.parts.lambda) - b[e];
+    __syncthreads();
+    row_topk_on<UPDATE>(
+        s, p, row, [=](int64_t e) { return cache[e]; }, [=](int64_t e) { return b[e]; });
 }
 
 }  // namespace ef21

@@ -13,14 +13,14 @@
 //   then, on the candidates only, either
 //   select    (small k) one workgroup per row: candidate keys into LDS, radix select there, ordered
 //             emission of the k kept entries (+ line 6 of Algorithm 2); or
-//   hist x3, count, emit, rescue   (large k) the same steps spread over 16 workgroups per row,
+//   hist x3, count, emit   (large k) the same steps spread over several workgroups per row,
 //             chained by kernel boundaries: a kernel merges its LDS histograms into the row's
 //             global one with a few atomics per bin, the NEXT kernel's workgroups each scan the
 //             merged histogram in their prologue.
 //
 // The estimate can be wrong (fewer than k candidates); the row is then selected by the exact
-// one-workgroup algorithm on the original data (inside `select`, or by `rescue`), so the result
-// never depends on the sample.  Slots have the capacity of their piece, so any input fits.
+// one-workgroup algorithm on the original data (inside `select`, or by an extra workgroup of the
+// second `hist` kernel), so the result never depends on the sample.  Slots have the capacity of their piece, so any input fits.
 #include <cmath>
 
 #include "topk_row_impl.h"
@@ -35,10 +35,10 @@ constexpr int kSamplePer = kSample / kBlk;
 constexpr int kPieceLen = 256, kPieces = kSample / kPieceLen;
 constexpr int kMaxSlots = 4096;              // slots (wavefront pieces) per row
 constexpr int kSelCap = 28672;               // candidate keys the select kernel holds in LDS
-constexpr int kCandThreads = 256;            // count / emit workgroups (large k): one wavefront per slot
+constexpr int kCandThreads = 1024;           // count / emit workgroups (large k): one wavefront per slot
 constexpr int kCandWaves = kCandThreads / kWave;
-constexpr int kHistThreads = 512;            // candidate histogram workgroups (large k)
-constexpr int kCandBlocks = 16;              // ... of which each row gets this many
+constexpr int kHistThreads = kRowThreads;    // candidate histogram workgroups (large k)
+constexpr int kCandBlocks = 8;               // ... of which each row gets this many
 constexpr int kBins1 = 1 << kBits1, kBins2 = 1 << kBits2, kBins3 = 1 << kBits3;
 
 struct RowInfo {
@@ -325,6 +325,15 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
 }
 
 // ---------------------------------------------------------------- select (small k): one workgroup per row
+// Each wavefront owns a contiguous range of the row's slots, hence a contiguous range of the flat list
+// of candidates.  With W = the row's largest slot count rounded up to a power of two, a slot is cut into
+// units of min(W, 64) entries: one load instruction serves 64 / W slots if W < 64 (lane = slot * W +
+// entry) or one of the W / 64 steps of a slot otherwise; either way the lanes, the units of a batch and
+// the batches follow the candidate order, and kSlotBatch units are in flight together.  Rows with a slot
+// above kMaxUnitSlot candidates are walked slot by slot instead.
+constexpr int kSlotBatch = 8;
+constexpr uint32_t kMaxUnitSlot = 256;
+
 template <bool DIFF, bool UPDATE>
 __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
     __shared__ RowShared s;
@@ -335,20 +344,29 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
     const int nslot = (int)w.nslot;
     const uint32_t *slot_cnt = w.slot_cnt + row * w.nslot;
 
-    // exclusive scan of the slot counts: four consecutive slots per thread
+    // exclusive scan of the slot counts (four consecutive slots per thread) and their maximum
     constexpr int kPer = kMaxSlots / kBlk;
-    uint32_t c[kPer], mine = 0;
+    uint32_t c[kPer], mine = 0, largest = 0;
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
         const int sl = tid * kPer + j;
         c[j] = sl < nslot ? slot_cnt[sl] : 0u;
         mine += c[j];
+        largest = c[j] > largest ? c[j] : largest;
     }
     const uint32_t incl = wave_inclusive_scan(mine);
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const uint32_t other = __shfl_xor(largest, o, kWave);
+        largest = other > largest ? other : largest;
+    }
     if (lane == kWave - 1) s.wave_a[wave] = incl;
+    if (lane == 0) s.wave_b[wave] = largest;
     __syncthreads();
     uint32_t run = incl - mine;
     for (int v = 0; v < wave; ++v) run += s.wave_a[v];
+    largest = 0;
+    for (int v = 0; v < kBlkWaves; ++v) largest = s.wave_b[v] > largest ? s.wave_b[v] : largest;
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
         const int sl = tid * kPer + j;
@@ -363,35 +381,65 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
         return;
     }
 
-    // slot of flat candidate j: the last slot whose prefix is <= j
-    auto slot_of = [&](uint32_t j) {
-        int lo = 0, hi = nslot;                  // invariant: off[lo] <= j < off[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (off[mid] <= j) lo = mid;
-            else hi = mid;
-        }
-        return lo;
-    };
     const float *cand_val = w.cand_val + row * w.nslot * w.L;
     const int32_t *cand_idx = w.cand_idx + row * w.nslot * w.L;
     const float *cand_new = w.cand_new + row * w.nslot * w.L;
-    // flat position j -> address in the slots; kBatch independent loads in flight per thread
-    constexpr int kBatch = 8;
-    auto address_of = [&](uint32_t j) {
-        const int sl = slot_of(j);
-        return (int64_t)sl * w.L + (int64_t)(j - off[sl]);
-    };
-    for (uint32_t j0 = tid; j0 < M; j0 += kBlk * kBatch) {
-        int64_t at[kBatch];
-        float v[kBatch];
+    // this wavefront's slots [s0, s1) and candidates [lo, hi)
+    const int per_wave = (nslot + kBlkWaves - 1) / kBlkWaves;
+    const int s0 = wave * per_wave < nslot ? wave * per_wave : nslot;
+    const int s1 = s0 + per_wave < nslot ? s0 + per_wave : nslot;
+    const uint32_t lo = off[s0], hi = off[s1];
+    // the units (see above): either several slots per unit or several units per slot
+    uint32_t W = 1;
+    while (W < kMaxUnitSlot && W < largest) W <<= 1;
+    const int slots_per_unit = W < (uint32_t)kWave ? kWave / (int)W : 1;    // slots served by one unit
+    const int units_per_slot = W > (uint32_t)kWave ? (int)W / kWave : 1;    // units a slot is cut into
+    const int lanes_per_slot = W < (uint32_t)kWave ? (int)W : kWave;
+    const int my_slot = lane / lanes_per_slot;        // slot of this lane inside a unit
+    const uint32_t my_e = (uint32_t)(lane % lanes_per_slot);
+    const bool crowded = largest > kMaxUnitSlot;
+    const int n_units = (s1 - s0 + slots_per_unit - 1) / slots_per_unit * units_per_slot;
+    // unit t of this wavefront -> (slot, entry of this lane); slot >= s1 marks a lane without a slot
+    auto unit_slot = [&](int t) { return s0 + (t / units_per_slot) * slots_per_unit + my_slot; };
+    auto unit_entry = [&](int t) { return (uint32_t)(t % units_per_slot) * (uint32_t)kWave + my_e; };
+
+    // candidate keys into LDS
+    if (!crowded) {
+        for (int t0 = 0; t0 < n_units; t0 += kSlotBatch) {
+            float v[kSlotBatch];
+            uint32_t at_key[kSlotBatch];
+            bool in[kSlotBatch];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) at[u] = j0 + u * kBlk < M ? address_of(j0 + u * kBlk) : -1;
+            for (int u = 0; u < kSlotBatch; ++u) {
+                const int sl = unit_slot(t0 + u);
+                const uint32_t j = unit_entry(t0 + u);
+                const int slc = sl < s1 ? sl : s1 - 1;
+                const uint32_t first = off[slc], cnt = off[slc + 1] - first;
+                in[u] = t0 + u < n_units && sl < s1 && j < cnt;
+                at_key[u] = first + j;
+                v[u] = cand_val[(int64_t)slc * w.L + (in[u] ? j : 0u)];     // clamped: no load behind a branch
+            }
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) v[u] = at[u] >= 0 ? cand_val[at[u]] : 0.f;
+            for (int u = 0; u < kSlotBatch; ++u)
+                if (in[u]) keys[at_key[u]] = mag_key(v[u]);
+        }
+    } else {
+        for (int sl = s0; sl < s1; ++sl) {
+            const uint32_t first = off[sl], cnt = off[sl + 1] - first;
+            for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSlotBatch) {
+                float v[kSlotBatch];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u)
-            if (at[u] >= 0) keys[j0 + u * kBlk] = mag_key(v[u]);
+                for (int u = 0; u < kSlotBatch; ++u) {
+                    const uint32_t j = j0 + u * kWave + lane;
+                    v[u] = cand_val[(int64_t)sl * w.L + (j < cnt ? j : 0u)];
+                }
+#pragma unroll
+                for (int u = 0; u < kSlotBatch; ++u) {
+                    const uint32_t j = j0 + u * kWave + lane;
+                    if (j < cnt) keys[first + j] = mag_key(v[u]);
+                }
+            }
+        }
     }
     __syncthreads();
 
@@ -417,11 +465,7 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
     }
     const uint32_t T = prefix, q = need;
 
-    // ordered emission: each wavefront owns a contiguous range of the flat candidate list
-    uint32_t piece = (M + kBlkWaves - 1) / kBlkWaves;
-    piece = (piece + kWave - 1) / kWave * kWave;
-    const uint32_t lo = (uint32_t)wave * piece < M ? (uint32_t)wave * piece : M;
-    const uint32_t hi = lo + piece < M ? lo + piece : M;
+    // ordered emission: counts of this wavefront's range, prefix over the wavefronts ...
     uint32_t n_gt = 0, n_eq = 0;
     for (uint32_t base = lo; base < hi; base += kWave) {
         const uint32_t j = base + lane;
@@ -440,49 +484,69 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
         eq_run += s.wave_b[v];
     }
     uint32_t out_run = gt_before + (eq_run < q ? eq_run : q);
-    // first the output position of every kept candidate (LDS only; keys[j] is replaced by it) ...
-    constexpr uint32_t kDropped = 0xffffffffu;
-    for (uint32_t base = lo; base < hi; base += kWave) {
-        const uint32_t j = base + lane;
-        const bool in = j < hi;
-        const uint32_t key = in ? keys[j] : 0u;
+    int32_t *out_idx = p.out_idx + row * p.k;
+    float *out_val = p.out_val + row * p.k;
+    float *g_row = UPDATE ? p.g_i + row * p.d : nullptr;
+    // one step of the emission over 64 lanes in candidate order; `in` marks lanes that hold a candidate
+    auto emit_step = [&](bool in, uint32_t key, int32_t e, float v, float nx) {
         const bool gt = in && key > T, eq = in && key == T;
         const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
         const uint32_t eq_below = eq_run + lanes_below(m_eq);
         const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
-        const bool keep = gt || (eq && eq_below < q);
-        if (in) keys[j] = keep ? out_run + lanes_below(m_gt) + ties_before : kDropped;
+        if (gt || (eq && eq_below < q)) {
+            const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
+            out_idx[pos] = e;
+            out_val[pos] = v;
+            if (UPDATE) g_row[e] = nx;          // Algorithm 2, line 6
+        }
         const uint32_t eq_next = eq_run + popc64(m_eq);
         out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
         eq_run = eq_next;
-    }
-    __syncthreads();
-    // ... then the gather of (position, value) from the slots, kBatch loads in flight per thread
-    int32_t *out_idx = p.out_idx + row * p.k;
-    float *out_val = p.out_val + row * p.k;
-    for (uint32_t j0 = tid; j0 < M; j0 += kBlk * kBatch) {
-        int64_t at[kBatch];
-        uint32_t pos[kBatch];
-        int32_t e[kBatch];
-        float v[kBatch], nx[kBatch];
+    };
+    // ... then the slots in order: (position, value[, new g_i entry]) of a whole batch are loaded, then the
+    // kept ones written
+    if (!crowded) {
+        for (int t0 = 0; t0 < n_units; t0 += kSlotBatch) {
+            int32_t e[kSlotBatch];
+            float v[kSlotBatch], nx[kSlotBatch];
+            uint32_t key[kSlotBatch];
+            bool in[kSlotBatch];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const uint32_t j = j0 + u * kBlk;
-            pos[u] = j < M ? keys[j] : kDropped;
-            at[u] = pos[u] != kDropped ? address_of(j) : -1;
+            for (int u = 0; u < kSlotBatch; ++u) {
+                const int sl = unit_slot(t0 + u);
+                const uint32_t j = unit_entry(t0 + u);
+                const int slc = sl < s1 ? sl : s1 - 1;
+                const uint32_t first = off[slc], cnt = off[slc + 1] - first;
+                in[u] = t0 + u < n_units && sl < s1 && j < cnt;
+                const int64_t at = (int64_t)slc * w.L + (in[u] ? j : 0u);
+                e[u] = cand_idx[at];
+                v[u] = cand_val[at];
+                nx[u] = UPDATE ? cand_new[at] : 0.f;
+                key[u] = in[u] ? keys[first + j] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kSlotBatch; ++u) emit_step(in[u], key[u], e[u], v[u], nx[u]);
         }
+    } else {
+        for (int sl = s0; sl < s1; ++sl) {
+            const uint32_t first = off[sl], cnt = off[sl + 1] - first;
+            for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSlotBatch) {
+                int32_t e[kSlotBatch];
+                float v[kSlotBatch], nx[kSlotBatch];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            e[u] = at[u] >= 0 ? cand_idx[at[u]] : 0;
-            v[u] = at[u] >= 0 ? cand_val[at[u]] : 0.f;
-            nx[u] = UPDATE && at[u] >= 0 ? cand_new[at[u]] : 0.f;
-        }
+                for (int u = 0; u < kSlotBatch; ++u) {
+                    const uint32_t j = j0 + u * kWave + lane;
+                    const int64_t at = (int64_t)sl * w.L + (j < cnt ? j : 0u);
+                    e[u] = cand_idx[at];
+                    v[u] = cand_val[at];
+                    nx[u] = UPDATE ? cand_new[at] : 0.f;
+                }
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            if (at[u] < 0) continue;
-            out_idx[pos[u]] = e[u];
-            out_val[pos[u]] = v[u];
-            if (UPDATE) (p.g_i + row * p.d)[e[u]] = nx[u];      // Algorithm 2, line 6
+                for (int u = 0; u < kSlotBatch; ++u) {
+                    const uint32_t j = j0 + u * kWave + lane;
+                    emit_step(j < cnt, j < cnt ? keys[first + j] : 0u, e[u], v[u], nx[u]);
+                }
+            }
         }
     }
 }
@@ -544,16 +608,27 @@ __device__ void zero_global_hist(uint32_t *hist, int bins) {
 // (few, so that the merge below costs a few atomics per bin).  Prologue: the result of the previous
 // stage from the merged histogram.  Body: LDS histogram of this stage's digit over the workgroup's
 // slots, four slots in flight per wavefront, then merged into the row's global histogram.
-template <int STAGE>
+// Stage 2 has one more workgroup per row: if stage 1 found fewer than k candidates (the estimate
+// failed) it selects the row by the exact one-workgroup algorithm on the original data, while the
+// row's other workgroups, and the later kernels, leave the row alone.  (DIFF, UPDATE matter there only.)
+template <int STAGE, bool DIFF, bool UPDATE>
 __global__ __launch_bounds__(kHistThreads) void cand_hist_kernel(TopkArgs p, Ws w) {
     constexpr int NB = STAGE == 1 ? kBins1 : (STAGE == 2 ? kBins2 : kBins3);
     constexpr int SHIFT = STAGE == 1 ? kBits2 + kBits3 : (STAGE == 2 ? kBits3 : 0);
     constexpr int PSHIFT = STAGE == 1 ? 31 : (STAGE == 2 ? kBits2 + kBits3 : kBits3);
-    __shared__ uint32_t hist[NB];
+    __shared__ RowShared rs;
     __shared__ uint32_t lds_wave[kHistThreads / kWave], lds_out[2];
+    uint32_t *hist = rs.hist;
+    static_assert(NB <= (1 << kBits1), "the stage's histogram must fit the row algorithm's");
     const int64_t row = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     RowInfo *info = w.info + row;
+    if constexpr (STAGE == 2) {
+        if (blockIdx.x == kCandBlocks) {             // the rescue workgroup
+            if (info->failed) row_topk<DIFF, UPDATE>(rs, p, row);
+            return;
+        }
+    }
     const uint32_t *slot_cnt = w.slot_cnt + row * w.nslot;
     uint32_t prefix = 0;    // digits known so far
     if constexpr (STAGE == 1) {
@@ -653,29 +728,44 @@ __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws
     (void)p;
 }
 
-// Ordered emission, one wavefront per slot.  The wavefront first adds up the counts of all earlier
-// slots of its row (at most kMaxSlots of them, 64 per load), which gives its output offset and the
-// number of ties already used.
+// Ordered emission, one wavefront per slot.  The workgroup first adds up the counts of all slots of its
+// row before its own (at most kMaxSlots of them), which gives its output offset and the number of ties
+// already used; a wavefront then adds the counts of the workgroup's earlier slots.
 template <bool UPDATE>
 __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws w) {
+    __shared__ uint32_t before_gt[kCandWaves], before_eq[kCandWaves], own_gt[kCandWaves], own_eq[kCandWaves];
     const int64_t row = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const RowInfo *info = w.info + row;
-    if (info->failed) return;
+    if (info->failed) return;                                                     // the whole workgroup
     if (blockIdx.x == 0) zero_global_hist(w.hist3 + row * kBins3, kBins3);       // consumed by count
-    const int64_t sl = (int64_t)blockIdx.x * kCandWaves + wave;
-    if (sl >= w.nslot) return;
+    const int64_t sl0 = (int64_t)blockIdx.x * kCandWaves, sl = sl0 + wave;
+    const bool active = sl < w.nslot;
     const uint32_t T = info->T, q = info->q;
     const uint32_t *slot_gt = w.slot_gt + row * w.nslot, *slot_eq = w.slot_eq + row * w.nslot;
-    uint32_t gt_mine = 0, eq_mine = 0;
-    for (int64_t t = lane; t < sl; t += kWave) {
-        gt_mine += slot_gt[t];
-        eq_mine += slot_eq[t];
+    uint32_t gt_part = 0, eq_part = 0;
+    for (int64_t t = threadIdx.x; t < sl0; t += kCandThreads) {
+        gt_part += slot_gt[t];
+        eq_part += slot_eq[t];
     }
-    const uint32_t gt_run = wave_sum_u32(gt_mine);
-    uint32_t eq_run = wave_sum_u32(eq_mine);
+    const uint32_t mine_gt = active ? slot_gt[sl] : 0u, mine_eq = active ? slot_eq[sl] : 0u;
+    const uint32_t cnt = active ? w.slot_cnt[row * w.nslot + sl] : 0u;
+    gt_part = wave_sum_u32(gt_part);
+    eq_part = wave_sum_u32(eq_part);
+    if (lane == 0) {
+        before_gt[wave] = gt_part;
+        before_eq[wave] = eq_part;
+        own_gt[wave] = mine_gt;
+        own_eq[wave] = mine_eq;
+    }
+    __syncthreads();
+    if (!active) return;
+    uint32_t gt_run = 0, eq_run = 0;
+    for (int v = 0; v < kCandWaves; ++v) {
+        gt_run += before_gt[v] + (v < wave ? own_gt[v] : 0u);
+        eq_run += before_eq[v] + (v < wave ? own_eq[v] : 0u);
+    }
     uint32_t out_run = gt_run + (eq_run < q ? eq_run : q);
-    const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
     const int32_t *slot_idx = w.cand_idx + (row * w.nslot + sl) * w.L;
     const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
     const float *slot_new = w.cand_new + (row * w.nslot + sl) * w.L;
@@ -701,14 +791,6 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
         out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
         eq_run = eq_next;
     }
-}
-
-// Rows whose estimate failed are selected by the exact one-workgroup algorithm.
-template <bool DIFF, bool UPDATE>
-__global__ __launch_bounds__(kBlk) void split_rescue_kernel(TopkArgs p, Ws w) {
-    __shared__ RowShared s;
-    if (!w.info[blockIdx.x].failed) return;
-    row_topk<DIFF, UPDATE>(s, p, blockIdx.x);
 }
 
 __global__ __launch_bounds__(kCandThreads) void zero_words_kernel(uint32_t *p, size_t words) {
@@ -782,12 +864,14 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
         mk(K_TOPK_SELECT);
         return st;
     }
-    const dim3 hgrid(kCandBlocks, (unsigned)p.n), hblock(kHistThreads);
-    hipLaunchKernelGGL(cand_hist_kernel<1>, hgrid, hblock, 0, stream, p, w);
+    const dim3 hgrid(kCandBlocks, (unsigned)p.n), hgrid2(kCandBlocks + 1, (unsigned)p.n), hblock(kHistThreads);
+    hipLaunchKernelGGL((cand_hist_kernel<1, false, false>), hgrid, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
-    hipLaunchKernelGGL(cand_hist_kernel<2>, hgrid, hblock, 0, stream, p, w);
+    if (upd) hipLaunchKernelGGL((cand_hist_kernel<2, true, true>), hgrid2, hblock, 0, stream, p, w);
+    else if (diff) hipLaunchKernelGGL((cand_hist_kernel<2, true, false>), hgrid2, hblock, 0, stream, p, w);
+    else hipLaunchKernelGGL((cand_hist_kernel<2, false, false>), hgrid2, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
-    hipLaunchKernelGGL(cand_hist_kernel<3>, hgrid, hblock, 0, stream, p, w);
+    hipLaunchKernelGGL((cand_hist_kernel<3, false, false>), hgrid, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
     const dim3 grid((unsigned)((w.nslot + kCandWaves - 1) / kCandWaves), (unsigned)p.n), block(kCandThreads);
     hipLaunchKernelGGL(cand_count_kernel, grid, block, 0, stream, p, w);
@@ -795,10 +879,6 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
     if (upd) hipLaunchKernelGGL(cand_emit_kernel<true>, grid, block, 0, stream, p, w);
     else hipLaunchKernelGGL(cand_emit_kernel<false>, grid, block, 0, stream, p, w);
     mk(K_TOPK_EMIT);
-    if (upd) hipLaunchKernelGGL((split_rescue_kernel<true, true>), dim3((unsigned)p.n), dim3(kBlk), 0, stream, p, w);
-    else if (diff) hipLaunchKernelGGL((split_rescue_kernel<true, false>), dim3((unsigned)p.n), dim3(kBlk), 0, stream, p, w);
-    else hipLaunchKernelGGL((split_rescue_kernel<false, false>), dim3((unsigned)p.n), dim3(kBlk), 0, stream, p, w);
-    mk(K_TOPK_ROW);
     return hipGetLastError();
 }
 

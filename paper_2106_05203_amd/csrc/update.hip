@@ -135,11 +135,14 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const int32_t *__re
     }
 }
 
-// Small problems (d <= kSmallD, n * k <= kSmallEntries, n <= kSmallWorkers): one workgroup, one launch.
-// Every thread keeps up to 8 message entries in registers; the workers' entries are then added to the
-// LDS accumulator worker by worker (a barrier between workers, no memory access in that loop).
+// Small problems (d <= kSmallD, n * k <= kSmallEntries, n * ceil(k / 64) <= kSmallSteps): one workgroup, one launch.  All threads stage the
+// messages in LDS; then ONE wavefront adds them to the LDS accumulator worker by worker, 64 entries of a
+// worker per step (positions inside a message are distinct, and a wavefront's LDS accesses execute in
+// program order, so no barrier is needed between workers) while the other wavefronts fetch g and x.
 constexpr int kSmallThreads = 1024, kSmallPer = 8;
-constexpr int kSmallD = 16384, kSmallEntries = kSmallThreads * kSmallPer, kSmallWorkers = 256;
+constexpr int kSmallD = 16384, kSmallEntries = kSmallThreads * kSmallPer;
+constexpr int kSmallFetch = 4;      // coordinates per thread fetched ahead (d <= 4096)
+constexpr int kSmallSteps = 512;    // at most this many sequential steps of the adding wavefront
 
 template <bool STEP>
 __global__ __launch_bounds__(kSmallThreads) void aggregate_small_kernel(const int32_t *__restrict__ idx,
@@ -148,9 +151,11 @@ __global__ __launch_bounds__(kSmallThreads) void aggregate_small_kernel(const in
                                                                         float *__restrict__ x, float inv_n,
                                                                         float neg_gamma) {
     __shared__ float acc[kSmallD];
-    const int tid = threadIdx.x;
+    __shared__ int32_t m_idx[kSmallEntries];
+    __shared__ float m_val[kSmallEntries];
+    const int tid = threadIdx.x, lane = lane_id();
     const int64_t total = (int64_t)n * k;
-    int32_t e[kSmallPer], wk[kSmallPer];
+    int32_t e[kSmallPer];
     float v[kSmallPer];
 #pragma unroll
     for (int u = 0; u < kSmallPer; ++u) {
@@ -158,20 +163,54 @@ __global__ __launch_bounds__(kSmallThreads) void aggregate_small_kernel(const in
         const int64_t at = t < total ? t : 0;
         e[u] = idx[at];
         v[u] = val[at];
-        wk[u] = t < total ? (int32_t)(t / k) : -1;
     }
     for (int64_t j = tid; j < d; j += kSmallThreads) acc[j] = 0.f;
-    __syncthreads();
-    for (int32_t w = 0; w < n; ++w) {           // worker order; positions inside a message are distinct
 #pragma unroll
-        for (int u = 0; u < kSmallPer; ++u)
-            if (wk[u] == w) acc[e[u]] += v[u];
-        __syncthreads();
+    for (int u = 0; u < kSmallPer; ++u) {
+        const int64_t t = tid + (int64_t)u * kSmallThreads;
+        if (t < total) {
+            m_idx[t] = e[u];
+            m_val[t] = v[u];
+        }
     }
-    for (int64_t j = tid; j < d; j += kSmallThreads) {
-        const float gj = fmaf(acc[j], inv_n, g[j]);
-        g[j] = gj;
-        if (STEP) x[j] = fmaf(neg_gamma, gj, x[j]);
+    __syncthreads();
+    const bool ahead = d <= (int64_t)kSmallFetch * kSmallThreads;
+    float gj[kSmallFetch], xj[kSmallFetch];
+    if (tid < kWave) {
+        for (int32_t w = 0; w < n; ++w) {           // worker order
+            for (int64_t i0 = 0; i0 < k; i0 += kWave) {
+                const int64_t i = i0 + lane;
+                if (i < k) acc[m_idx[w * k + i]] += m_val[w * k + i];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+    if (ahead) {
+#pragma unroll
+        for (int u = 0; u < kSmallFetch; ++u) {
+            const int64_t j = tid + (int64_t)u * kSmallThreads;
+            gj[u] = j < d ? g[j] : 0.f;
+            xj[u] = STEP && j < d ? x[j] : 0.f;
+        }
+    }
+    __syncthreads();
+    if (ahead) {
+#pragma unroll
+        for (int u = 0; u < kSmallFetch; ++u) {
+            const int64_t j = tid + (int64_t)u * kSmallThreads;
+            if (j < d) {
+                const float gn = fmaf(acc[j], inv_n, gj[u]);
+                g[j] = gn;
+                if (STEP) x[j] = fmaf(neg_gamma, gn, xj[u]);
+            }
+        }
+    } else {
+        for (int64_t j = tid; j < d; j += kSmallThreads) {
+            const float gn = fmaf(acc[j], inv_n, g[j]);
+            g[j] = gn;
+            if (STEP) x[j] = fmaf(neg_gamma, gn, x[j]);
+        }
     }
 }
 
@@ -203,7 +242,7 @@ size_t aggregate_index_bytes(int32_t n, int64_t d) {
 hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int64_t k, int64_t d, float *g, float *x,
                             float gamma, void *index, hipStream_t stream) {
     const float inv_n = 1.0f / (float)n;
-    if (d <= kSmallD && (int64_t)n * k <= kSmallEntries && n <= kSmallWorkers) {
+    if (d <= kSmallD && (int64_t)n * k <= kSmallEntries && (int64_t)n * ((k + kWave - 1) / kWave) <= kSmallSteps) {
         if (x)
             hipLaunchKernelGGL(aggregate_small_kernel<true>, dim3(1), dim3(kSmallThreads), 0, stream, idx, val, n, k, d,
                                g, x, inv_n, -gamma);

@@ -86,6 +86,31 @@ def test_single_step_from_oracle_state(gpu, oracle, n, d, k, order):
             budget.reset()
 
 
+@pytest.mark.parametrize("k", [5000, 60000])
+def test_step_when_the_sample_misleads(gpu, oracle, k):
+    """Long rows whose large differences sit exactly on the 32 sampled pieces: the candidate threshold
+    guessed from the sample keeps fewer than k candidates and the exact per-row algorithm takes over,
+    inside the step (difference, state update) for the small-k and the large-k candidate stage."""
+    torch, binding = gpu
+    n, d, gamma = 2, 300_000, 0.25
+    print(f"misleading sample step k={k}", flush=True)
+    rng = np.random.default_rng(k)
+    g_i0 = (rng.standard_normal((n, d)) * 1e-3).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+    grads = (g_i0 + 1e-3 * rng.standard_normal((n, d))).astype(np.float32)
+    pos = np.concatenate([(p * (d - 256)) // 31 + np.arange(256) for p in range(32)])
+    grads[:, pos] += (1.0 + rng.random((n, pos.size))).astype(np.float32)
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    budget = RoundingBudget(n, d, gamma)
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+        oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma)
+        h.step(to_gpu(torch, grads))
+        torch.cuda.synchronize()
+        compare_state(torch, h, st, budget)
+
+
 def test_first_pass_compresses_zero_vector(gpu, oracle):
     """g_i^0 = grad: the first grad-first pass sees v = 0; k zero-valued pairs at positions 0..k-1
     are emitted and the state does not change."""
