@@ -31,9 +31,11 @@ constexpr int kAtrThreads = 1024;
 constexpr int kAtrWaves = kAtrThreads / kWave;
 constexpr int kCscThreads = 512;      // pass 2
 constexpr int kCscWaves = kCscThreads / kWave;
-constexpr int kCscGroups = 4;         // groups of 64 columns per wavefront
+constexpr int kCscGroups = 4;         // groups of 64 consecutive columns per wavefront
 constexpr int kCscCols = kCscWaves * kCscGroups * kWave;   // columns per workgroup
-constexpr int kTile = 1024;           // staged products per wavefront
+constexpr int kTile = 1024;           // staged products per wavefront: four loads of four entries per lane
+constexpr int64_t kCscPad = 2048;     // zeroed entries after the column-major copy (tiles are loaded whole)
+constexpr int64_t kIdx16Rows = 65536; // m up to this: 16-bit row indices in the column-major copy
 constexpr int kLongColumn = 48;       // a longer piece of a column inside one tile is summed by the whole wavefront
 constexpr int64_t kCoefLdsRows = 16384;   // m up to this: coef vector in LDS (64 KB)
 constexpr int kRangeCols = 12288;     // at most this many columns per range (48 KB of LDS as fp32)
@@ -54,8 +56,8 @@ struct IndexLayout {
     int32_t *split;     // [R + 1][rows] offsets of the column ranges inside each row
     float *coef;        // [rows] r_l / m
     int32_t *colptr;    // [n][d + 1] CSC column starts, relative to the worker's first non-zero
-    int32_t *csc_row;   // [nnz] row inside the worker
-    float *csc_val;     // [nnz]
+    void *csc_row;      // [nnz + kCscPad] row inside the worker: uint16 if m <= kIdx16Rows, else int32
+    float *csc_val;     // [nnz + kCscPad]
     int R;
     int64_t Wc;
 };
@@ -76,15 +78,15 @@ size_t index_layout(int32_t n, int64_t m, int64_t d, int64_t nnz, char *base, In
     char *s = take(sizeof(int32_t) * (size_t)rows * (R + 1));   // [R + 1][rows]
     char *cf = take(sizeof(float) * (size_t)rows);
     char *cp = take(sizeof(int32_t) * (size_t)n * (d + 1));
-    char *cr = take(sizeof(int32_t) * (size_t)nnz);
-    char *cv = take(sizeof(float) * (size_t)nnz);
+    char *cr = take((m <= kIdx16Rows ? sizeof(uint16_t) : sizeof(int32_t)) * (size_t)(nnz + kCscPad));
+    char *cv = take(sizeof(float) * (size_t)(nnz + kCscPad));
     if (out) {
         out->bad = (uint32_t *)b;
         out->zpart = (float *)c;
         out->split = (int32_t *)s;
         out->coef = (float *)cf;
         out->colptr = (int32_t *)cp;
-        out->csc_row = (int32_t *)cr;
+        out->csc_row = (void *)cr;
         out->csc_val = (float *)cv;
         out->R = (int)R;
         out->Wc = Wc;
@@ -184,30 +186,43 @@ __global__ __launch_bounds__(kAtrThreads) void csr_dot_kernel(const int64_t *__r
     const int64_t width = c0 + Wc < d ? Wc : d - c0;
     for (int64_t j = threadIdx.x; j < width; j += kAtrThreads) lds[j] = x[c0 + j];
     __syncthreads();
-    for (int64_t l0 = (int64_t)wave * kRows; l0 < m; l0 += (int64_t)kAtrWaves * kRows) {
-        const SliceBounds mine = batch_bounds(rowptr, split, rows, range, worker, m, l0, lane);
+    // the bounds of the next batch are fetched while the current one is worked on; two steps of 64 entries
+    // per row are loaded together (a slice of the usual length is then one round trip)
+    constexpr int kSteps = 2;
+    const int64_t stride = (int64_t)kAtrWaves * kRows;
+    int64_t l0 = (int64_t)wave * kRows;
+    SliceBounds next = batch_bounds(rowptr, split, rows, range, worker, m, l0 < m ? l0 : 0, lane);
+    for (; l0 < m; l0 += stride) {
+        const SliceBounds mine = next;
+        if (l0 + stride < m) next = batch_bounds(rowptr, split, rows, range, worker, m, l0 + stride, lane);
         const int32_t longest = batch_longest(mine.len);
         float s[kRows];
 #pragma unroll
         for (int u = 0; u < kRows; ++u) s[u] = 0.f;
-        for (int32_t t0 = 0; t0 < longest; t0 += kWave) {
-            int32_t c[kRows];
-            float v[kRows];
-            bool in[kRows];
+        for (int32_t t0 = 0; t0 < longest; t0 += kSteps * kWave) {
+            int32_t c[kSteps][kRows];
+            float v[kSteps][kRows];
+            bool in[kSteps][kRows];
 #pragma unroll
             for (int u = 0; u < kRows; ++u) {
                 const int64_t b = __shfl(mine.b, u, kWave);
                 const int32_t len = __shfl(mine.len, u, kWave);
-                in[u] = t0 + lane < len;
-                const int64_t at = b + (in[u] ? t0 + lane : (len > 0 ? len - 1 : 0));
-                c[u] = len > 0 ? stream_load(col + at) : (int32_t)c0;
-                v[u] = len > 0 ? stream_load(val + at) : 0.f;
+#pragma unroll
+                for (int q = 0; q < kSteps; ++q) {
+                    const int32_t t = t0 + q * kWave + lane;
+                    in[q][u] = t < len;
+                    const int64_t at = b + (in[q][u] ? t : (len > 0 ? len - 1 : 0));
+                    c[q][u] = len > 0 ? stream_load(col + at) : (int32_t)c0;
+                    v[q][u] = len > 0 ? stream_load(val + at) : 0.f;
+                }
             }
 #pragma unroll
-            for (int u = 0; u < kRows; ++u) {
-                const float xv = lds[c[u] - c0];
-                if (in[u]) s[u] = fmaf(v[u], xv, s[u]);
-            }
+            for (int q = 0; q < kSteps; ++q)
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) {
+                    const float xv = lds[c[q][u] - c0];
+                    if (in[q][u]) s[u] = fmaf(v[q][u], xv, s[u]);
+                }
         }
 #pragma unroll
         for (int u = 0; u < kRows; ++u) {
@@ -278,12 +293,13 @@ __global__ __launch_bounds__(kAtrThreads) void csc_count_kernel(const int64_t *_
 // order and hands out the positions inside each column from a cursor in LDS (the columns of a row are
 // distinct, so the lanes of one step never meet), which makes the order inside a column -- hence the
 // order of the floating-point sums of pass 2 -- a function of the matrix alone.  Dynamic LDS: Wc words.
+template <class RowIndex>
 __global__ __launch_bounds__(kWave) void csc_fill_kernel(const int64_t *__restrict__ rowptr,
                                                          const int32_t *__restrict__ col,
                                                          const float *__restrict__ val,
                                                          const int32_t *__restrict__ split,
                                                          const int32_t *__restrict__ colptr,
-                                                         int32_t *__restrict__ csc_row, float *__restrict__ csc_val,
+                                                         RowIndex *__restrict__ csc_row, float *__restrict__ csc_val,
                                                          int64_t m, int64_t d, int64_t Wc) {
     extern __shared__ uint32_t cursor[];
     const int range = blockIdx.x;
@@ -315,7 +331,7 @@ __global__ __launch_bounds__(kWave) void csc_fill_kernel(const int64_t *__restri
                 if (in[u]) {
                     const uint32_t pos = cursor[c[u] - c0];
                     cursor[c[u] - c0] = pos + 1u;
-                    csc_row[first + pos] = (int32_t)(l0 + u);
+                    csc_row[first + pos] = (RowIndex)(l0 + u);
                     csc_val[first + pos] = v[u];
                 }
             }
@@ -336,16 +352,21 @@ __global__ __launch_bounds__(kThreads) void csr_coef_kernel(const float *__restr
 }
 
 // ---- pass 2: gradient columns from the column-major copy.  Dynamic LDS: m floats if COEF_LDS.
-template <bool COEF_LDS>
+// A wavefront owns 256 consecutive columns (four groups of 64, lane j the columns j, j + 64, ...), whose
+// entries are one contiguous span of the copy.  The span is walked in tiles of 1024 entries aligned to
+// four entries: each lane loads four times four consecutive (row, value) pairs, all loads of the tile
+// in flight together, multiplies by coef[row] and stages the products in LDS; then every lane adds, for
+// each of its columns, the piece of the column that lies in the tile, in storage order.
+template <bool COEF_LDS, class RowIndex>
 __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__restrict__ colptr,
-                                                               const int32_t *__restrict__ csc_row,
+                                                               const RowIndex *__restrict__ csc_row,
                                                                const float *__restrict__ csc_val,
                                                                const int64_t *__restrict__ rowptr,
                                                                const float *__restrict__ coef,
                                                                const float *__restrict__ x, float *__restrict__ grad,
                                                                int64_t m, int64_t d, float lambda) {
     extern __shared__ float coef_lds[];
-    __shared__ float tiles[kCscWaves][kTile];
+    __shared__ __attribute__((aligned(16))) float tiles[kCscWaves][kTile];
     const int64_t worker = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const float *cf = coef + worker * m;
@@ -353,61 +374,77 @@ __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__
         for (int64_t l = threadIdx.x; l < m; l += kCscThreads) coef_lds[l] = cf[l];
         __syncthreads();
     }
+    const int64_t cb = ((int64_t)blockIdx.x * kCscWaves + wave) * (kCscGroups * kWave);
+    if (cb >= d) return;                                        // the whole wavefront; no barrier follows
     const int64_t first = rowptr[worker * m];
-    const int32_t *rw = csc_row + first;
-    const float *vl = csc_val + first;
     const int32_t *cp = colptr + worker * (d + 1);
     float *tile = tiles[wave];
 
+    int64_t b[kCscGroups], e[kCscGroups];                      // global entry ranges of this lane's columns
+#pragma unroll
     for (int g = 0; g < kCscGroups; ++g) {
-        const int64_t cb = ((int64_t)blockIdx.x * kCscGroups + g) * (kCscWaves * kWave) + wave * kWave;
-        if (cb >= d) break;                                    // uniform in the wavefront
-        const bool has_col = cb + lane < d;                    // lanes past d hold an empty piece at the end
-        const int32_t b = cp[has_col ? cb + lane : d], e = cp[has_col ? cb + lane + 1 : d];
-        const int32_t B = __shfl(b, 0, kWave), E = __shfl(e, kWave - 1, kWave);
-        float acc = 0.f;
-        for (int32_t t0 = B; t0 < E; t0 += kTile) {
-            // stage the products of up to kTile entries, 256 at a time, all loads of a block in flight
-            constexpr int kUnroll = 4;
-            for (int32_t s0 = 0; s0 < kTile && t0 + s0 < E; s0 += kUnroll * kWave) {
-                int32_t r[kUnroll];
-                float v[kUnroll];
+        const int64_t c = cb + g * kWave + lane;
+        b[g] = first + cp[c < d ? c : d];                      // columns past d: an empty range at the end
+        e[g] = first + cp[c < d ? c + 1 : d];
+    }
+    const int64_t span_b = __shfl(b[0], 0, kWave), span_e = __shfl(e[kCscGroups - 1], kWave - 1, kWave);
+    float acc[kCscGroups];
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    const int32_t t = t0 + s0 + u * kWave + lane;
-                    const int32_t at = t < E ? t : E - 1;       // clamped: no load behind a branch
-                    r[u] = stream_load(rw + at);
-                    v[u] = stream_load(vl + at);
-                }
+    for (int g = 0; g < kCscGroups; ++g) acc[g] = 0.f;
+
+    constexpr int kLoads = kTile / (4 * kWave);                // 4
+    const int64_t last4 = (span_e - 1) & ~(int64_t)3;          // last aligned quad that holds an entry of the span
+    for (int64_t t0 = span_b & ~(int64_t)3; t0 < span_e; t0 += kTile) {
+        typedef float v4f __attribute__((ext_vector_type(4)));
+        typedef RowIndex v4r __attribute__((ext_vector_type(4)));
+        v4r r[kLoads];
+        v4f v[kLoads];
 #pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    const float c = COEF_LDS ? coef_lds[r[u]] : cf[r[u]];
-                    tile[s0 + u * kWave + lane] = v[u] * c;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            // every lane adds the piece of its column that lies in this tile, in storage order
-            const int32_t t1 = t0 + kTile < E ? t0 + kTile : E;
-            const int32_t lo = b > t0 ? b : t0, hi = e < t1 ? e : t1;
+        for (int u = 0; u < kLoads; ++u) {
+            int64_t at = t0 + u * (4 * kWave) + 4 * lane;
+            at = at < last4 ? at : last4;                      // clamped (re-reads the last quad): no load behind a branch
+            r[u] = __builtin_nontemporal_load(reinterpret_cast<const v4r *>(csc_row + at));
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(csc_val + at));
+        }
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            v4f pr;
+            pr.x = v[u].x * (COEF_LDS ? coef_lds[r[u].x] : cf[r[u].x]);
+            pr.y = v[u].y * (COEF_LDS ? coef_lds[r[u].y] : cf[r[u].y]);
+            pr.z = v[u].z * (COEF_LDS ? coef_lds[r[u].z] : cf[r[u].z]);
+            pr.w = v[u].w * (COEF_LDS ? coef_lds[r[u].w] : cf[r[u].w]);
+            *reinterpret_cast<v4f *>(tile + u * (4 * kWave) + 4 * lane) = pr;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int64_t t1 = t0 + kTile < span_e ? t0 + kTile : span_e;
+#pragma unroll
+        for (int g = 0; g < kCscGroups; ++g) {
+            const int64_t lo64 = b[g] > t0 ? b[g] : t0, hi64 = e[g] < t1 ? e[g] : t1;
+            const int32_t lo = (int32_t)(lo64 - t0), hi = (int32_t)(hi64 - t0);     // tile coordinates; hi <= lo: nothing
+            if (__ballot(lo < hi) == 0) continue;              // the group has nothing in this tile (uniform)
             const bool is_long = hi - lo > kLongColumn;
             if (!is_long)
-                for (int32_t t = lo; t < hi; ++t) acc += tile[t - t0];
+                for (int32_t t = lo; t < hi; ++t) acc[g] += tile[t];
             uint64_t todo = __ballot(is_long);
-            while (todo) {                                       // uniform in the wavefront
+            while (todo) {                                     // uniform in the wavefront
                 const int src = __ffsll((long long)todo) - 1;
                 todo &= todo - 1;
                 const int32_t L = __shfl(lo, src, kWave), H = __shfl(hi, src, kWave);
                 float part = 0.f;
-                for (int32_t t = L + lane; t < H; t += kWave) part += tile[t - t0];
+                for (int32_t t = L + lane; t < H; t += kWave) part += tile[t];
                 part = wave_sum(part);
-                if (lane == src) acc += part;
+                if (lane == src) acc[g] += part;
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
         }
-        if (cb + lane < d) grad[worker * d + cb + lane] = acc + regulariser_grad(x[cb + lane], lambda);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+#pragma unroll
+    for (int g = 0; g < kCscGroups; ++g) {
+        const int64_t c = cb + g * kWave + lane;
+        if (c < d) grad[worker * d + c] = acc[g] + regulariser_grad(x[c], lambda);
     }
 }
 
@@ -482,8 +519,17 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
     const size_t lds_bytes = sizeof(uint32_t) * (size_t)ix.Wc;
     hipLaunchKernelGGL(csc_count_kernel, grid, dim3(kAtrThreads), lds_bytes, stream, rowptr, col, ix.split, ix.colptr,
                        m, d, ix.R, ix.Wc);
-    hipLaunchKernelGGL(csc_fill_kernel, grid, dim3(kWave), lds_bytes, stream, rowptr, col, val, ix.split, ix.colptr,
-                       ix.csc_row, ix.csc_val, m, d, ix.Wc);
+    const bool idx16 = m <= kIdx16Rows;
+    const size_t row_bytes = idx16 ? sizeof(uint16_t) : sizeof(int32_t);
+    st = hipMemsetAsync((char *)ix.csc_row + row_bytes * (size_t)nnz, 0, row_bytes * (size_t)kCscPad, stream);
+    if (st == hipSuccess) st = hipMemsetAsync(ix.csc_val + nnz, 0, sizeof(float) * (size_t)kCscPad, stream);
+    if (st != hipSuccess) return st;
+    if (idx16)
+        hipLaunchKernelGGL(csc_fill_kernel<uint16_t>, grid, dim3(kWave), lds_bytes, stream, rowptr, col, val, ix.split,
+                           ix.colptr, (uint16_t *)ix.csc_row, ix.csc_val, m, d, ix.Wc);
+    else
+        hipLaunchKernelGGL(csc_fill_kernel<int32_t>, grid, dim3(kWave), lds_bytes, stream, rowptr, col, val, ix.split,
+                           ix.colptr, (int32_t *)ix.csc_row, ix.csc_val, m, d, ix.Wc);
     st = hipStreamSynchronize(stream);
     if (st != hipSuccess) return st;
     *usable = true;
@@ -502,7 +548,7 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
             hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csr_dot_kernel),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, sizeof(float) * kRangeCols);
             if (st == hipSuccess)
-                st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csc_grad_kernel<true>),
+                st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csc_grad_kernel<true, uint16_t>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, sizeof(float) * kCoefLdsRows);
             if (st != hipSuccess) return st;
             configured = true;
@@ -514,12 +560,16 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
                            stream, y, ix.zpart, ix.R, rows, 1.0f / (float)m, ix.coef);
         mk(K_GRAD_AUX);
         const dim3 grid((unsigned)((d + kCscCols - 1) / kCscCols), (unsigned)n);
+        static_assert(kCoefLdsRows <= kIdx16Rows, "a coefficient vector that fits LDS has 16-bit row indices");
         if (m <= kCoefLdsRows)
-            hipLaunchKernelGGL(csc_grad_kernel<true>, grid, dim3(kCscThreads), sizeof(float) * (size_t)m, stream,
-                               ix.colptr, ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
+            hipLaunchKernelGGL((csc_grad_kernel<true, uint16_t>), grid, dim3(kCscThreads), sizeof(float) * (size_t)m, stream,
+                               ix.colptr, (const uint16_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
+        else if (m <= kIdx16Rows)
+            hipLaunchKernelGGL((csc_grad_kernel<false, uint16_t>), grid, dim3(kCscThreads), 0, stream, ix.colptr,
+                               (const uint16_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
         else
-            hipLaunchKernelGGL(csc_grad_kernel<false>, grid, dim3(kCscThreads), 0, stream, ix.colptr, ix.csc_row,
-                               ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
+            hipLaunchKernelGGL((csc_grad_kernel<false, int32_t>), grid, dim3(kCscThreads), 0, stream, ix.colptr,
+                               (const int32_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
         mk(K_GRAD_MAIN);
         return hipGetLastError();
     }

@@ -111,11 +111,11 @@ def test_csr_ragged_rows(gpu, oracle):
 
 
 @pytest.mark.parametrize("n,m,d,always,extra", [(2, 1500, 200, (0, 5, 199), 6), (1, 17000, 70, (1,), 3),
-                                                (3, 100, 13000, (12287, 12288), 40)])
+                                                (3, 100, 13000, (12287, 12288), 40), (1, 70000, 70, (69,), 2)])
 def test_csr_long_columns_many_rows(gpu, oracle, n, m, d, always, extra):
     """Columns present in every row (pieces of a column longer than a staging tile, summed by the whole
-    wavefront), more rows per worker than the in-LDS coefficient vector holds, columns next to a range
-    boundary; and the sorted-CSR gradient is bitwise reproducible."""
+    wavefront), more rows per worker than the in-LDS coefficient vector holds, more than 16-bit row
+    indices hold, columns next to a range boundary; and the sorted-CSR gradient is bitwise reproducible."""
     torch, binding = gpu
     print(f"csr long columns case n={n} m={m} d={d}", flush=True)
     rng = np.random.default_rng(m + d)
