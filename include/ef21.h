@@ -95,10 +95,10 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
  * Allocates a gradient buffer [n][d] and scratch on first use.  The csr call also reads the matrix
  * once (it waits for the stream): if every row's columns are strictly ascending and inside [0, d),
  * and no worker holds 2^31 - 2^16 entries or more, it builds what the fast two-pass gradient kernels
- * need -- a small per-row index of column ranges and a column-major copy of each worker's block
- * (8 bytes per entry plus 4 n (d + 1) bytes of device memory, owned by the handle).  Otherwise a
- * slower kernel based on global floating-point atomics is used, in which columns outside [0, d) are
- * skipped.
+ * need -- a small per-row index of column ranges and two re-ordered copies of the matrix with 16-bit
+ * indices (about 12 bytes per entry plus 4 n (d + 1) + 4 (n m + n) ceil(d / 12288) bytes of device
+ * memory in all, owned by the handle).  Otherwise a slower kernel based on global floating-point
+ * atomics is used, in which columns outside [0, d) are skipped.
  */
 int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_t m, float lambda);
 int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *col, const float *val,

@@ -94,8 +94,8 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
 
 // Gradient of eq. (9) for all workers, CSR rows with nnz entries in all.  `index`
 // (logreg_csr_index_bytes bytes, owned by the caller) is built once per problem by logreg_csr_build_index
-// and holds per-row column-range offsets, a column-major copy of each worker's block (8 bytes per entry)
-// and scratch for the two-pass kernels.  The build synchronises the stream and reports whether those
+// and holds per-row column-range offsets, a range-major and a column-major copy of the matrix (6 bytes per
+// entry each) and scratch for the two-pass kernels.  The build synchronises the stream and reports whether those
 // kernels can be used (every row's columns ascending and inside [0, d), fewer than 2^31 entries per
 // worker); pass index = nullptr to launch_logreg_grad_csr otherwise.
 size_t logreg_csr_index_bytes(int32_t n, int64_t m, int64_t d, int64_t nnz);

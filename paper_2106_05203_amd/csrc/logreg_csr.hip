@@ -5,19 +5,18 @@
 // a scatter-add into the gradient.  Served from L2 they move a whole cache line per entry and are an
 // order of magnitude off the bandwidth roofline; global float atomics are worse still, and LDS float
 // atomics are slow too.  So each half is arranged to read a short vector held in LDS and to write
-// nothing at random.  Needs every row's column indices ascending (checked once, when the problem is
-// attached); what is built at attach time:
-//   - the columns are cut into R = ceil(d / 12288) ranges, and `split` holds where each range starts
-//     inside each row, so a range's slice of a row is contiguous;
-//   - a column-major copy (CSC) of each worker's block of the matrix: colptr, row index, value.
-// Per gradient, two streaming passes over the non-zeros:
-//   pass 1 (CSR)  one workgroup per (range, worker), x-range in LDS; one wavefront per row slice:
-//                 partial dot product z_part[range][row]
-//   coef          coef_l = r_l / m from the summed partial dot products (one thread per row)
-//   pass 2 (CSC)  the worker's coef vector (m floats) in LDS; a wavefront owns 64 consecutive columns,
-//                 loads their entries coalesced, multiplies by coef[row] and stages the products in LDS,
-//                 where every lane sums its own column in storage order -- no atomics, bitwise
-//                 reproducible -- and adds the regulariser term
+// nothing at random, from its own copy of the matrix.  Needs every row's column indices ascending
+// (checked once, when the problem is attached); what is built at attach time, 6 bytes per entry each:
+//   - a range-major copy: the columns are cut into R = ceil(d / 12288) ranges; per (range, worker) the
+//     rows' slices of that range one after the other, as (16-bit column inside the range, value);
+//   - a column-major copy (CSC) of each worker's block: (16-bit row inside the worker, value)
+//     (32-bit rows if a worker has more than 65536 of them).
+// Per gradient, two streaming passes, both the same segmented sum (segment_sums below):
+//   pass 1  segments = row slices, vector = the range of x in LDS: partial dot products z_part[range][row]
+//   coef    coef_l = r_l / m from the summed partial dot products (one thread per row)
+//   pass 2  segments = columns, vector = the worker's coef (m floats) in LDS: the gradient entries,
+//           plus the regulariser term
+// No atomics; every sum is taken in a fixed order (bitwise reproducible).
 // Unsorted rows, or d too large for the index, fall back to a kernel built on global atomics.
 #include "device_utils.h"
 #include "kernels.h"
@@ -36,7 +35,7 @@ constexpr int kCscCols = kCscWaves * kCscGroups * kWave;   // columns per workgr
 constexpr int kTile = 1024;           // staged products per wavefront: four loads of four entries per lane
 constexpr int64_t kCscPad = 2048;     // zeroed entries after the column-major copy (tiles are loaded whole)
 constexpr int64_t kIdx16Rows = 65536; // m up to this: 16-bit row indices in the column-major copy
-constexpr int kLongColumn = 48;       // a longer piece of a column inside one tile is summed by the whole wavefront
+constexpr int kLongColumn = 128;      // a longer piece of a segment inside one tile is summed by the whole wavefront
 constexpr int64_t kCoefLdsRows = 16384;   // m up to this: coef vector in LDS (64 KB)
 constexpr int kRangeCols = 12288;     // at most this many columns per range (48 KB of LDS as fp32)
 constexpr int kMaxRanges = 64;
@@ -58,6 +57,10 @@ struct IndexLayout {
     int32_t *colptr;    // [n][d + 1] CSC column starts, relative to the worker's first non-zero
     void *csc_row;      // [nnz + kCscPad] row inside the worker: uint16 if m <= kIdx16Rows, else int32
     float *csc_val;     // [nnz + kCscPad]
+    int64_t *bstart;    // [R][n] first entry of the (range, worker) block of the range-major copy
+    int32_t *rptr;      // [R][n][m + 1] start of each row's slice inside its block
+    uint16_t *rcol;     // [nnz + kCscPad] column minus the range's first column
+    float *rval;        // [nnz + kCscPad]
     int R;
     int64_t Wc;
 };
@@ -80,6 +83,10 @@ size_t index_layout(int32_t n, int64_t m, int64_t d, int64_t nnz, char *base, In
     char *cp = take(sizeof(int32_t) * (size_t)n * (d + 1));
     char *cr = take((m <= kIdx16Rows ? sizeof(uint16_t) : sizeof(int32_t)) * (size_t)(nnz + kCscPad));
     char *cv = take(sizeof(float) * (size_t)(nnz + kCscPad));
+    char *bs = take(sizeof(int64_t) * (size_t)R * n);
+    char *rp = take(sizeof(int32_t) * (size_t)R * n * (m + 1));
+    char *rc = take(sizeof(uint16_t) * (size_t)(nnz + kCscPad));
+    char *rv = take(sizeof(float) * (size_t)(nnz + kCscPad));
     if (out) {
         out->bad = (uint32_t *)b;
         out->zpart = (float *)c;
@@ -88,6 +95,10 @@ size_t index_layout(int32_t n, int64_t m, int64_t d, int64_t nnz, char *base, In
         out->colptr = (int32_t *)cp;
         out->csc_row = (void *)cr;
         out->csc_val = (float *)cv;
+        out->bstart = (int64_t *)bs;
+        out->rptr = (int32_t *)rp;
+        out->rcol = (uint16_t *)rc;
+        out->rval = (float *)rv;
         out->R = (int)R;
         out->Wc = Wc;
     }
@@ -137,12 +148,10 @@ __global__ __launch_bounds__(kThreads) void csr_split_kernel(const int64_t *__re
     }
 }
 
-// Both passes walk a worker's rows kRows at a time per wavefront: lanes 0..kRows-1 fetch the bounds
-// of the rows' slices (split is [R + 1][rows]), the bounds are broadcast, and the slices' loads are
-// issued for all kRows rows before anything is consumed -- a row slice is short (d/R times the
-// density, typically one or two loads per lane), so one row at a time would leave a wavefront
-// waiting on a chain of dependent loads per row.  Addresses past a slice's end are clamped to its
-// last entry and their contribution dropped, so that no load sits behind a branch.
+// The fill of the column-major copy walks a worker's rows kRows at a time: lanes 0..kRows-1 fetch the
+// bounds of the rows' slices (split is [R + 1][rows]), the bounds are broadcast, and the slices' loads are
+// issued for all kRows rows before anything is consumed.  Addresses past a slice's end are clamped to
+// its last entry and their contribution dropped, so that no load sits behind a branch.
 constexpr int kRows = 8;
 
 struct SliceBounds {
@@ -171,64 +180,163 @@ __device__ __forceinline__ int32_t batch_longest(int32_t len) {
     return __shfl(len, 0, kWave);
 }
 
-// ---- pass 1: partial dot products.  Dynamic LDS: Wc floats.
-__global__ __launch_bounds__(kAtrThreads) void csr_dot_kernel(const int64_t *__restrict__ rowptr,
-                                                              const int32_t *__restrict__ col,
-                                                              const float *__restrict__ val,
-                                                              const int32_t *__restrict__ split,
-                                                              const float *__restrict__ x, float *__restrict__ zpart,
-                                                              int64_t m, int64_t d, int64_t Wc) {
-    extern __shared__ float lds[];
+// ---- attach time: the range-major copy.  One workgroup per (range, worker): where the block starts,
+// where each row's slice starts inside it, then the slices themselves (column minus the range's first).
+__global__ __launch_bounds__(kAtrThreads) void csrr_build_kernel(const int64_t *__restrict__ rowptr,
+                                                                 const int32_t *__restrict__ col,
+                                                                 const float *__restrict__ val,
+                                                                 const int32_t *__restrict__ split,
+                                                                 int64_t *__restrict__ bstart,
+                                                                 int32_t *__restrict__ rptr,
+                                                                 uint16_t *__restrict__ rcol,
+                                                                 float *__restrict__ rval, int64_t m, int64_t Wc) {
+    __shared__ long long part[kAtrWaves];
+    __shared__ uint32_t wave_total[kAtrWaves];
     const int range = blockIdx.x;
-    const int64_t worker = blockIdx.y, rows = (int64_t)gridDim.y * m;
+    const int64_t worker = blockIdx.y, n = gridDim.y, rows = n * m;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = lane_id();
+    const int32_t *s_lo = split + (int64_t)range * rows + worker * m;
+    const int32_t *s_hi = split + (int64_t)(range + 1) * rows + worker * m;
+    long long lower = 0;
+    for (int64_t l = tid; l < m; l += kAtrThreads) lower += s_lo[l];
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) lower += __shfl_xor(lower, o, kWave);
+    if (lane == 0) part[wave] = lower;
+    __syncthreads();
+    long long base = rowptr[worker * m];
+    for (int w = 0; w < kAtrWaves; ++w) base += part[w];
+    if (tid == 0) bstart[(int64_t)range * n + worker] = base;
+    int32_t *rp = rptr + ((int64_t)range * n + worker) * (m + 1);
+    uint32_t carry = 0;
+    for (int64_t l0 = 0; l0 < m; l0 += kAtrThreads) {          // exclusive scan of the slice lengths
+        const int64_t l = l0 + tid;
+        const uint32_t len = l < m ? (uint32_t)(s_hi[l] - s_lo[l]) : 0u;
+        const uint32_t incl = wave_inclusive_scan(len);
+        __syncthreads();
+        if (lane == kWave - 1) wave_total[wave] = incl;
+        __syncthreads();
+        uint32_t before = carry, all = 0;
+        for (int w = 0; w < kAtrWaves; ++w) {
+            if (w < wave) before += wave_total[w];
+            all += wave_total[w];
+        }
+        if (l < m) rp[l] = (int32_t)(before + incl - len);
+        carry += all;
+    }
+    if (tid == 0) rp[m] = (int32_t)carry;
+    __syncthreads();                                            // rp is read back below
+    const int64_t c0 = (int64_t)range * Wc;
+    for (int64_t l = wave; l < m; l += kAtrWaves) {
+        const int64_t src = rowptr[worker * m + l] + s_lo[l];
+        const int32_t len = s_hi[l] - s_lo[l];
+        const int64_t before = rp[l];
+        for (int32_t t = lane; t < len; t += kWave) {
+            rcol[base + before + t] = (uint16_t)(col[src + t] - c0);
+            rval[base + before + t] = val[src + t];
+        }
+    }
+}
+
+// ---- both passes: sums over segments of a contiguous list of (index, value) pairs.
+// The calling wavefront owns 4 x 64 consecutive segments; lane j holds the entry ranges [b[g], e[g]) of
+// segments j, j + 64, ... (ascending and contiguous over (g, lane); an empty range where there is no
+// segment).  The span is walked in tiles of 1024 entries aligned to four entries: each lane loads four
+// times four consecutive pairs, all loads of the tile in flight together, multiplies the values by
+// vec(index) and stages the products in LDS; then every lane adds, for each of its segments, the piece
+// that lies in the tile, in storage order (a piece longer than kLongColumn entries by the whole
+// wavefront).  acc[g] receives the sums.  The lists must be readable up to three entries past the span.
+template <class Index, class VecFn>
+__device__ __forceinline__ void segment_sums(const int64_t (&b)[kCscGroups], const int64_t (&e)[kCscGroups],
+                                             const Index *__restrict__ index, const float *__restrict__ value,
+                                             VecFn vec, float *tile, int lane, float (&acc)[kCscGroups]) {
+    const int64_t span_b = __shfl(b[0], 0, kWave), span_e = __shfl(e[kCscGroups - 1], kWave - 1, kWave);
+#pragma unroll
+    for (int g = 0; g < kCscGroups; ++g) acc[g] = 0.f;
+    constexpr int kLoads = kTile / (4 * kWave);                // 4
+    const int64_t last4 = (span_e - 1) & ~(int64_t)3;          // last aligned quad that holds an entry of the span
+    for (int64_t t0 = span_b & ~(int64_t)3; t0 < span_e; t0 += kTile) {
+        typedef float v4f __attribute__((ext_vector_type(4)));
+        typedef Index v4r __attribute__((ext_vector_type(4)));
+        v4r r[kLoads];
+        v4f v[kLoads];
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            int64_t at = t0 + u * (4 * kWave) + 4 * lane;
+            at = at < last4 ? at : last4;                      // clamped (re-reads the last quad): no load behind a branch
+            r[u] = __builtin_nontemporal_load(reinterpret_cast<const v4r *>(index + at));
+            v[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(value + at));
+        }
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            v4f pr;
+            pr.x = v[u].x * vec(r[u].x);
+            pr.y = v[u].y * vec(r[u].y);
+            pr.z = v[u].z * vec(r[u].z);
+            pr.w = v[u].w * vec(r[u].w);
+            *reinterpret_cast<v4f *>(tile + u * (4 * kWave) + 4 * lane) = pr;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int64_t t1 = t0 + kTile < span_e ? t0 + kTile : span_e;
+#pragma unroll
+        for (int g = 0; g < kCscGroups; ++g) {
+            const int64_t lo64 = b[g] > t0 ? b[g] : t0, hi64 = e[g] < t1 ? e[g] : t1;
+            const int32_t lo = (int32_t)(lo64 - t0), hi = (int32_t)(hi64 - t0);     // tile coordinates; hi <= lo: nothing
+            if (__ballot(lo < hi) == 0) continue;              // the group has nothing in this tile (uniform)
+            const bool is_long = hi - lo > kLongColumn;
+            if (!is_long)
+                for (int32_t t = lo; t < hi; ++t) acc[g] += tile[t];
+            uint64_t todo = __ballot(is_long);
+            while (todo) {                                     // uniform in the wavefront
+                const int src = __ffsll((long long)todo) - 1;
+                todo &= todo - 1;
+                const int32_t L = __shfl(lo, src, kWave), H = __shfl(hi, src, kWave);
+                float part = 0.f;
+                for (int32_t t = L + lane; t < H; t += kWave) part += tile[t];
+                part = wave_sum(part);
+                if (lane == src) acc[g] += part;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// ---- pass 1: partial dot products from the range-major copy.  Dynamic LDS: Wc floats (the range of x).
+// Grid (R * row chunks, n); a workgroup takes kCscCols rows of one (range, worker), a wavefront 256 of them.
+__global__ __launch_bounds__(kCscThreads) void csrr_dot_kernel(const int64_t *__restrict__ bstart,
+                                                               const int32_t *__restrict__ rptr,
+                                                               const uint16_t *__restrict__ rcol,
+                                                               const float *__restrict__ rval,
+                                                               const float *__restrict__ x, float *__restrict__ zpart,
+                                                               int64_t m, int64_t d, int R, int64_t Wc) {
+    extern __shared__ float x_lds[];
+    __shared__ __attribute__((aligned(16))) float tiles[kCscWaves][kTile];
+    const int range = blockIdx.x % R;
+    const int64_t chunk = blockIdx.x / R, worker = blockIdx.y, n = gridDim.y, rows = n * m;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const int64_t c0 = (int64_t)range * Wc;
     const int64_t width = c0 + Wc < d ? Wc : d - c0;
-    for (int64_t j = threadIdx.x; j < width; j += kAtrThreads) lds[j] = x[c0 + j];
+    for (int64_t j = threadIdx.x; j < width; j += kCscThreads) x_lds[j] = x[c0 + j];
     __syncthreads();
-    // the bounds of the next batch are fetched while the current one is worked on; two steps of 64 entries
-    // per row are loaded together (a slice of the usual length is then one round trip)
-    constexpr int kSteps = 2;
-    const int64_t stride = (int64_t)kAtrWaves * kRows;
-    int64_t l0 = (int64_t)wave * kRows;
-    SliceBounds next = batch_bounds(rowptr, split, rows, range, worker, m, l0 < m ? l0 : 0, lane);
-    for (; l0 < m; l0 += stride) {
-        const SliceBounds mine = next;
-        if (l0 + stride < m) next = batch_bounds(rowptr, split, rows, range, worker, m, l0 + stride, lane);
-        const int32_t longest = batch_longest(mine.len);
-        float s[kRows];
+    const int64_t l_first = (chunk * kCscWaves + wave) * (kCscGroups * kWave);
+    if (l_first >= m) return;                                   // the whole wavefront; no barrier follows
+    const int64_t base = bstart[(int64_t)range * n + worker];
+    const int32_t *rp = rptr + ((int64_t)range * n + worker) * (m + 1);
+    int64_t b[kCscGroups], e[kCscGroups];
 #pragma unroll
-        for (int u = 0; u < kRows; ++u) s[u] = 0.f;
-        for (int32_t t0 = 0; t0 < longest; t0 += kSteps * kWave) {
-            int32_t c[kSteps][kRows];
-            float v[kSteps][kRows];
-            bool in[kSteps][kRows];
+    for (int g = 0; g < kCscGroups; ++g) {
+        const int64_t l = l_first + g * kWave + lane;
+        b[g] = base + rp[l < m ? l : m];                       // rows past m: an empty range at the end
+        e[g] = base + rp[l < m ? l + 1 : m];
+    }
+    float acc[kCscGroups];
+    segment_sums(b, e, rcol, rval, [&](uint16_t c) { return x_lds[c]; }, tiles[wave], lane, acc);
 #pragma unroll
-            for (int u = 0; u < kRows; ++u) {
-                const int64_t b = __shfl(mine.b, u, kWave);
-                const int32_t len = __shfl(mine.len, u, kWave);
-#pragma unroll
-                for (int q = 0; q < kSteps; ++q) {
-                    const int32_t t = t0 + q * kWave + lane;
-                    in[q][u] = t < len;
-                    const int64_t at = b + (in[q][u] ? t : (len > 0 ? len - 1 : 0));
-                    c[q][u] = len > 0 ? stream_load(col + at) : (int32_t)c0;
-                    v[q][u] = len > 0 ? stream_load(val + at) : 0.f;
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < kSteps; ++q)
-#pragma unroll
-                for (int u = 0; u < kRows; ++u) {
-                    const float xv = lds[c[q][u] - c0];
-                    if (in[q][u]) s[u] = fmaf(v[q][u], xv, s[u]);
-                }
-        }
-#pragma unroll
-        for (int u = 0; u < kRows; ++u) {
-            const float z = wave_sum(s[u]);
-            if (lane == 0 && l0 + u < m) zpart[(int64_t)range * rows + worker * m + l0 + u] = z;
-        }
+    for (int g = 0; g < kCscGroups; ++g) {
+        const int64_t l = l_first + g * kWave + lane;
+        if (l < m) zpart[(int64_t)range * rows + worker * m + l] = acc[g];
     }
 }
 
@@ -352,11 +460,7 @@ __global__ __launch_bounds__(kThreads) void csr_coef_kernel(const float *__restr
 }
 
 // ---- pass 2: gradient columns from the column-major copy.  Dynamic LDS: m floats if COEF_LDS.
-// A wavefront owns 256 consecutive columns (four groups of 64, lane j the columns j, j + 64, ...), whose
-// entries are one contiguous span of the copy.  The span is walked in tiles of 1024 entries aligned to
-// four entries: each lane loads four times four consecutive (row, value) pairs, all loads of the tile
-// in flight together, multiplies by coef[row] and stages the products in LDS; then every lane adds, for
-// each of its columns, the piece of the column that lies in the tile, in storage order.
+// A workgroup takes kCscCols columns of one worker, a wavefront 256 of them; vec = the worker's coef.
 template <bool COEF_LDS, class RowIndex>
 __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__restrict__ colptr,
                                                                const RowIndex *__restrict__ csc_row,
@@ -378,8 +482,6 @@ __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__
     if (cb >= d) return;                                        // the whole wavefront; no barrier follows
     const int64_t first = rowptr[worker * m];
     const int32_t *cp = colptr + worker * (d + 1);
-    float *tile = tiles[wave];
-
     int64_t b[kCscGroups], e[kCscGroups];                      // global entry ranges of this lane's columns
 #pragma unroll
     for (int g = 0; g < kCscGroups; ++g) {
@@ -387,60 +489,9 @@ __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__
         b[g] = first + cp[c < d ? c : d];                      // columns past d: an empty range at the end
         e[g] = first + cp[c < d ? c + 1 : d];
     }
-    const int64_t span_b = __shfl(b[0], 0, kWave), span_e = __shfl(e[kCscGroups - 1], kWave - 1, kWave);
     float acc[kCscGroups];
-#pragma unroll
-    for (int g = 0; g < kCscGroups; ++g) acc[g] = 0.f;
-
-    constexpr int kLoads = kTile / (4 * kWave);                // 4
-    const int64_t last4 = (span_e - 1) & ~(int64_t)3;          // last aligned quad that holds an entry of the span
-    for (int64_t t0 = span_b & ~(int64_t)3; t0 < span_e; t0 += kTile) {
-        typedef float v4f __attribute__((ext_vector_type(4)));
-        typedef RowIndex v4r __attribute__((ext_vector_type(4)));
-        v4r r[kLoads];
-        v4f v[kLoads];
-#pragma unroll
-        for (int u = 0; u < kLoads; ++u) {
-            int64_t at = t0 + u * (4 * kWave) + 4 * lane;
-            at = at < last4 ? at : last4;                      // clamped (re-reads the last quad): no load behind a branch
-            r[u] = __builtin_nontemporal_load(reinterpret_cast<const v4r *>(csc_row + at));
-            v[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(csc_val + at));
-        }
-#pragma unroll
-        for (int u = 0; u < kLoads; ++u) {
-            v4f pr;
-            pr.x = v[u].x * (COEF_LDS ? coef_lds[r[u].x] : cf[r[u].x]);
-            pr.y = v[u].y * (COEF_LDS ? coef_lds[r[u].y] : cf[r[u].y]);
-            pr.z = v[u].z * (COEF_LDS ? coef_lds[r[u].z] : cf[r[u].z]);
-            pr.w = v[u].w * (COEF_LDS ? coef_lds[r[u].w] : cf[r[u].w]);
-            *reinterpret_cast<v4f *>(tile + u * (4 * kWave) + 4 * lane) = pr;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int64_t t1 = t0 + kTile < span_e ? t0 + kTile : span_e;
-#pragma unroll
-        for (int g = 0; g < kCscGroups; ++g) {
-            const int64_t lo64 = b[g] > t0 ? b[g] : t0, hi64 = e[g] < t1 ? e[g] : t1;
-            const int32_t lo = (int32_t)(lo64 - t0), hi = (int32_t)(hi64 - t0);     // tile coordinates; hi <= lo: nothing
-            if (__ballot(lo < hi) == 0) continue;              // the group has nothing in this tile (uniform)
-            const bool is_long = hi - lo > kLongColumn;
-            if (!is_long)
-                for (int32_t t = lo; t < hi; ++t) acc[g] += tile[t];
-            uint64_t todo = __ballot(is_long);
-            while (todo) {                                     // uniform in the wavefront
-                const int src = __ffsll((long long)todo) - 1;
-                todo &= todo - 1;
-                const int32_t L = __shfl(lo, src, kWave), H = __shfl(hi, src, kWave);
-                float part = 0.f;
-                for (int32_t t = L + lane; t < H; t += kWave) part += tile[t];
-                part = wave_sum(part);
-                if (lane == src) acc[g] += part;
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    }
+    segment_sums(b, e, csc_row, csc_val, [&](RowIndex r) { return COEF_LDS ? coef_lds[r] : cf[r]; }, tiles[wave], lane,
+                 acc);
 #pragma unroll
     for (int g = 0; g < kCscGroups; ++g) {
         const int64_t c = cb + g * kWave + lane;
@@ -519,6 +570,11 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
     const size_t lds_bytes = sizeof(uint32_t) * (size_t)ix.Wc;
     hipLaunchKernelGGL(csc_count_kernel, grid, dim3(kAtrThreads), lds_bytes, stream, rowptr, col, ix.split, ix.colptr,
                        m, d, ix.R, ix.Wc);
+    hipLaunchKernelGGL(csrr_build_kernel, grid, dim3(kAtrThreads), 0, stream, rowptr, col, val, ix.split, ix.bstart,
+                       ix.rptr, ix.rcol, ix.rval, m, ix.Wc);
+    st = hipMemsetAsync(ix.rcol + nnz, 0, sizeof(uint16_t) * (size_t)kCscPad, stream);
+    if (st == hipSuccess) st = hipMemsetAsync(ix.rval + nnz, 0, sizeof(float) * (size_t)kCscPad, stream);
+    if (st != hipSuccess) return st;
     const bool idx16 = m <= kIdx16Rows;
     const size_t row_bytes = idx16 ? sizeof(uint16_t) : sizeof(int32_t);
     st = hipMemsetAsync((char *)ix.csc_row + row_bytes * (size_t)nnz, 0, row_bytes * (size_t)kCscPad, stream);
@@ -545,7 +601,7 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
         index_layout(n, m, d, nnz, (char *)const_cast<void *>(index), &ix);
         static bool configured = false;
         if (!configured) {
-            hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csr_dot_kernel),
+            hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csrr_dot_kernel),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, sizeof(float) * kRangeCols);
             if (st == hipSuccess)
                 st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csc_grad_kernel<true, uint16_t>),
@@ -553,8 +609,10 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
             if (st != hipSuccess) return st;
             configured = true;
         }
-        hipLaunchKernelGGL(csr_dot_kernel, dim3((unsigned)ix.R, (unsigned)n), dim3(kAtrThreads),
-                           sizeof(float) * (size_t)ix.Wc, stream, rowptr, col, val, ix.split, x, ix.zpart, m, d, ix.Wc);
+        const int64_t row_chunks = (m + kCscCols - 1) / kCscCols;
+        hipLaunchKernelGGL(csrr_dot_kernel, dim3((unsigned)(ix.R * row_chunks), (unsigned)n), dim3(kCscThreads),
+                           sizeof(float) * (size_t)ix.Wc, stream, ix.bstart, ix.rptr, ix.rcol, ix.rval, x, ix.zpart, m, d,
+                           ix.R, ix.Wc);
         mk(K_GRAD_MAIN);
         hipLaunchKernelGGL(csr_coef_kernel, dim3((unsigned)((rows + kThreads - 1) / kThreads)), dim3(kThreads), 0,
                            stream, y, ix.zpart, ix.R, rows, 1.0f / (float)m, ix.coef);
