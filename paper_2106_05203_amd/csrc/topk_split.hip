@@ -13,14 +13,17 @@
 //   then, on the candidates only, either
 //   select    (small k) one workgroup per row: candidate keys into LDS, radix select there, ordered
 //             emission of the k kept entries (+ line 6 of Algorithm 2); or
-//   hist x3, count, emit   (large k) the same steps spread over several workgroups per row,
+//   hist x2, count, emit   (large k) the same steps spread over several workgroups per row,
 //             chained by kernel boundaries: a kernel merges its LDS histograms into the row's
 //             global one with a few atomics per bin, the NEXT kernel's workgroups each scan the
-//             merged histogram in their prologue.
+//             merged histogram in their prologue.  The candidates' keys lie at or above key_lo and
+//             the threshold key T a little above it, so the two digits are taken from key - key_lo:
+//             12 bits from bit 11 upwards (a window of one octave; keys beyond it share the last
+//             bin), then the low 11 bits.
 //
-// The estimate can be wrong (fewer than k candidates); the row is then selected by the exact
+// The estimate can be wrong (fewer than k candidates, or T beyond the window); the row is then selected by the exact
 // one-workgroup algorithm on the original data (inside `select`, or by an extra workgroup of the
-// second `hist` kernel), so the result never depends on the sample.  Slots have the capacity of their piece, so any input fits.
+// `count` kernel), so the result never depends on the sample.  Slots have the capacity of their piece, so any input fits.
 #include <cmath>
 
 #include "topk_row_impl.h"
@@ -37,19 +40,21 @@ constexpr int kMaxSlots = 4096;              // slots (wavefront pieces) per row
 constexpr int kSelCap = 28672;               // candidate keys the select kernel holds in LDS
 constexpr int kCandThreads = 1024;           // count / emit workgroups (large k): one wavefront per slot
 constexpr int kCandWaves = kCandThreads / kWave;
-constexpr int kHistThreads = kRowThreads;    // candidate histogram workgroups (large k)
-constexpr int kCandBlocks = 8;               // ... of which each row gets this many
+constexpr int kHistThreads = 512;            // candidate histogram workgroups (large k)
+constexpr int kCandBlocks = 16;              // ... of which each row gets this many
 constexpr int kBins1 = 1 << kBits1, kBins2 = 1 << kBits2, kBins3 = 1 << kBits3;
+constexpr int kBitsA = 12, kBitsB = 11;        // large k: digits of key - key_lo
+constexpr int kBinsA = 1 << kBitsA, kBinsB = 1 << kBitsB;
 
 struct RowInfo {
-    uint32_t failed, M;   // fewer than k candidates were collected; number of candidates
-    uint32_t d1, need1;   // first digit of the threshold key; entries still needed from that bin
-    uint32_t p22, need2;  // first two digits; entries still needed from that sub-bin
-    uint32_t T, q;        // threshold key; number of entries equal to T to keep
+    uint32_t failed, M;       // the estimate failed (see above); number of candidates
+    uint32_t bin_a, need_a;   // first digit of T - key_lo; entries still needed from that bin
+    uint32_t T, q;            // threshold key; number of entries equal to T to keep
+    uint32_t key_lo, pad;     // lower bound of the candidate keys (from collect)
 };
 
 struct Ws {
-    uint32_t *hist1, *hist2, *hist3;      // [n][bins], kept zero between calls
+    uint32_t *hist_a, *hist_b;            // [n][kBinsA], [n][kBinsB], kept zero between calls
     RowInfo *info;                        // [n]
     uint32_t *slot_cnt, *slot_gt, *slot_eq;   // [n][nslot]
     int32_t *cand_idx;                    // [n][nslot][L]
@@ -86,9 +91,8 @@ size_t layout(int32_t n, int64_t d, char *base, Ws *w) {
         off += align256(bytes);
         return p;
     };
-    char *h1 = take(sizeof(uint32_t) * (size_t)n * kBins1);
-    char *h2 = take(sizeof(uint32_t) * (size_t)n * kBins2);
-    char *h3 = take(sizeof(uint32_t) * (size_t)n * kBins3);
+    char *h2 = take(sizeof(uint32_t) * (size_t)n * kBinsA);
+    char *h3 = take(sizeof(uint32_t) * (size_t)n * kBinsB);
     char *inf = take(sizeof(RowInfo) * (size_t)n);
     const size_t slots = sizeof(uint32_t) * (size_t)n * tmp.nslot;
     char *s0 = take(slots), *s1 = take(slots), *s2 = take(slots);
@@ -97,7 +101,7 @@ size_t layout(int32_t n, int64_t d, char *base, Ws *w) {
     char *cn = take(sizeof(float) * (size_t)n * tmp.nslot * tmp.L);
     if (w) {
         *w = tmp;
-        w->hist1 = (uint32_t *)h1; w->hist2 = (uint32_t *)h2; w->hist3 = (uint32_t *)h3;
+        w->hist_a = (uint32_t *)h2; w->hist_b = (uint32_t *)h3;
         w->info = (RowInfo *)inf;
         w->slot_cnt = (uint32_t *)s0; w->slot_gt = (uint32_t *)s1; w->slot_eq = (uint32_t *)s2;
         w->cand_idx = (int32_t *)ci; w->cand_val = (float *)cv; w->cand_new = (float *)cn;
@@ -263,65 +267,67 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
     const float *a = p.a + row * d;
     const float *b = DIFF ? p.b + row * d : nullptr;
     const uint32_t key_lo = estimate_key_lo<DIFF>(s, a, b, d, p.k);
+    if (blockIdx.x == 0 && threadIdx.x == 0) w.info[row].key_lo = key_lo;
 
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const int64_t slot_no = (int64_t)blockIdx.x * kBlkWaves + wave;
-    if (slot_no >= w.nslot) return;
-    StageRing &ring = rings[wave];
-    const int64_t lo = slot_no * w.L;
-    const int64_t hi = lo + w.L < d ? lo + w.L : d;
-    const int64_t slot_at = (row * w.nslot + slot_no) * w.L;
-    const SlotPtrs slot{w.cand_idx + slot_at, w.cand_val + slot_at, w.cand_new + slot_at};
-    uint32_t cnt = 0, flushed = 0;
-    constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
-    int64_t base = lo;
-    for (; base + kGroup <= hi; base += kGroup) {
-        float v[kUnroll][VEC], bv[kUnroll][VEC];
-        if constexpr (VEC == 4) {
-            float4 va[kUnroll], vb[kUnroll];
+    if (slot_no < w.nslot) {
+        StageRing &ring = rings[wave];
+        const int64_t lo = slot_no * w.L;
+        const int64_t hi = lo + w.L < d ? lo + w.L : d;
+        const int64_t slot_at = (row * w.nslot + slot_no) * w.L;
+        const SlotPtrs slot{w.cand_idx + slot_at, w.cand_val + slot_at, w.cand_new + slot_at};
+        uint32_t cnt = 0, flushed = 0;
+        constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
+        int64_t base = lo;
+        for (; base + kGroup <= hi; base += kGroup) {
+            float v[kUnroll][VEC], bv[kUnroll][VEC];
+            if constexpr (VEC == 4) {
+                float4 va[kUnroll], vb[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                va[u] = stream_load4(a + base + u * kStep + lane * 4);
-                if constexpr (DIFF) vb[u] = stream_load4(b + base + u * kStep + lane * 4);
-            }
+                for (int u = 0; u < kUnroll; ++u) {
+                    va[u] = stream_load4(a + base + u * kStep + lane * 4);
+                    if constexpr (DIFF) vb[u] = stream_load4(b + base + u * kStep + lane * 4);
+                }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                v[u][0] = va[u].x; v[u][1] = va[u].y; v[u][2] = va[u].z; v[u][3] = va[u].w;
-                if constexpr (DIFF) {
-                    bv[u][0] = vb[u].x; bv[u][1] = vb[u].y; bv[u][2] = vb[u].z; bv[u][3] = vb[u].w;
+                for (int u = 0; u < kUnroll; ++u) {
+                    v[u][0] = va[u].x; v[u][1] = va[u].y; v[u][2] = va[u].z; v[u][3] = va[u].w;
+                    if constexpr (DIFF) {
+                        bv[u][0] = vb[u].x; bv[u][1] = vb[u].y; bv[u][2] = vb[u].z; bv[u][3] = vb[u].w;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    v[u][0] = stream_load(a + base + u * kStep + lane);
+                    if constexpr (DIFF) bv[u][0] = stream_load(b + base + u * kStep + lane);
                 }
             }
-        } else {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                v[u][0] = stream_load(a + base + u * kStep + lane);
-                if constexpr (DIFF) bv[u][0] = stream_load(b + base + u * kStep + lane);
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) {
+                    if constexpr (DIFF) v[u][t] -= bv[u][t];
+                    else bv[u][t] = 0.f;
+                }
+                append_candidates<VEC, true, UPDATE>(v[u], bv[u], base + u * kStep + lane * VEC, hi, key_lo, ring,
+                                                     lane, slot, cnt, flushed);
             }
         }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
+        for (; base < hi; base += kStep) {           // checked tail, entry by entry
+            const int64_t e0 = base + lane * VEC;
+            float v[VEC], bv[VEC];
 #pragma unroll
             for (int t = 0; t < VEC; ++t) {
-                if constexpr (DIFF) v[u][t] -= bv[u][t];
-                else bv[u][t] = 0.f;
+                v[t] = e0 + t < hi ? a[e0 + t] : 0.f;
+                bv[t] = DIFF && e0 + t < hi ? b[e0 + t] : 0.f;
+                v[t] -= bv[t];
             }
-            append_candidates<VEC, true, UPDATE>(v[u], bv[u], base + u * kStep + lane * VEC, hi, key_lo, ring, lane,
-                                                 slot, cnt, flushed);
+            append_candidates<VEC, false, UPDATE>(v, bv, e0, hi, key_lo, ring, lane, slot, cnt, flushed);
         }
+        drain_ring<UPDATE>(ring, flushed, cnt, lane, slot);
+        if (lane == 0) w.slot_cnt[row * w.nslot + slot_no] = cnt;
     }
-    for (; base < hi; base += kStep) {           // checked tail, entry by entry
-        const int64_t e0 = base + lane * VEC;
-        float v[VEC], bv[VEC];
-#pragma unroll
-        for (int t = 0; t < VEC; ++t) {
-            v[t] = e0 + t < hi ? a[e0 + t] : 0.f;
-            bv[t] = DIFF && e0 + t < hi ? b[e0 + t] : 0.f;
-            v[t] -= bv[t];
-        }
-        append_candidates<VEC, false, UPDATE>(v, bv, e0, hi, key_lo, ring, lane, slot, cnt, flushed);
-    }
-    drain_ring<UPDATE>(ring, flushed, cnt, lane, slot);
-    if (lane == 0) w.slot_cnt[row * w.nslot + slot_no] = cnt;
 }
 
 // ---------------------------------------------------------------- select (small k): one workgroup per row
@@ -604,33 +610,26 @@ __device__ void zero_global_hist(uint32_t *hist, int bins) {
     for (int i = threadIdx.x; i < bins; i += blockDim.x) hist[i] = 0u;
 }
 
-// Digit STAGE (1, 2 or 3) of the radix select over the candidates, kCandBlocks workgroups per row
-// (few, so that the merge below costs a few atomics per bin).  Prologue: the result of the previous
-// stage from the merged histogram.  Body: LDS histogram of this stage's digit over the workgroup's
-// slots, four slots in flight per wavefront, then merged into the row's global histogram.
-// Stage 2 has one more workgroup per row: if stage 1 found fewer than k candidates (the estimate
-// failed) it selects the row by the exact one-workgroup algorithm on the original data, while the
-// row's other workgroups, and the later kernels, leave the row alone.  (DIFF, UPDATE matter there only.)
-template <int STAGE, bool DIFF, bool UPDATE>
+// Digit STAGE (1 or 2) of the radix select over the candidates' key - key_lo, kCandBlocks workgroups per
+// row (few, so that the merge below costs a few atomics per bin).  Prologue: stage 1 adds up the slot
+// counts (fewer than k candidates: the estimate failed); stage 2 selects the first digit from the merged
+// histogram (the last bin, which also holds every key beyond the window, cannot be resolved: failed).
+// Body: LDS histogram of this stage's digit over the workgroup's slots, four slots in flight per
+// wavefront, then merged into the row's global histogram.
+// A failed row is left alone by the later kernels, except for one extra workgroup of the count kernel
+// that selects it by the exact one-workgroup algorithm on the original data.
+template <int STAGE>
 __global__ __launch_bounds__(kHistThreads) void cand_hist_kernel(TopkArgs p, Ws w) {
-    constexpr int NB = STAGE == 1 ? kBins1 : (STAGE == 2 ? kBins2 : kBins3);
-    constexpr int SHIFT = STAGE == 1 ? kBits2 + kBits3 : (STAGE == 2 ? kBits3 : 0);
-    constexpr int PSHIFT = STAGE == 1 ? 31 : (STAGE == 2 ? kBits2 + kBits3 : kBits3);
-    __shared__ RowShared rs;
+    static_assert(STAGE == 1 || STAGE == 2, "two digits");
+    constexpr int NB = STAGE == 1 ? kBinsA : kBinsB;
+    __shared__ uint32_t hist[NB];
     __shared__ uint32_t lds_wave[kHistThreads / kWave], lds_out[2];
-    uint32_t *hist = rs.hist;
-    static_assert(NB <= (1 << kBits1), "the stage's histogram must fit the row algorithm's");
     const int64_t row = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     RowInfo *info = w.info + row;
-    if constexpr (STAGE == 2) {
-        if (blockIdx.x == kCandBlocks) {             // the rescue workgroup
-            if (info->failed) row_topk<DIFF, UPDATE>(rs, p, row);
-            return;
-        }
-    }
     const uint32_t *slot_cnt = w.slot_cnt + row * w.nslot;
-    uint32_t prefix = 0;    // digits known so far
+    const uint32_t key_lo = info->key_lo;
+    uint32_t bin_a = 0;
     if constexpr (STAGE == 1) {
         uint32_t mine = 0, M;
         for (int64_t sl = threadIdx.x; sl < w.nslot; sl += kHistThreads) mine += slot_cnt[sl];
@@ -643,26 +642,21 @@ __global__ __launch_bounds__(kHistThreads) void cand_hist_kernel(TopkArgs p, Ws 
         if (failed) return;
     } else {
         if (info->failed) return;
-        if constexpr (STAGE == 2) {
-            select_digit<kBins1, kHistThreads>(w.hist1 + row * kBins1, (uint32_t)p.k, lds_wave, lds_out);
-            prefix = lds_out[0];
-            if (blockIdx.x == 0 && threadIdx.x == 0) {
-                info->d1 = lds_out[0];
-                info->need1 = lds_out[1];
-            }
-        } else {
-            select_digit<kBins2, kHistThreads>(w.hist2 + row * kBins2, info->need1, lds_wave, lds_out);
-            prefix = (info->d1 << kBits2) | lds_out[0];
-            if (blockIdx.x == 0 && threadIdx.x == 0) {
-                info->p22 = prefix;
-                info->need2 = lds_out[1];
-            }
-            if (blockIdx.x == 0) zero_global_hist(w.hist1 + row * kBins1, kBins1);   // consumed by stage 2
+        select_digit<kBinsA, kHistThreads>(w.hist_a + row * kBinsA, (uint32_t)p.k, lds_wave, lds_out);
+        bin_a = lds_out[0];
+        const bool failed = bin_a == (uint32_t)kBinsA - 1u;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            info->bin_a = bin_a;
+            info->need_a = lds_out[1];
+            if (failed) info->failed = 1u;
         }
+        if (failed) return;
     }
     for (int i = threadIdx.x; i < NB; i += kHistThreads) hist[i] = 0u;
     __syncthreads();
-    constexpr int kInFlight = 4;
+    // kInFlight slots of the wavefront at a time, kSteps steps of 64 candidates of each: all loads of such a
+    // round are issued before the first is used (a slot usually holds fewer than kSteps * 64 candidates)
+    constexpr int kInFlight = 8, kSteps = 4;
     const int64_t stride = (int64_t)kCandBlocks * (kHistThreads / kWave);
     for (int64_t sl0 = (int64_t)blockIdx.x * (kHistThreads / kWave) + wave; sl0 < w.nslot; sl0 += stride * kInFlight) {
         uint32_t cnt[kInFlight], most = 0;
@@ -674,19 +668,30 @@ __global__ __launch_bounds__(kHistThreads) void cand_hist_kernel(TopkArgs p, Ws 
             val[u] = w.cand_val + (row * w.nslot + (sl < w.nslot ? sl : 0)) * w.L;
             most = cnt[u] > most ? cnt[u] : most;
         }
-        for (uint32_t j = lane; j < most; j += kWave) {
-            float v[kInFlight];
+        for (uint32_t j0 = 0; j0 < most; j0 += kWave * kSteps) {
+            float v[kSteps][kInFlight];
 #pragma unroll
-            for (int u = 0; u < kInFlight; ++u) v[u] = j < cnt[u] ? val[u][j] : 0.f;
+            for (int q = 0; q < kSteps; ++q)
 #pragma unroll
-            for (int u = 0; u < kInFlight; ++u) {
-                const uint32_t key = mag_key(v[u]);
-                if (j < cnt[u] && (key >> PSHIFT) == prefix) atomicAdd(&hist[(key >> SHIFT) & (NB - 1)], 1u);
-            }
+                for (int u = 0; u < kInFlight; ++u) {
+                    const uint32_t j = j0 + q * kWave + lane;
+                    v[q][u] = val[u][j < cnt[u] ? j : 0u];            // clamped: no load behind a branch
+                }
+#pragma unroll
+            for (int q = 0; q < kSteps; ++q)
+#pragma unroll
+                for (int u = 0; u < kInFlight; ++u) {
+                    const uint32_t j = j0 + q * kWave + lane;
+                    if (j >= cnt[u]) continue;
+                    const uint32_t rel = mag_key(v[q][u]) - key_lo;       // candidates have key >= key_lo
+                    const uint32_t a = rel >> kBitsB < (uint32_t)kBinsA - 1u ? rel >> kBitsB : (uint32_t)kBinsA - 1u;
+                    if (STAGE == 1) atomicAdd(&hist[a], 1u);
+                    else if (a == bin_a) atomicAdd(&hist[rel & (kBinsB - 1)], 1u);
+                }
         }
     }
     __syncthreads();
-    uint32_t *merged = STAGE == 1 ? w.hist1 + row * kBins1 : (STAGE == 2 ? w.hist2 + row * kBins2 : w.hist3 + row * kBins3);
+    uint32_t *merged = STAGE == 1 ? w.hist_a + row * kBinsA : w.hist_b + row * kBinsB;
     for (int b = threadIdx.x; b < NB; b += kHistThreads) {
         const uint32_t c = hist[b];
         if (c) atomicAdd(merged + b, c);
@@ -695,37 +700,56 @@ __global__ __launch_bounds__(kHistThreads) void cand_hist_kernel(TopkArgs p, Ws 
 
 // One wavefront per slot.  Prologue: threshold key T and tie quota q from the third digit's
 // histogram.  Body: the slot's number of candidates above T and equal to T.
+template <bool DIFF, bool UPDATE>
 __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws w) {
+    static_assert(kCandThreads == kRowThreads, "the rescue workgroup runs the one-workgroup algorithm");
+    __shared__ RowShared rs;
     __shared__ uint32_t lds_wave[kCandWaves], lds_out[2];
     const int64_t row = blockIdx.y;
     const int wave = threadIdx.x / kWave, lane = lane_id();
     RowInfo *info = w.info + row;
+    if (blockIdx.x == gridDim.x - 1) {               // the rescue workgroup (DIFF, UPDATE matter here only)
+        if (info->failed) {
+            zero_global_hist(w.hist_a + row * kBinsA, kBinsA);     // left behind if stage 2 declared the failure
+            row_topk<DIFF, UPDATE>(rs, p, row);
+        }
+        return;
+    }
     if (info->failed) return;
-    select_digit<kBins3, kCandThreads>(w.hist3 + row * kBins3, info->need2, lds_wave, lds_out);
-    const uint32_t T = (info->p22 << kBits3) | lds_out[0];
+    select_digit<kBinsB, kCandThreads>(w.hist_b + row * kBinsB, info->need_a, lds_wave, lds_out);
+    const uint32_t T = info->key_lo + ((info->bin_a << kBitsB) | lds_out[0]);
     if (blockIdx.x == 0) {
         if (threadIdx.x == 0) {
             info->T = T;
             info->q = lds_out[1];
         }
-        zero_global_hist(w.hist2 + row * kBins2, kBins2);     // consumed by stage 3
+        zero_global_hist(w.hist_a + row * kBinsA, kBinsA);     // consumed by stage 2
     }
     const int64_t sl = (int64_t)blockIdx.x * kCandWaves + wave;
     if (sl >= w.nslot) return;
     const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
     const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
     uint32_t n_gt = 0, n_eq = 0;
-    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
-        const uint32_t j = j0 + lane;
-        const uint32_t key = j < cnt ? mag_key(slot_val[j]) : 0u;
-        n_gt += popc64(__ballot(j < cnt && key > T));
-        n_eq += popc64(__ballot(j < cnt && key == T));
+    constexpr int kSteps = 4;
+    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSteps) {
+        float v[kSteps];
+#pragma unroll
+        for (int q = 0; q < kSteps; ++q) {
+            const uint32_t j = j0 + q * kWave + lane;
+            v[q] = slot_val[j < cnt ? j : 0u];
+        }
+#pragma unroll
+        for (int q = 0; q < kSteps; ++q) {
+            const uint32_t j = j0 + q * kWave + lane;
+            const uint32_t key = mag_key(v[q]);
+            n_gt += popc64(__ballot(j < cnt && key > T));
+            n_eq += popc64(__ballot(j < cnt && key == T));
+        }
     }
     if (lane == 0) {
         w.slot_gt[row * w.nslot + sl] = n_gt;
         w.slot_eq[row * w.nslot + sl] = n_eq;
     }
-    (void)p;
 }
 
 // Ordered emission, one wavefront per slot.  The workgroup first adds up the counts of all slots of its
@@ -738,7 +762,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const RowInfo *info = w.info + row;
     if (info->failed) return;                                                     // the whole workgroup
-    if (blockIdx.x == 0) zero_global_hist(w.hist3 + row * kBins3, kBins3);       // consumed by count
+    if (blockIdx.x == 0) zero_global_hist(w.hist_b + row * kBinsB, kBinsB);       // consumed by count
     const int64_t sl0 = (int64_t)blockIdx.x * kCandWaves, sl = sl0 + wave;
     const bool active = sl < w.nslot;
     const uint32_t T = info->T, q = info->q;
@@ -771,25 +795,37 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
     const float *slot_new = w.cand_new + (row * w.nslot + sl) * w.L;
     int32_t *out_idx = p.out_idx + row * p.k;
     float *out_val = p.out_val + row * p.k;
-    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave) {
-        const uint32_t j = j0 + lane;
-        const bool in = j < cnt;
-        const float v = in ? slot_val[j] : 0.f;
-        const int32_t e = in ? slot_idx[j] : 0;
-        const uint32_t key = mag_key(v);
-        const bool gt = in && key > T, eq = in && key == T;
-        const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
-        const uint32_t eq_below = eq_run + lanes_below(m_eq);
-        const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
-        if (gt || (eq && eq_below < q)) {
-            const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
-            out_idx[pos] = e;
-            out_val[pos] = v;
-            if (UPDATE) (p.g_i + row * p.d)[e] = slot_new[j];   // Algorithm 2, line 6
+    constexpr int kSteps = 4;
+    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSteps) {
+        float v[kSteps], nx[kSteps];
+        int32_t e[kSteps];
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const uint32_t j = j0 + s * kWave + lane;
+            const uint32_t jc = j < cnt ? j : 0u;                // clamped: no load behind a branch
+            v[s] = slot_val[jc];
+            e[s] = slot_idx[jc];
+            nx[s] = UPDATE ? slot_new[jc] : 0.f;
         }
-        const uint32_t eq_next = eq_run + popc64(m_eq);
-        out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
-        eq_run = eq_next;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const uint32_t j = j0 + s * kWave + lane;
+            const bool in = j < cnt;
+            const uint32_t key = mag_key(v[s]);
+            const bool gt = in && key > T, eq = in && key == T;
+            const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
+            const uint32_t eq_below = eq_run + lanes_below(m_eq);
+            const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
+            if (gt || (eq && eq_below < q)) {
+                const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
+                out_idx[pos] = e[s];
+                out_val[pos] = v[s];
+                if (UPDATE) (p.g_i + row * p.d)[e[s]] = nx[s];   // Algorithm 2, line 6
+            }
+            const uint32_t eq_next = eq_run + popc64(m_eq);
+            out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
+            eq_run = eq_next;
+        }
     }
 }
 
@@ -864,17 +900,16 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
         mk(K_TOPK_SELECT);
         return st;
     }
-    const dim3 hgrid(kCandBlocks, (unsigned)p.n), hgrid2(kCandBlocks + 1, (unsigned)p.n), hblock(kHistThreads);
-    hipLaunchKernelGGL((cand_hist_kernel<1, false, false>), hgrid, hblock, 0, stream, p, w);
+    const dim3 hgrid(kCandBlocks, (unsigned)p.n), hblock(kHistThreads);
+    hipLaunchKernelGGL(cand_hist_kernel<1>, hgrid, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
-    if (upd) hipLaunchKernelGGL((cand_hist_kernel<2, true, true>), hgrid2, hblock, 0, stream, p, w);
-    else if (diff) hipLaunchKernelGGL((cand_hist_kernel<2, true, false>), hgrid2, hblock, 0, stream, p, w);
-    else hipLaunchKernelGGL((cand_hist_kernel<2, false, false>), hgrid2, hblock, 0, stream, p, w);
+    hipLaunchKernelGGL(cand_hist_kernel<2>, hgrid, hblock, 0, stream, p, w);
     mk(K_TOPK_REFINE);
-    hipLaunchKernelGGL((cand_hist_kernel<3, false, false>), hgrid, hblock, 0, stream, p, w);
-    mk(K_TOPK_REFINE);
-    const dim3 grid((unsigned)((w.nslot + kCandWaves - 1) / kCandWaves), (unsigned)p.n), block(kCandThreads);
-    hipLaunchKernelGGL(cand_count_kernel, grid, block, 0, stream, p, w);
+    const unsigned slot_blocks = (unsigned)((w.nslot + kCandWaves - 1) / kCandWaves);
+    const dim3 grid(slot_blocks, (unsigned)p.n), cgrid(slot_blocks + 1, (unsigned)p.n), block(kCandThreads);
+    if (upd) hipLaunchKernelGGL((cand_count_kernel<true, true>), cgrid, block, 0, stream, p, w);
+    else if (diff) hipLaunchKernelGGL((cand_count_kernel<true, false>), cgrid, block, 0, stream, p, w);
+    else hipLaunchKernelGGL((cand_count_kernel<false, false>), cgrid, block, 0, stream, p, w);
     mk(K_TOPK_COUNT);
     if (upd) hipLaunchKernelGGL(cand_emit_kernel<true>, grid, block, 0, stream, p, w);
     else hipLaunchKernelGGL(cand_emit_kernel<false>, grid, block, 0, stream, p, w);

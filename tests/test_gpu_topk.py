@@ -99,6 +99,20 @@ def test_long_rows_misleading_sample(gpu, oracle, k):
     check(gpu, oracle, V, k)
 
 
+@pytest.mark.parametrize("k", [10000, 60000])
+def test_long_rows_sample_far_too_low(gpu, oracle, k):
+    """The opposite mistake: the sampled pieces hold tiny values and everything else is large, so the
+    guessed threshold admits every entry and the k-th largest magnitude lies far above it (above the
+    window of leading digits the collect pass counts, for the large-k variant).  Same results."""
+    d = 300_000
+    rng = np.random.default_rng(k + 1)
+    V = (1000.0 * (1.0 + rng.random((3, d)))).astype(np.float32)
+    pos = np.concatenate([(p * (d - 256)) // 31 + np.arange(256) for p in range(32)])
+    V[:, pos] = (rng.standard_normal((3, pos.size)) * 1e-3).astype(np.float32)
+    V[1] = -V[1]
+    check(gpu, oracle, V, k)
+
+
 @pytest.mark.parametrize("n,d,k", [(2, 1_500_000, 100_000), (1, 2_000_001, 700_000), (3, 400_000, 399_999)])
 def test_long_rows_large_k(gpu, oracle, n, d, k):
     """k large enough that the candidates are processed by many workgroups per row."""
