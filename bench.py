@@ -29,6 +29,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
 MEASURED_TRAFFIC_BYTES = {
     "C2/grad_main": 804.9e6,       # profiles/ef21_step_C2_hbm_traffic_pmc.md
     "C4/topk_collect": 739.4e6,    # profiles/ef21_step_C4_hbm_traffic_pmc.md
+    "C3/grad_main": 1307.8e6,      # profiles/ef21_step_C3_hbm_traffic_pmc.md (both passes)
 }
 
 
@@ -131,14 +132,17 @@ def bench_csr(torch, binding, workloads, steps: int, warmup: int):
     x0 = torch.zeros(d, device="cuda")
     h.set_state(x0, h.local_grad(x0), None)
     wall, ev = timed_loop(torch, lambda i: h.step(), steps, warmup)
-    per_kernel, _ = kernel_times(torch, h, lambda i: h.step(), steps)
+    per_kernel, launches = kernel_times(torch, h, lambda i: h.step(), steps)
     total_nnz = n * m * nnz
     it_bytes = 8 * total_nnz + 8 * (n * m + 1) + 4 * n * m + 12 * n * d + 24 * n * k + 12 * d
     out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", "ms_per_step": round(wall, 5),
            "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()}, "iteration_algorithmic_bytes": it_bytes,
            "iteration_frac_of_hbm_peak": round(it_bytes / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-    out["roofline"] = roofline(8.0 * total_nnz + 8.0 * (n * m + 1) + 4.0 * n * m + 4.0 * n * d, per_kernel["grad_main"],
-                               "logreg_csr_kernel (grad_main)")
+    # the gradient takes two passes (two launches of the grad_main class): its algorithmic bytes against both
+    out["roofline"] = roofline(8.0 * total_nnz + 8.0 * (n * m + 1) + 4.0 * n * m + 4.0 * n * d,
+                               per_kernel["grad_main"] * launches["grad_main"],
+                               "csrr_dot_kernel + csc_grad_kernel (grad_main, both passes)",
+                               MEASURED_TRAFFIC_BYTES.get("C3/grad_main"))
     h.close()
     return out
 
