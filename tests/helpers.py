@@ -63,18 +63,21 @@ class RoundingBudget:
 
 def gradient_rounding_floor(A, y, x, dot_depth, sum_depth, lam=0.1):
     """First-order bound on what fp32 rounding can do to one worker's logistic gradient
-    grad_j = (1/m) sum_l r_l a_lj,  r_l = -y_l sigma(-y_l z_l),  z_l = a_l^T x  (dense A [m][d], fp64):
+    grad_j = (1/m) sum_l r_l a_lj,  r_l = -y_l sigma(-y_l z_l),  z_l = a_l^T x  (A [m][d]: dense, or a
+    scipy.sparse matrix):
       - z_l carries at most dot_depth * u * sum_j |a_lj x_j| (a dot product summed in `dot_depth` levels),
         which moves r_l by sigma_l (1 - sigma_l) times that;
       - the sum over rows carries at most sum_depth * u * |r_l a_lj| per term.
     Returned per coordinate; a coordinate that cancels to almost zero keeps this floor."""
     u = 2.0 ** -24
-    A = np.asarray(A, dtype=np.float64)
+    sparse = hasattr(A, "tocsr")                       # a scipy.sparse matrix is taken as it is
+    A = A.astype(np.float64) if sparse else np.asarray(A, dtype=np.float64)
+    absA = abs(A)
     x = np.asarray(x, dtype=np.float64)
     y = np.asarray(y, dtype=np.float64)
     z = A @ x
     sig = 1.0 / (1.0 + np.exp(y * z))                 # |r_l|
-    dz = dot_depth * u * (np.abs(A) @ np.abs(x))
+    dz = dot_depth * u * (absA @ np.abs(x))
     dr = sig * (1.0 - sig) * dz + sum_depth * u * sig
     reg = 2.0 * lam * np.abs(x) / (1.0 + x * x) ** 2               # the regulariser term's own rounding
-    return (np.abs(A).T @ dr) / A.shape[0] + 8 * u * reg
+    return np.asarray(absA.T @ dr).reshape(-1) / A.shape[0] + 8 * u * reg

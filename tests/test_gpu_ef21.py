@@ -282,6 +282,41 @@ def test_config4_full_size_step(gpu, oracle):
             g_prev = g.astype(np.float64)
 
 
+@pytest.mark.timeout(400)
+def test_config2_full_size_steps(gpu, oracle):
+    """Config 2 at full size, the launch configuration bench.py times: five iterations with the
+    library's own gradients against the oracle's: f(x^t) within 1e-4, the invariant g = mean g_i."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C2"]
+    print("C2 full size steps", flush=True)
+    W = workloads.logreg_dense(c["n"], c["d"], c["m"], seed=c["seed"])
+    P = oracle.LogRegDense(W.A, W.y, c["lam"])
+    A, y = to_gpu(torch, W.A), to_gpu(torch, W.y)
+    f_ref, f_gpu, first_diff, (x, g_i, g), st = run_both(
+        gpu, oracle, P, lambda h: h.set_problem_dense(A, y, c["lam"]), c["k"], c["gamma"], 5)
+    assert np.all(np.abs(f_gpu - f_ref) <= 1e-4 * np.abs(f_ref)), (f_ref, f_gpu, first_diff)
+    mean = g_i.astype(np.float64).mean(axis=0)
+    assert np.all(np.abs(g - mean) <= 1e-5 * np.abs(mean) + 1e-6 * np.abs(mean).max())
+
+
+@pytest.mark.timeout(600)
+def test_config3_full_size_steps(gpu, oracle):
+    """Config 3 at full size (CSR, 10^8 non-zeros, long-row Top-k with k = 500): three iterations."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C3"]
+    n, d, m = c["n"], c["d"], c["m"]
+    print("C3 full size steps", flush=True)
+    W = workloads.logreg_csr(n, d, m, c["nnz_per_row"], seed=c["seed"])
+    P = oracle.LogRegCSR(W.rowptr, W.col, W.val, W.y, n, m, d, c["lam"])
+    rp, col, val, y = (to_gpu(torch, W.rowptr, np.int64), to_gpu(torch, W.col, np.int32), to_gpu(torch, W.val),
+                       to_gpu(torch, W.y))
+    f_ref, f_gpu, first_diff, (x, g_i, g), st = run_both(
+        gpu, oracle, P, lambda h: h.set_problem_csr(rp, col, val, y, m, c["lam"]), c["k"], c["gamma"], 3)
+    assert np.all(np.abs(f_gpu - f_ref) <= 1e-4 * np.abs(f_ref)), (f_ref, f_gpu, first_diff)
+    mean = g_i.astype(np.float64).mean(axis=0)
+    assert np.all(np.abs(g - mean) <= 1e-5 * np.abs(mean) + 1e-6 * np.abs(mean).max())
+
+
 @pytest.mark.parametrize("n,d,m,k", [(5, 2000, 120, 20), (3, 99, 64, 7), (2, 8192, 40, 100), (2, 8200, 40, 100)])
 def test_step_with_internal_gradient_equals_supplied_gradient(gpu, n, d, m, k):
     """ef21_step(NULL) computes the dense gradient itself; the result must be bit for bit what

@@ -163,3 +163,59 @@ def test_csr_unsorted_columns(gpu, oracle):
         torch.cuda.synchronize()
     assert_grads_close(got.cpu().numpy(), P.grads(x.astype(np.float64)), densify(W), W.y, x, nnz / 64 + 8, 64,
                        "unsorted")
+
+
+@pytest.mark.timeout(400)
+def test_config2_full_size_gradient(gpu, oracle):
+    """Config 2 at full size (n = 20, m = 5000, d = 2000, 800 MB of rows): every worker's gradient, at
+    x = 0 (closed form -A^T y / 2m inside the oracle's pins) and at a random x."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C2"]
+    n, d, m = c["n"], c["d"], c["m"]
+    print("C2 full size gradient", flush=True)
+    W = workloads.logreg_dense(n, d, m, seed=c["seed"])
+    P = oracle.LogRegDense(W.A, W.y, c["lam"])
+    rng = np.random.default_rng(21)
+    with binding.EF21(n, d, c["k"], c["gamma"]) as h:
+        h.set_problem_dense(to_gpu(torch, W.A), to_gpu(torch, W.y), c["lam"])
+        for x in (np.zeros(d, np.float32), rng.standard_normal(d).astype(np.float32)):
+            got = h.local_grad(to_gpu(torch, x))
+            again = h.local_grad(to_gpu(torch, x))
+            torch.cuda.synchronize()
+            assert torch.equal(got, again)
+            assert_grads_close(got.cpu().numpy(), P.grads(x.astype(np.float64)), W.A, W.y, x, d / 64 + 8, 16,
+                               "C2 full size")
+
+
+@pytest.mark.timeout(600)
+def test_config3_full_size_gradient(gpu, oracle):
+    """Config 3 at full size (n = 100, m = 2000, d = 50000, 10^8 non-zeros): three workers' gradients
+    coordinate by coordinate (the rounding floor needs the worker's matrix), all workers through the
+    norm of the difference."""
+    import scipy.sparse as sp
+    torch, binding = gpu
+    c = workloads.CONFIGS["C3"]
+    n, d, m, nnz = c["n"], c["d"], c["m"], c["nnz_per_row"]
+    print("C3 full size gradient", flush=True)
+    W = workloads.logreg_csr(n, d, m, nnz, seed=c["seed"])
+    P = oracle.LogRegCSR(W.rowptr, W.col, W.val, W.y, n, m, d, c["lam"])
+    rng = np.random.default_rng(22)
+    x = rng.standard_normal(d).astype(np.float32)
+    with binding.EF21(n, d, c["k"], c["gamma"]) as h:
+        h.set_problem_csr(to_gpu(torch, W.rowptr, np.int64), to_gpu(torch, W.col, np.int32), to_gpu(torch, W.val),
+                          to_gpu(torch, W.y), m, c["lam"])
+        got = h.local_grad(to_gpu(torch, x))
+        again = h.local_grad(to_gpu(torch, x))
+        torch.cuda.synchronize()
+        assert torch.equal(got, again)
+    got = got.cpu().numpy()
+    ref = P.grads(x.astype(np.float64))
+    for i in (0, 57, 99):
+        lo, hi = W.rowptr[i * m], W.rowptr[(i + 1) * m]
+        A_i = sp.csr_matrix((W.val[lo:hi], W.col[lo:hi], W.rowptr[i * m:(i + 1) * m + 1] - lo), shape=(m, d))
+        bound = 1e-5 * np.abs(ref[i]) + gradient_rounding_floor(A_i, W.y[i], x, nnz / 64 + 8, 64)
+        err = np.abs(got[i].astype(np.float64) - ref[i])
+        assert np.all(err <= bound), f"worker {i}: max err {err.max():.3e}, {int((err > bound).sum())} bad"
+        assert np.median(bound) <= 5e-5 * np.max(np.abs(ref[i]))
+    rel = np.linalg.norm(got - ref, axis=1) / np.linalg.norm(ref, axis=1)
+    assert rel.max() <= 1e-6, f"relative error of the gradients in the 2-norm: {rel.max():.3e}"
