@@ -96,7 +96,36 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
     out["roofline"] = roofline(4.0 * n * m * d + 4.0 * n * m + 4.0 * d, per_kernel["grad_main"],
                                "logreg_dense_fused_kernel (grad_main)", MEASURED_TRAFFIC_BYTES.get(f"{name}/grad_main"))
     out["iteration_frac_of_hbm_peak"] = round(out["iteration_algorithmic_bytes"] / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    if name == "C0":      # launch-bound: the same iterations replayed from a HIP graph of 10 captured steps
+        out["hip_graph_10_steps"] = graph_replay(torch, h, steps)
     return out, (W, h)
+
+
+def graph_replay(torch, h, steps: int, per_graph: int = 10):
+    """ef21_step only enqueues kernels, so it can be captured: ms per iteration when `per_graph` steps are
+    captured into one HIP graph and the graph is replayed (reported beside the eager figure, never as it)."""
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        h.use_current_stream()
+        h.step()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(per_graph):
+                h.step()
+        replays = max(1, steps // per_graph)
+        graph.replay()
+        side.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        for _ in range(replays):
+            graph.replay()
+        e1.record(side)
+        side.synchronize()
+    h.use_current_stream()
+    ms = e0.elapsed_time(e1) / (replays * per_graph)
+    return {"ms_per_step": round(ms, 5), "value": round(1e3 / ms, 2), "unit": "EF21 iterations/s"}
 
 
 def bench_topk(torch, binding, workloads, steps: int, warmup: int):

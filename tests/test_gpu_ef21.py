@@ -359,3 +359,54 @@ def test_get_set_state_roundtrip_and_errors(gpu):
     for bad in [(0, 5, 1, 0.1), (2, 5, 6, 0.1), (2, 5, 1, -1.0)]:
         with pytest.raises(binding.EF21Error):
             binding.EF21(*bad)
+
+
+@pytest.mark.parametrize("case", ["dense_problem", "long_rows_large_k", "long_rows_small_k"])
+def test_step_replayed_from_a_hip_graph(gpu, case):
+    """ef21_step only enqueues kernels (no allocation, no memset, no host wait once the handle is warm), so
+    a caller may capture it into a HIP graph.  Every replay, with eager work and synchronisations in
+    between, must leave exactly the state that an eager handle has after the same number of steps."""
+    torch, binding = gpu
+    rng = np.random.default_rng(5)
+    if case == "dense_problem":
+        c = workloads.CONFIGS["C0"]
+        n, d, k, gamma = c["n"], c["d"], c["k"], c["gamma"]
+        W = workloads.logreg_dense(n, d, c["m"], seed=1)
+        A, y = to_gpu(torch, W.A), to_gpu(torch, W.y)
+        grads = None
+    else:
+        n, d, gamma = 3, 200_000, 0.1
+        k = 40_000 if case == "long_rows_large_k" else 300
+        grads = to_gpu(torch, rng.standard_normal((n, d)).astype(np.float32))
+
+    def fresh():
+        h = binding.EF21(n, d, k, gamma)
+        if grads is None:
+            h.set_problem_dense(A, y, 0.1)
+            x0 = torch.zeros(d, device="cuda")
+            h.set_state(x0, h.local_grad(x0), None)
+        return h
+
+    side = torch.cuda.Stream()
+    with fresh() as eager, fresh() as replayed:
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            replayed.use_current_stream()
+            replayed.step(grads)                       # warm-up: buffers and kernel attributes exist afterwards
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                replayed.step(grads)
+        eager.step(grads)
+        torch.cuda.synchronize()
+        for r in range(4):
+            graph.replay()
+            eager.step(grads)
+            torch.cuda.synchronize()
+            scratch = torch.randn(1000, device="cuda").sum().item()      # unrelated eager work between replays
+            assert np.isfinite(scratch)
+            got = replayed.get_state() + replayed.get_messages()     # copies on each handle's own stream
+            ref = eager.get_state() + eager.get_messages()
+            torch.cuda.synchronize()
+            for a, b, name in zip(got, ref, ("x", "g_i", "g", "message positions", "message values")):
+                assert torch.equal(a, b), f"replay {r}: {name} differ from the eager handle"
