@@ -68,6 +68,7 @@ def roofline(bytes_per_launch: float, ms: float, kernel: str, traffic=None) -> d
     achieved = bytes_per_launch / (ms * 1e-3) / 1e9
     return {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "frac_by_traffic": None if traffic is None else round(traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "algorithmic_bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(ms, 5)}
 
 
@@ -99,6 +100,28 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
     if name == "C0":      # launch-bound: the same iterations replayed from a HIP graph of 10 captured steps
         out["hip_graph_10_steps"] = graph_replay(torch, h, steps)
     return out, (W, h)
+
+
+def hbm_ceiling(torch, binding, gib: int = 1, reps: int = 10):
+    """What the simplest kernels get out of this GPU's HBM: one read of `gib` GiB, and a copy of it."""
+    src = torch.zeros(gib << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, device="cuda")
+    nbytes = src.numel() * 4
+    out = {}
+    for name, fn, moved in (("read", lambda: binding.ef21_hbm_read(src, sink), nbytes),
+                            ("copy", lambda: binding.ef21_hbm_copy(dst, src), 2 * nbytes)):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[f"{name}_GBps"] = round(moved / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9, 1)
+    out["note"] = f"plain kernels on {gib} GiB: a read with non-temporal loads; a copy (read + written bytes counted)"
+    return out
 
 
 def graph_replay(torch, h, steps: int, per_graph: int = 10):
@@ -265,6 +288,7 @@ def main() -> int:
     which = set(filter(None, args.only.split(","))) or {"C0", "C1", "C2", "C3", "C4"}
     K, Wm = args.steps, args.warmup
 
+    ceiling = hbm_ceiling(torch, binding)
     head, (W2, h2) = bench_dense(torch, binding, workloads, "C2", K, Wm)
     extra = {}
     cpu = None
@@ -296,6 +320,7 @@ def main() -> int:
                                f"gamma={c2['gamma']}, lambda={c2['lam']}", "n": c2["n"], "d": c2["d"], "m": c2["m"],
                    "k": c2["k"]},
         "roofline": head["roofline"],
+        "hbm_measured_ceiling": ceiling,
         "cpu_baseline": cpu,
         "kernel_ms": head["kernel_ms"],
         "iteration_frac_of_hbm_peak": head["iteration_frac_of_hbm_peak"],

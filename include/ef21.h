@@ -153,6 +153,18 @@ int ef21_set_timing(ef21_handle h, int enabled);
 int ef21_get_timing(ef21_handle h, double *ms, int64_t *launches, int reset);
 const char *ef21_kernel_name(int kernel_class);
 
+/*
+ * Plain streaming kernels, for measurement only (not part of the paper's method): what this GPU's HBM
+ * delivers to the simplest possible kernel, to set beside the vendor's peak.  Both take DEVICE pointers to
+ * 16-byte aligned buffers of `bytes` bytes (a multiple of 16) and enqueue one kernel on `hip_stream`.
+ *   ef21_hbm_read   reads `src` once with the same non-temporal loads the library's kernels use and
+ *                   writes one float to sink[0] (sink may alias nothing else)
+ *   ef21_hbm_copy   dst <- src
+ * EF21_EINVAL: NULL pointer, misaligned pointer, bytes < 16 or not a multiple of 16.
+ */
+int ef21_hbm_read(const void *src, int64_t bytes, float *sink, void *hip_stream);
+int ef21_hbm_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,7 @@ SYMBOLS = (
     "ef21_last_error", "ef21_create", "ef21_destroy", "ef21_set_stream", "ef21_topk",
     "ef21_set_problem_dense", "ef21_set_problem_csr", "ef21_set_state", "ef21_get_state",
     "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
+    "ef21_hbm_read", "ef21_hbm_copy",
 )
 K_COUNT = 9
 
@@ -63,6 +64,8 @@ def load_library() -> C.CDLL:
     lib.ef21_set_timing.argtypes = [p, C.c_int]
     lib.ef21_get_timing.argtypes = [p, p, p, C.c_int]
     lib.ef21_kernel_name.argtypes = [C.c_int]
+    lib.ef21_hbm_read.argtypes = [p, C.c_int64, p, p]
+    lib.ef21_hbm_copy.argtypes = [p, p, C.c_int64, p]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = C.c_int
     lib.ef21_kernel_name.restype = C.c_char_p
@@ -108,6 +111,20 @@ def ef21_topk(rows: torch.Tensor, k: int, out_idx: torch.Tensor | None = None,
     _check(lib.ef21_topk(_dev(rows, torch.float32), n, d, k, _dev(out_idx, torch.int32), _dev(out_val, torch.float32),
                          _current_stream_ptr()))
     return out_idx, out_val
+
+
+def ef21_hbm_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """One plain read of `src` (ef21_hbm_read) on torch's current stream; measurement only."""
+    lib = load_library()
+    _check(lib.ef21_hbm_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _current_stream_ptr()))
+
+
+def ef21_hbm_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """dst <- src by a plain copy kernel (ef21_hbm_copy) on torch's current stream; measurement only."""
+    lib = load_library()
+    if dst.numel() * dst.element_size() != src.numel() * src.element_size():
+        raise ValueError("dst and src must have the same size in bytes")
+    _check(lib.ef21_hbm_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _current_stream_ptr()))
 
 
 class EF21:

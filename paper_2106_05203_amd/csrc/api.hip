@@ -465,6 +465,26 @@ int ef21_get_timing(ef21_handle h, double *ms, int64_t *launches, int reset) {
     return EF21_OK;
 }
 
+static int check_hbm_args(const void *a, const void *b, int64_t bytes) {
+    if (!a || !b) return fail(EF21_EINVAL, "pointers must not be NULL");
+    if (bytes < 16 || bytes % 16 != 0) return fail(EF21_EINVAL, "bytes must be a positive multiple of 16");
+    if ((uintptr_t)a % 16 != 0 || (uintptr_t)b % 4 != 0) return fail(EF21_EINVAL, "buffers must be 16-byte aligned");
+    return EF21_OK;
+}
+
+int ef21_hbm_read(const void *src, int64_t bytes, float *sink, void *hip_stream) {
+    if (int rc = check_hbm_args(src, sink, bytes)) return rc;
+    EF21_HIP(ef21::launch_hbm_read(src, bytes / 16, sink, (hipStream_t)hip_stream));
+    return EF21_OK;
+}
+
+int ef21_hbm_copy(void *dst, const void *src, int64_t bytes, void *hip_stream) {
+    if (int rc = check_hbm_args(src, dst, bytes)) return rc;
+    if ((uintptr_t)dst % 16 != 0) return fail(EF21_EINVAL, "buffers must be 16-byte aligned");
+    EF21_HIP(ef21::launch_hbm_copy(dst, src, bytes / 16, (hipStream_t)hip_stream));
+    return EF21_OK;
+}
+
 const char *ef21_kernel_name(int kernel_class) {
     static const char *names[EF21_K_COUNT] = {"grad_main",   "grad_aux",   "topk_row",  "topk_collect", "topk_select",
                                               "topk_refine", "topk_count", "topk_emit", "model_step"};

@@ -105,4 +105,9 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
                                   float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker());
 
+// Plain streaming kernels for measuring what the HBM delivers: one read of `n16` 16-byte words (their sum goes
+// to sink[0]), and a copy.
+hipError_t launch_hbm_read(const void *src, int64_t n16, float *sink, hipStream_t stream);
+hipError_t launch_hbm_copy(void *dst, const void *src, int64_t n16, hipStream_t stream);
+
 }  // namespace ef21

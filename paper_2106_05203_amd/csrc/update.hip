@@ -214,6 +214,25 @@ __global__ __launch_bounds__(kSmallThreads) void aggregate_small_kernel(const in
     }
 }
 
+// ---- plain streaming kernels (measurement only): 2048 workgroups, each thread strides over the buffer
+__global__ __launch_bounds__(kThreads) void hbm_read_kernel(const float *__restrict__ src, int64_t n16,
+                                                            float *__restrict__ sink) {
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    float acc = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) {
+        const float4 v = stream_load4(src + 4 * i);
+        acc += (v.x + v.y) + (v.z + v.w);
+    }
+    acc = wave_sum(acc);
+    if (acc == 1.2345e-31f) sink[0] = acc;       // keeps the loads alive; practically never stores
+}
+
+__global__ __launch_bounds__(kThreads) void hbm_copy_kernel(float4 *__restrict__ dst, const float4 *__restrict__ src,
+                                                            int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 unsigned grid_for(int64_t items, int64_t cap) {
     int64_t blocks = (items + kThreads - 1) / kThreads;
     if (blocks > cap) blocks = cap;
@@ -269,6 +288,18 @@ hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int
     else
         hipLaunchKernelGGL((aggregate_kernel<false, false>), grid, block, 0, stream, idx, val, start, n, k, d, nblk, g,
                            x, inv_n, -gamma);
+    return hipGetLastError();
+}
+
+hipError_t launch_hbm_read(const void *src, int64_t n16, float *sink, hipStream_t stream) {
+    hipLaunchKernelGGL(hbm_read_kernel, dim3(grid_for(n16, 2048)), dim3(kThreads), 0, stream, (const float *)src, n16,
+                       sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_hbm_copy(void *dst, const void *src, int64_t n16, hipStream_t stream) {
+    hipLaunchKernelGGL(hbm_copy_kernel, dim3(grid_for(n16, 8192)), dim3(kThreads), 0, stream, (float4 *)dst,
+                       (const float4 *)src, n16);
     return hipGetLastError();
 }
 
