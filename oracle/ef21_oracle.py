@@ -4,7 +4,8 @@ Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import 
 It imports nothing from the HIP package and the HIP package imports nothing from here.
 
 The iteration of Algorithm 2 (EF21, multiple nodes) is composed here from the C routines, one
-call per line of the algorithm, in the order the paper states; all state lives in fp64 numpy
+call per line of the algorithm, in the order the paper states, and so is Algorithm 3 (EF21+), whose
+distortions and choice are written out in numpy; all state lives in fp64 numpy
 arrays (``storage_f32=True`` rounds every stored value to fp32, see the C file's header).
 """
 from __future__ import annotations
@@ -253,6 +254,66 @@ def iteration(state: EF21State, grads_at, k: int, gamma: float, order: str = "gr
         model_step(state, gamma, storage_f32)
     else:
         raise ValueError(order)
+
+
+# ------------------------------------------------------------------ Algorithm 3 (EF21+, multi-node)
+def plus_update(state: EF21State, grads, k: int, storage_f32: bool = True):
+    """Lines 5 to 8 and 10 of Algorithm 3 for all workers, in place, with C = Top-k and s = grad f_i(x):
+         b = C(s)                                  (line 5, the plain compressor)
+         m = g_i + C(s - g_i)                      (line 6, the Markov compressor)
+         B = ||b - s||^2,  M = ||m - s||^2         (line 7; fp64 sums of the stored values)
+         g_i <- m if M <= B else b                 (line 8)
+         g   <- (1/n) sum_i g_i                    (line 10)
+    The message a worker sends is the k pairs of whichever compressor it chose, kept in state.msg_*.
+    Returns (branch [n] int32: 1 where the plain compressor was chosen, B [n], M [n])."""
+    grads = round_storage(grads, storage_f32)
+    n, d = state.g_i.shape
+    assert grads.shape == (n, d)
+    idx = np.empty((n, k), dtype=np.int32)
+    val = np.empty((n, k), dtype=np.float64)
+    branch = np.zeros(n, dtype=np.int32)
+    Bs, Ms = np.empty(n), np.empty(n)
+    for i in range(n):
+        s, g_old = grads[i], state.g_i[i]
+        ib, vb = topk(s, k)
+        b = np.zeros(d)
+        b[ib] = vb
+        if storage_f32:      # the difference is one fp32 subtraction, the update one fp32 addition
+            v = (s.astype(np.float32) - g_old.astype(np.float32)).astype(np.float64)
+        else:
+            v = s - g_old
+        im, vm = topk(v, k)
+        m = g_old.copy()
+        if storage_f32:
+            m[im] = (g_old[im].astype(np.float32) + vm.astype(np.float32)).astype(np.float64)
+        else:
+            m[im] = g_old[im] + vm
+        Bs[i] = float(np.sum((b - s) ** 2))
+        Ms[i] = float(np.sum((m - s) ** 2))
+        if Ms[i] <= Bs[i]:
+            state.g_i[i], idx[i], val[i] = m, im, vm
+        else:
+            state.g_i[i], idx[i], val[i], branch[i] = b, ib, vb, 1
+    state.g[:] = mean_rows(state.g_i, storage_f32)
+    state.msg_idx, state.msg_val = idx, val
+    return branch, Bs, Ms
+
+
+def iteration_plus(state: EF21State, grads_at, k: int, gamma: float, order: str = "grad_first",
+                   storage_f32: bool = True):
+    """One pass of the loop body of Algorithm 3 (EF21+); arguments and the two orders as in `iteration`.
+    Returns what plus_update returns."""
+    def grads_now():
+        return grads_at(state.x) if callable(grads_at) else grads_at
+
+    if order == "step_first":
+        model_step(state, gamma, storage_f32)
+        return plus_update(state, grads_now(), k, storage_f32)
+    if order == "grad_first":
+        out = plus_update(state, grads_now(), k, storage_f32)
+        model_step(state, gamma, storage_f32)
+        return out
+    raise ValueError(order)
 
 
 # ------------------------------------------------------------------------ theory (Section 3.4)
