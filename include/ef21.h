@@ -42,10 +42,11 @@ enum {
     EF21_ESTATE = -4  /* call not possible in the handle's state (e.g. no problem set)   */
 };
 
-/* flags of ef21_step */
+/* flags of ef21_step (one order, optionally or-ed with EF21_PLUS) */
 enum {
     EF21_ORDER_GRAD_FIRST = 0u, /* lines 5, 6, 8 at the current x, then line 3 (default)      */
-    EF21_ORDER_STEP_FIRST = 1u  /* line 3, then lines 5, 6, 8 at the new x (loop as printed)  */
+    EF21_ORDER_STEP_FIRST = 1u, /* line 3, then lines 5, 6, 8 at the new x (loop as printed)  */
+    EF21_PLUS = 2u              /* the loop body of Algorithm 3 (EF21+) instead of Algorithm 2 */
 };
 
 /* Human-readable text of the calling thread's last failure ("" if none).  Library-owned. */
@@ -139,6 +140,21 @@ int ef21_local_grad(ef21_handle h, const float *x, float *out_grad);
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags);
 
 /*
+ * With EF21_PLUS in flags, ef21_step runs the loop body of Algorithm 3 (EF21+, Section 3.5) on the same
+ * state: with s = grad f_i(x) (or the supplied row) every worker forms b = C(s) (line 5) and
+ * m = g_i + C(s - g_i) (line 6), C = Top-k as in ef21_topk; the distortions B = ||b - s||^2 and
+ * M = ||m - s||^2 (line 7) are computed in fp64 as ||s||^2 and ||s - g_i||^2 minus the sums of the kept
+ * squares, every sum in a fixed order; g_i <- m if M <= B, else b (line 8); g <- (1/n) sum_i g_i, the
+ * rows added in worker order in fp64 and the mean rounded once (line 10).  ef21_get_messages then returns, per worker, the k pairs
+ * of the compressor it chose.  The first such call on a handle allocates (and waits for the stream).
+ *
+ * ef21_get_choices copies out what the last EF21_PLUS step decided: branch [n] int32 (1 = the plain
+ * compressor b was chosen, 0 = the Markov compressor m) and distortions [n][2] fp64 (B_i, M_i); either
+ * pointer may be NULL.  EF21_ESTATE before the first EF21_PLUS step.
+ */
+int ef21_get_choices(ef21_handle h, int32_t *branch, double *distortions);
+
+/*
  * Per-kernel timing, for measurement only (not part of the paper's method).  While enabled,
  * ef21_step and ef21_local_grad record one HIP event on the handle's stream after each kernel
  * they launch; the time between consecutive events is charged to the class of the later kernel.
@@ -146,9 +162,9 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags);
  * accumulated milliseconds per class and launches[EF21_K_COUNT] the number of intervals (either
  * may be NULL); reset != 0 clears the sums.  Classes, in order (names from ef21_kernel_name):
  * grad_main, grad_aux, topk_row, topk_collect, topk_select, topk_refine, topk_count, topk_emit,
- * model_step.
+ * model_step, plus (what is particular to Algorithm 3).
  */
-enum { EF21_K_COUNT = 9 };
+enum { EF21_K_COUNT = 10 };
 int ef21_set_timing(ef21_handle h, int enabled);
 int ef21_get_timing(ef21_handle h, double *ms, int64_t *launches, int reset);
 const char *ef21_kernel_name(int kernel_class);

@@ -15,16 +15,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libef21.so")
 
 EF21_OK, EF21_EINVAL, EF21_ENOMEM, EF21_EHIP, EF21_ESTATE = 0, -1, -2, -3, -4
-ORDER_GRAD_FIRST, ORDER_STEP_FIRST = 0, 1
+ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS = 0, 1, 2
 
 # every symbol include/ef21.h declares
 SYMBOLS = (
     "ef21_last_error", "ef21_create", "ef21_destroy", "ef21_set_stream", "ef21_topk",
     "ef21_set_problem_dense", "ef21_set_problem_csr", "ef21_set_state", "ef21_get_state",
     "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
-    "ef21_hbm_read", "ef21_hbm_copy",
+    "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices",
 )
-K_COUNT = 9
+K_COUNT = 10
 
 
 class EF21Error(RuntimeError):
@@ -64,6 +64,7 @@ def load_library() -> C.CDLL:
     lib.ef21_set_timing.argtypes = [p, C.c_int]
     lib.ef21_get_timing.argtypes = [p, p, p, C.c_int]
     lib.ef21_kernel_name.argtypes = [C.c_int]
+    lib.ef21_get_choices.argtypes = [p, p, p]
     lib.ef21_hbm_read.argtypes = [p, C.c_int64, p, p]
     lib.ef21_hbm_copy.argtypes = [p, p, C.c_int64, p]
     for name in SYMBOLS[2:]:
@@ -212,6 +213,15 @@ class EF21:
         with torch.cuda.device(self.device):
             _check(self._lib.ef21_get_messages(self._h, idx.data_ptr(), val.data_ptr()))
         return idx, val
+
+    def get_choices(self):
+        """(branch [n] int32: 1 = plain compressor chosen, distortions [n][2] float64: B_i, M_i) of the last
+        step taken with PLUS."""
+        branch = torch.empty(self.n, dtype=torch.int32, device=self.device)
+        bm = torch.empty((self.n, 2), dtype=torch.float64, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self._lib.ef21_get_choices(self._h, branch.data_ptr(), bm.data_ptr()))
+        return branch, bm
 
     # -- measurement
     def set_timing(self, enabled: bool) -> None:

@@ -89,6 +89,12 @@ struct ef21_ctx {
     void *csr_index = nullptr;      // column-range index of the attached CSR problem
     bool csr_indexed = false;
     int64_t nnz = 0;                // entries of the attached CSR problem
+    // Algorithm 3 (allocated by the first EF21_PLUS step)
+    int32_t *plus_idx = nullptr;    // [2][n][k]: C(s), then C(s - g_i)
+    float *plus_val = nullptr;
+    void *plus_scratch = nullptr;
+    int32_t *plus_branch = nullptr; // [n]
+    double *plus_bm = nullptr;      // [n][2]
     Timing timing;
 };
 
@@ -166,6 +172,11 @@ void free_ctx(ef21_ctx *c) {
     (void)hipFree(c->topk_ws);
     (void)hipFree(c->csr_index);
     (void)hipFree(c->agg_index);
+    (void)hipFree(c->plus_idx);
+    (void)hipFree(c->plus_val);
+    (void)hipFree(c->plus_scratch);
+    (void)hipFree(c->plus_branch);
+    (void)hipFree(c->plus_bm);
     delete c;
 }
 
@@ -412,18 +423,78 @@ int ef21_local_grad(ef21_handle h, const float *x, float *out_grad) {
     return enqueue_local_grad(h, x ? x : h->x, out_grad);
 }
 
+// Buffers of Algorithm 3, allocated by the first EF21_PLUS step of a handle.
+static int ensure_plus_buffers(ef21_ctx *c) {
+    if (c->plus_bm) return EF21_OK;
+    const size_t nk = (size_t)c->n * (size_t)c->k;
+    EF21_HIP(hipStreamSynchronize(c->stream));
+    if (hipMalloc((void **)&c->plus_idx, sizeof(int32_t) * 2 * nk) != hipSuccess ||
+        hipMalloc((void **)&c->plus_val, sizeof(float) * 2 * nk) != hipSuccess ||
+        hipMalloc(&c->plus_scratch, ef21::plus_scratch_bytes(c->n, c->d)) != hipSuccess ||
+        hipMalloc((void **)&c->plus_branch, sizeof(int32_t) * (size_t)c->n) != hipSuccess ||
+        hipMalloc((void **)&c->plus_bm, sizeof(double) * 2 * (size_t)c->n) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(c->plus_idx);
+        (void)hipFree(c->plus_val);
+        (void)hipFree(c->plus_scratch);
+        (void)hipFree(c->plus_branch);
+        (void)hipFree(c->plus_bm);
+        c->plus_idx = nullptr;
+        c->plus_val = nullptr;
+        c->plus_scratch = nullptr;
+        c->plus_branch = nullptr;
+        c->plus_bm = nullptr;
+        return fail(EF21_ENOMEM, "hipMalloc of the EF21+ buffers failed");
+    }
+    return EF21_OK;
+}
+
+// Lines 5 to 8 and 10 of Algorithm 3 for all workers (the model step is the caller's).
+static int enqueue_plus(ef21_ctx *h, const float *grads, const ef21::Marker &mk) {
+    const size_t nk = (size_t)h->n * (size_t)h->k;
+    int32_t *idx_b = h->plus_idx, *idx_m = h->plus_idx + nk;
+    float *val_b = h->plus_val, *val_m = h->plus_val + nk;
+    ef21::TopkArgs plain{grads, nullptr, h->n, h->d, h->k, idx_b, val_b, nullptr};        // line 5: C(s)
+    if (int rc = enqueue_topk(plain, h->topk_ws, h->stream, mk)) return rc;
+    ef21::TopkArgs markov{grads, h->g_i, h->n, h->d, h->k, idx_m, val_m, nullptr};        // line 6: C(s - g_i)
+    if (int rc = enqueue_topk(markov, h->topk_ws, h->stream, mk)) return rc;
+    hipError_t st = ef21::launch_plus_choose(grads, h->g_i, h->n, h->d, h->k, idx_b, val_b, idx_m, val_m,
+                                             h->plus_scratch, h->plus_branch, h->plus_bm, h->msg_idx, h->msg_val,
+                                             h->stream);                                  // lines 7 and 8
+    if (st == hipSuccess) st = ef21::launch_mean_rows(h->g_i, h->g, h->n, h->d, h->stream);   // line 10
+    mk(ef21::K_PLUS);
+    if (st != hipSuccess) return fail_hip(st, "EF21+ kernel launch");
+    return EF21_OK;
+}
+
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
     if (int rc = check_handle(h)) return rc;
-    if (flags > EF21_ORDER_STEP_FIRST) return fail(EF21_EINVAL, "unknown flags");
+    if (flags > (EF21_ORDER_STEP_FIRST | EF21_PLUS)) return fail(EF21_EINVAL, "unknown flags");
     if (!grads && h->kind == kNone)
         return fail(EF21_ESTATE, "grads is NULL and no problem is attached to compute them from");
-    const bool step_first = flags == EF21_ORDER_STEP_FIRST;
+    const bool step_first = (flags & EF21_ORDER_STEP_FIRST) != 0;
+    const bool plus = (flags & EF21_PLUS) != 0;
+    if (plus)
+        if (int rc = ensure_plus_buffers(h)) return rc;
     const ef21::Marker mk = marker_of(h);
     mk(-1);
     if (step_first) {   // Algorithm 2, line 3
         hipError_t st = ef21::launch_model_step(h->x, h->g, h->d, h->gamma, h->stream);
         mk(ef21::K_MODEL_STEP);
         if (st != hipSuccess) return fail_hip(st, "model step launch");
+    }
+    if (plus) {
+        if (!grads) {
+            if (int rc = enqueue_local_grad(h, h->x, h->grad)) return rc;
+            grads = h->grad;
+        }
+        if (int rc = enqueue_plus(h, grads, mk)) return rc;
+        if (!step_first) {
+            hipError_t st = ef21::launch_model_step(h->x, h->g, h->d, h->gamma, h->stream);
+            mk(ef21::K_MODEL_STEP);
+            if (st != hipSuccess) return fail_hip(st, "model step launch");
+        }
+        return EF21_OK;
     }
     ef21::GradParts parts;
     if (!grads) {
@@ -439,6 +510,18 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
                                            h->gamma, h->agg_index, h->stream);
     mk(ef21::K_MODEL_STEP);
     if (st != hipSuccess) return fail_hip(st, "aggregation launch");
+    return EF21_OK;
+}
+
+int ef21_get_choices(ef21_handle h, int32_t *branch, double *distortions) {
+    if (int rc = check_handle(h)) return rc;
+    if (!h->plus_bm) return fail(EF21_ESTATE, "no EF21_PLUS step has been taken on this handle");
+    if (branch)
+        EF21_HIP(hipMemcpyAsync(branch, h->plus_branch, sizeof(int32_t) * (size_t)h->n, hipMemcpyDeviceToDevice,
+                                h->stream));
+    if (distortions)
+        EF21_HIP(hipMemcpyAsync(distortions, h->plus_bm, sizeof(double) * 2 * (size_t)h->n, hipMemcpyDeviceToDevice,
+                                h->stream));
     return EF21_OK;
 }
 
@@ -487,7 +570,8 @@ int ef21_hbm_copy(void *dst, const void *src, int64_t bytes, void *hip_stream) {
 
 const char *ef21_kernel_name(int kernel_class) {
     static const char *names[EF21_K_COUNT] = {"grad_main",   "grad_aux",   "topk_row",  "topk_collect", "topk_select",
-                                              "topk_refine", "topk_count", "topk_emit", "model_step"};
+                                              "topk_refine", "topk_count", "topk_emit", "model_step",
+                                              "plus"};
     return (kernel_class >= 0 && kernel_class < EF21_K_COUNT) ? names[kernel_class] : "";
 }
 

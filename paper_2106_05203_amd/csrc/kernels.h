@@ -17,6 +17,7 @@ enum KernelId {
     K_TOPK_COUNT,      // long rows, large k: per-slot counts
     K_TOPK_EMIT,       // long rows, large k: ordered emission (+ fused update)
     K_MODEL_STEP,      // g <- g + mean of the messages and / or x <- x - gamma g
+    K_PLUS,            // Algorithm 3: distortions, choice and update of g_i, mean of the rows
     K_COUNT
 };
 
@@ -104,6 +105,15 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
                                   float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker());
+
+// Algorithm 3 (EF21+), lines 7 and 8, for all workers: from the gradients s [n][d], the estimators g_i [n][d]
+// (updated in place) and the two Top-k results (idx_b, val_b) = C(s), (idx_m, val_m) = C(s - g_i), all [n][k]:
+// BM[i] = (B_i, M_i), branch[i] = 1 where the plain compressor wins (M_i > B_i), (msg_idx, msg_val) = the chosen
+// pairs, and g_i <- b or m accordingly.  scratch: plus_scratch_bytes(n, d) bytes.
+size_t plus_scratch_bytes(int32_t n, int64_t d);
+hipError_t launch_plus_choose(const float *s, float *g_i, int32_t n, int64_t d, int64_t k, const int32_t *idx_b,
+                              const float *val_b, const int32_t *idx_m, const float *val_m, void *scratch,
+                              int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream);
 
 // Plain streaming kernels for measuring what the HBM delivers: one read of `n16` 16-byte words (their sum goes
 // to sink[0]), and a copy.

@@ -1,0 +1,174 @@
+"""GPU parity of EF21+ (Algorithm 3; ef21_step with EF21_PLUS through the C ABI) against the CPU oracle.
+
+Bars: the distortions B_i, M_i within 1e-9 relative (both sides sum in fp64, in different orders, and
+the library takes the difference form ||.||^2 - kept squares); the choice of line 8 identical wherever
+|M - B| exceeds that noise; then messages, g_i and g bit for bit, x within 1e-5 relative per coordinate
+plus the rounding of one fused multiply-add; f(x^t) within 1e-4 relative over a run."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from helpers import same_bits
+from paper_2106_05203_amd import workloads
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2106_05203_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    return torch, binding
+
+
+def to_gpu(torch, a, dtype=np.float32):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
+
+
+def compare_plus_step(torch, h, st, ref_choice, x_before, gamma, what):
+    """State of the handle against the oracle's after one EF21+ step."""
+    branch_ref, B_ref, M_ref = ref_choice
+    branch, bm = (t.cpu().numpy() for t in h.get_choices())
+    x, g_i, g = (t.cpu().numpy() for t in h.get_state())
+    idx, val = (t.cpu().numpy() for t in h.get_messages())
+    scale = np.maximum(np.maximum(B_ref, M_ref), 1e-300)
+    # the difference form loses what the kept squares take away: noise relative to the norms, not to B and M
+    noise = 1e-12 * np.maximum(B_ref, M_ref) + 1e-13 * (scale + np.abs(bm).max(axis=1))
+    tol = 1e-9 * scale + noise
+    assert np.all(np.abs(bm[:, 0] - B_ref) <= tol), f"{what}: B {bm[:, 0]} vs {B_ref}"
+    assert np.all(np.abs(bm[:, 1] - M_ref) <= tol), f"{what}: M {bm[:, 1]} vs {M_ref}"
+    decided = np.abs(M_ref - B_ref) > 4 * tol
+    assert np.array_equal(branch[decided], branch_ref[decided]), f"{what}: choices {branch} vs {branch_ref}"
+    same = branch == branch_ref
+    for i in np.nonzero(same)[0]:
+        assert np.array_equal(idx[i], st.msg_idx[i]), f"{what}: message positions of worker {i}"
+        assert same_bits(val[i], st.msg_val[i].astype(np.float32)), f"{what}: message values of worker {i}"
+        assert same_bits(g_i[i], st.g_i[i].astype(np.float32)), f"{what}: g_i row {i}"
+    if same.all():
+        assert same_bits(g, st.g.astype(np.float32)), f"{what}: g"
+        bound = 1e-5 * np.abs(st.x) + 2.0 ** -23 * (np.abs(x_before) + gamma * np.abs(st.g))
+        assert np.all(np.abs(x - st.x) <= bound), f"{what}: x"
+    return same.all()
+
+
+def test_hand_worked_example(gpu, oracle):
+    torch, binding = gpu
+    ex = json.load(open(os.path.join(HERE, "golden", "ef21_plus_hand_example.json")))
+    want = ex["expect"]
+    with binding.EF21(ex["n"], ex["d"], ex["k"], ex["gamma"]) as h:
+        h.set_state(to_gpu(torch, ex["x"]), to_gpu(torch, ex["g_i"]), None)
+        h.step(to_gpu(torch, ex["grads"]), binding.PLUS)
+        torch.cuda.synchronize()
+        branch, bm = (t.cpu().numpy() for t in h.get_choices())
+        x, g_i, g = (t.cpu().numpy() for t in h.get_state())
+        idx, val = (t.cpu().numpy() for t in h.get_messages())
+    assert branch.tolist() == want["branch"]
+    assert bm[:, 0].tolist() == want["B"] and bm[:, 1].tolist() == want["M"]
+    assert g_i.tolist() == want["g_i"] and g.tolist() == want["g"] and x.tolist() == want["x_after_step"]
+    assert idx.tolist() == want["msg_idx"] and val.tolist() == want["msg_val"]
+
+
+@pytest.mark.parametrize("n,d,k", [(1, 1, 1), (4, 100, 1), (6, 1000, 37), (5, 4099, 41), (20, 2000, 20),
+                                   (6, 70001, 700), (4, 300_000, 3000), (3, 300_000, 60_000)])
+@pytest.mark.parametrize("order", ["grad_first", "step_first"])
+def test_single_step_from_oracle_state(gpu, oracle, n, d, k, order):
+    """Estimators of very different quality, so that both branches of line 8 occur: rows with g_i = 0 (the two
+    compressors coincide, M = B, the Markov branch by the tie rule), rows close to the gradient (Markov
+    wins) and rows far off (the plain compressor wins)."""
+    torch, binding = gpu
+    print(f"EF21+ step case n={n} d={d} k={k} {order}", flush=True)
+    rng = np.random.default_rng(n * 1000 + d + k)
+    gamma = 0.25
+    x0 = rng.standard_normal(d).astype(np.float32)
+    base = rng.standard_normal((n, d)).astype(np.float32)
+    off = np.resize(np.array([0.0, 0.05, 5.0, 0.3], np.float32), n)[:, None]
+    g_i0 = (base * (off > 0) + off * rng.standard_normal((n, d))).astype(np.float32)
+    g_i0[off[:, 0] == 0] = 0.0
+    g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    flag = binding.PLUS | (binding.ORDER_STEP_FIRST if order == "step_first" else binding.ORDER_GRAD_FIRST)
+    seen = set()
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+        for t in range(3):
+            grads = (base + 0.3 * rng.standard_normal((n, d))).astype(np.float32)
+            x_before = st.x.copy() if order == "grad_first" else None
+            choice = oracle.iteration_plus(st, grads.astype(np.float64), k, gamma, order=order)
+            if x_before is None:
+                x_before = st.x.copy()          # step-first: x moved before the gradients were used
+            h.step(to_gpu(torch, grads), flag)
+            torch.cuda.synchronize()
+            seen.update(choice[0].tolist())
+            if order == "grad_first":
+                agreed = compare_plus_step(torch, h, st, choice, x_before, gamma, f"step {t}")
+            else:                                # x was stepped with the previous g: compare the rest
+                agreed = compare_plus_step(torch, h, st, choice, st.x, 0.0, f"step {t}")
+            # one state for the next step, whatever the near-ties did
+            h.set_state(to_gpu(torch, st.x), to_gpu(torch, st.g_i), to_gpu(torch, st.g))
+    if n >= 4 and k < d:
+        assert seen == {0, 1}, "the case should exercise both branches"
+
+
+def test_k_equals_d(gpu, oracle):
+    """Top-d keeps everything: B = 0 and M is rounding noise on both sides, so either branch may be
+    taken; both give g_i = grad f_i up to one rounding, and the step is the gradient step."""
+    torch, binding = gpu
+    rng = np.random.default_rng(8)
+    n, d, gamma = 3, 500, 0.1
+    g_i0 = rng.standard_normal((n, d)).astype(np.float32)
+    grads = rng.standard_normal((n, d)).astype(np.float32)
+    with binding.EF21(n, d, d, gamma) as h:
+        h.set_state(to_gpu(torch, np.zeros(d)), to_gpu(torch, g_i0), None)
+        h.step(to_gpu(torch, grads), binding.PLUS)
+        torch.cuda.synchronize()
+        x, g_i, g = (t.cpu().numpy() for t in h.get_state())
+        _, bm = (t.cpu().numpy() for t in h.get_choices())
+    assert np.all(np.abs(g_i - grads) <= 2.0 ** -23 * (np.abs(grads) + np.abs(g_i0)))
+    assert np.all(np.abs(bm) <= 1e-12 * (grads.astype(np.float64) ** 2).sum())
+    mean = grads.astype(np.float64).mean(axis=0)
+    assert np.allclose(x, -gamma * mean, rtol=1e-5, atol=1e-6)
+
+
+def test_run_on_a_dense_problem(gpu, oracle):
+    """Fifty iterations of EF21+ with the library's own gradients (config 0's problem, k = 2; half of the
+    workers start from a useless g_i): f(x^t) within 1e-4 of the oracle's, both branches in use."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C0"]
+    n, d, m, k, gamma = c["n"], c["d"], c["m"], 2, c["gamma"]
+    W = workloads.logreg_dense(n, d, m, seed=3)
+    P = oracle.LogRegDense(W.A, W.y, c["lam"])
+    x0 = np.zeros(d)
+    st = oracle.init_state(x0, P.grads(x0), k, init="compressed", storage_f32=True)
+    # every second worker starts from a useless estimator: the plain compressor wins there at first
+    st.g_i[1::2] = oracle.round_storage(5.0 * np.random.default_rng(9).standard_normal(st.g_i[1::2].shape), True)
+    st.g = oracle.mean_rows(st.g_i, True)
+    used = set()
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_problem_dense(to_gpu(torch, W.A), to_gpu(torch, W.y), c["lam"])
+        h.set_state(to_gpu(torch, st.x), to_gpu(torch, st.g_i), to_gpu(torch, st.g))
+        for t in range(50):
+            branch, _, _ = oracle.iteration_plus(st, P.grads, k, gamma, order="step_first")
+            h.step(None, binding.PLUS | binding.ORDER_STEP_FIRST)
+            used.update(h.get_choices()[0].cpu().numpy().tolist())
+            f_ref, f_gpu = P.loss(st.x), P.loss(h.get_x().cpu().numpy().astype(np.float64))
+            assert abs(f_gpu - f_ref) <= 1e-4 * abs(f_ref), f"iteration {t}: {f_gpu} vs {f_ref}"
+        x, g_i, g = (a.cpu().numpy() for a in h.get_state())
+    assert same_bits(g, (g_i.astype(np.float64).sum(axis=0) / n).astype(np.float32)) or \
+        np.allclose(g, g_i.astype(np.float64).mean(axis=0), rtol=1e-6, atol=1e-9)
+    assert used == {0, 1}, f"branches used: {used}"
+
+
+def test_errors(gpu):
+    torch, binding = gpu
+    with binding.EF21(2, 10, 3, 0.1) as h:
+        with pytest.raises(binding.EF21Error):
+            h.get_choices()                       # no EF21+ step yet
+        with pytest.raises(binding.EF21Error):
+            h.step(to_gpu(torch, np.zeros((2, 10))), 4)       # unknown flag
+        with pytest.raises(binding.EF21Error):
+            h.step(None, binding.PLUS)            # no problem attached
