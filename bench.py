@@ -97,6 +97,12 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
     out["roofline"] = roofline(4.0 * n * m * d + 4.0 * n * m + 4.0 * d, per_kernel["grad_main"],
                                "logreg_dense_fused_kernel (grad_main)", MEASURED_TRAFFIC_BYTES.get(f"{name}/grad_main"))
     out["iteration_frac_of_hbm_peak"] = round(out["iteration_algorithmic_bytes"] / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    if name == "C2":      # the same problem under Algorithm 3 (EF21+): two Top-k selections and the choice per worker
+        wall_p, _ = timed_loop(torch, lambda i: h.step(None, binding.PLUS), steps, warmup)
+        pk, pl = kernel_times(torch, h, lambda i: h.step(None, binding.PLUS), steps)
+        out["ef21_plus"] = {"value": round(1e3 / wall_p, 2), "unit": "EF21+ iterations/s", "ms_per_step": round(wall_p, 5),
+                            "kernel_ms_per_step": {k_: round(v * pl[k_], 5) for k_, v in pk.items()},
+                            "plain_compressor_chosen_last_step": int(h.get_choices()[0].sum().item())}
     if name == "C0":      # launch-bound: the same iterations replayed from a HIP graph of 10 captured steps
         out["hip_graph_10_steps"] = graph_replay(torch, h, steps)
     return out, (W, h)
@@ -324,6 +330,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "kernel_ms": head["kernel_ms"],
         "iteration_frac_of_hbm_peak": head["iteration_frac_of_hbm_peak"],
+        "ef21_plus": head.get("ef21_plus"),
         "workloads": extra,
     }
     print(json.dumps(line), flush=True)
