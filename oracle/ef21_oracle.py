@@ -4,8 +4,8 @@ Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import 
 It imports nothing from the HIP package and the HIP package imports nothing from here.
 
 The iteration of Algorithm 2 (EF21, multiple nodes) is composed here from the C routines, one
-call per line of the algorithm, in the order the paper states, and so is Algorithm 3 (EF21+), whose
-distortions and choice are written out in numpy; all state lives in fp64 numpy
+call per line of the algorithm, in the order the paper states, and so are Algorithm 3 (EF21+), whose
+distortions and choice are written out in numpy, and Algorithm 4 (the original EF); all state lives in fp64 numpy
 arrays (``storage_f32=True`` rounds every stored value to fp32, see the C file's header).
 """
 from __future__ import annotations
@@ -314,6 +314,40 @@ def iteration_plus(state: EF21State, grads_at, k: int, gamma: float, order: str 
         model_step(state, gamma, storage_f32)
         return out
     raise ValueError(order)
+
+
+# ------------------------------------------------------------------ Algorithm 4 (EF, the original error feedback)
+@dataclass
+class EFState:
+    """State of Algorithm 4: iterate x [d] and the workers' errors e_i [n][d]; the last messages w_i as pairs."""
+    x: np.ndarray
+    e: np.ndarray
+    msg_idx: np.ndarray | None = None
+    msg_val: np.ndarray | None = None
+
+
+def ef_iteration(state: EFState, grads_at, k: int, gamma: float, storage_f32: bool = True) -> None:
+    """One round of Algorithm 4 written with one gradient per round: at the current x,
+         p_i = e_i + gamma grad f_i(x)        (what the worker would like to send; lines 6 and 8)
+         w_i = C(p_i)                          (line 8, C = Top-k)
+         e_i <- p_i - w_i                      (line 6 of the next round)
+         x   <- x - (1/n) sum_i w_i            (line 4 of the next round)
+    which, started from e_i = 0, produces the algorithm's x^0, x^1, ... (its line 2 is the first round)."""
+    grads = round_storage(grads_at(state.x) if callable(grads_at) else grads_at, storage_f32)
+    n, d = state.e.shape
+    assert grads.shape == (n, d)
+    idx = np.empty((n, k), dtype=np.int32)
+    val = np.empty((n, k), dtype=np.float64)
+    total = np.zeros(d)
+    for i in range(n):
+        p = round_storage(state.e[i] + gamma * grads[i], storage_f32)
+        idx[i], val[i] = topk(p, k)
+        w = np.zeros(d)
+        w[idx[i]] = val[i]
+        state.e[i] = p - w                  # exact: zero where kept, p elsewhere
+        total += w                          # worker order
+    state.x = round_storage(state.x - total / n, storage_f32)
+    state.msg_idx, state.msg_val = idx, val
 
 
 # ------------------------------------------------------------------------ theory (Section 3.4)
