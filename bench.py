@@ -103,6 +103,10 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
         out["ef21_plus"] = {"value": round(1e3 / wall_p, 2), "unit": "EF21+ iterations/s", "ms_per_step": round(wall_p, 5),
                             "kernel_ms_per_step": {k_: round(v * pl[k_], 5) for k_, v in pk.items()},
                             "plain_compressor_chosen_last_step": int(h.get_choices()[0].sum().item())}
+    if name == "C2":      # and under Algorithm 4 (the original EF, the comparison method), errors started at zero
+        h.set_state(x0, torch.zeros((n, d), device="cuda"), None)
+        wall_e, _ = timed_loop(torch, lambda i: h.step(None, binding.CLASSIC_EF), steps, warmup)
+        out["classic_ef"] = {"value": round(1e3 / wall_e, 2), "unit": "EF iterations/s", "ms_per_step": round(wall_e, 5)}
     if name == "C0":      # launch-bound: the same iterations replayed from a HIP graph of 10 captured steps
         out["hip_graph_10_steps"] = graph_replay(torch, h, steps)
     return out, (W, h)
@@ -221,6 +225,11 @@ def bench_grads(torch, binding, workloads, steps: int, warmup: int):
            "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()}, "iteration_algorithmic_bytes": it_bytes,
            "iteration_frac_of_hbm_peak": round(it_bytes / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
            "topk_elements_per_s": round(n * d / (sum(v for k_, v in per_kernel.items() if k_.startswith("topk")) * 1e-3), 1)}
+    # the comparison method on the same gradients: Algorithm 4 rewrites its whole state e_i every round
+    h.set_state(torch.zeros(d, device="cuda"), torch.zeros((n, d), device="cuda"), None)
+    wall_e, _ = timed_loop(torch, lambda i: h.step(pool[i % 4], binding.CLASSIC_EF), steps, warmup)
+    out["classic_ef"] = {"value": round(1e3 / wall_e, 2), "unit": "EF iterations/s (gradients supplied)",
+                         "ms_per_step": round(wall_e, 5)}
     dom = "topk_collect" if "topk_collect" in per_kernel else "topk_row"
     out["roofline"] = roofline(8.0 * n * d, per_kernel[dom], f"{dom} (reads grad and g_i once)",
                                MEASURED_TRAFFIC_BYTES.get(f"C4/{dom}"))
@@ -331,6 +340,7 @@ def main() -> int:
         "kernel_ms": head["kernel_ms"],
         "iteration_frac_of_hbm_peak": head["iteration_frac_of_hbm_peak"],
         "ef21_plus": head.get("ef21_plus"),
+        "classic_ef": head.get("classic_ef"),
         "workloads": extra,
     }
     print(json.dumps(line), flush=True)

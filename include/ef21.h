@@ -46,7 +46,8 @@ enum {
 enum {
     EF21_ORDER_GRAD_FIRST = 0u, /* lines 5, 6, 8 at the current x, then line 3 (default)      */
     EF21_ORDER_STEP_FIRST = 1u, /* line 3, then lines 5, 6, 8 at the new x (loop as printed)  */
-    EF21_PLUS = 2u              /* the loop body of Algorithm 3 (EF21+) instead of Algorithm 2 */
+    EF21_PLUS = 2u,             /* the loop body of Algorithm 3 (EF21+) instead of Algorithm 2 */
+    EF21_CLASSIC_EF = 4u        /* one round of Algorithm 4 (the original EF); alone, see below  */
 };
 
 /* Human-readable text of the calling thread's last failure ("" if none).  Library-owned. */
@@ -153,6 +154,17 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags);
  * pointer may be NULL.  EF21_ESTATE before the first EF21_PLUS step.
  */
 int ef21_get_choices(ef21_handle h, int32_t *branch, double *distortions);
+
+/*
+ * With flags == EF21_CLASSIC_EF, ef21_step runs one round of Algorithm 4 (EF, the original error feedback
+ * that Section 4 compares EF21 with) on the same handle, the workers' errors e_i taking the place of g_i in
+ * ef21_set_state / ef21_get_state (start from e_i = 0): at the handle's x, with s = grad f_i(x) or the
+ * supplied row,  p_i = e_i + gamma s  (one fused multiply-add per entry, written over e_i),
+ * w_i = C(p_i)  (Top-k as in ef21_topk; returned by ef21_get_messages),  e_i = p_i - w_i  (zero at the kept
+ * positions),  x <- x - (1/n) sum_i w_i  (the sum per coordinate in worker order in fp32).  Started from
+ * e_i = 0 this produces the iterates x^0, x^1, ... of Algorithm 4.  The g of ef21_get_state holds
+ * (1/n) sum_i w_i of the last round.  Do not mix rounds of different algorithms on one state.
+ */
 
 /*
  * Per-kernel timing, for measurement only (not part of the paper's method).  While enabled,

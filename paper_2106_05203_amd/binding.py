@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libef21.so")
 
 EF21_OK, EF21_EINVAL, EF21_ENOMEM, EF21_EHIP, EF21_ESTATE = 0, -1, -2, -3, -4
-ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS = 0, 1, 2
+ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS, CLASSIC_EF = 0, 1, 2, 4
 
 # every symbol include/ef21.h declares
 SYMBOLS = (

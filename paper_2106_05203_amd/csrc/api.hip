@@ -467,11 +467,39 @@ static int enqueue_plus(ef21_ctx *h, const float *grads, const ef21::Marker &mk)
     return EF21_OK;
 }
 
+// One round of Algorithm 4 (EF) on the handle: the errors e_i live in g_i, g receives (1/n) sum_i w_i.
+static int enqueue_classic_ef(ef21_ctx *h, const float *grads, const ef21::Marker &mk) {
+    hipError_t st = ef21::launch_ef_accumulate(grads, h->g_i, h->n, h->d, h->gamma, h->stream);   // p_i over e_i
+    mk(ef21::K_PLUS);
+    if (st != hipSuccess) return fail_hip(st, "EF accumulation launch");
+    ef21::TopkArgs p{h->g_i, nullptr, h->n, h->d, h->k, h->msg_idx, h->msg_val, nullptr};            // w_i = C(p_i)
+    if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk)) return rc;
+    st = ef21::launch_ef_clear_kept(h->msg_idx, h->n, h->k, h->g_i, h->d, h->stream);               // e_i = p_i - w_i
+    if (st == hipSuccess) st = ef21::launch_fill_zero(h->g, h->d, h->stream);
+    mk(ef21::K_PLUS);
+    if (st != hipSuccess) return fail_hip(st, "EF error update launch");
+    st = ef21::launch_aggregate(h->msg_idx, h->msg_val, h->n, h->k, h->d, h->g, h->x, 1.0f, h->agg_index,
+                                h->stream);                                                         // x - mean w
+    mk(ef21::K_MODEL_STEP);
+    if (st != hipSuccess) return fail_hip(st, "aggregation launch");
+    return EF21_OK;
+}
+
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
     if (int rc = check_handle(h)) return rc;
-    if (flags > (EF21_ORDER_STEP_FIRST | EF21_PLUS)) return fail(EF21_EINVAL, "unknown flags");
+    if (flags > (EF21_ORDER_STEP_FIRST | EF21_PLUS) && flags != EF21_CLASSIC_EF)
+        return fail(EF21_EINVAL, "unknown flags (EF21_CLASSIC_EF combines with no other flag)");
     if (!grads && h->kind == kNone)
         return fail(EF21_ESTATE, "grads is NULL and no problem is attached to compute them from");
+    if (flags == EF21_CLASSIC_EF) {
+        const ef21::Marker mk0 = marker_of(h);
+        mk0(-1);
+        if (!grads) {
+            if (int rc = enqueue_local_grad(h, h->x, h->grad)) return rc;
+            grads = h->grad;
+        }
+        return enqueue_classic_ef(h, grads, mk0);
+    }
     const bool step_first = (flags & EF21_ORDER_STEP_FIRST) != 0;
     const bool plus = (flags & EF21_PLUS) != 0;
     if (plus)

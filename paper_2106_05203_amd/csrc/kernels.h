@@ -115,6 +115,11 @@ hipError_t launch_plus_choose(const float *s, float *g_i, int32_t n, int64_t d, 
                               const float *val_b, const int32_t *idx_m, const float *val_m, void *scratch,
                               int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream);
 
+// Algorithm 4 (EF): e <- e + gamma s over all n * d entries; e <- 0 at the kept positions idx [n][k]; v <- 0.
+hipError_t launch_ef_accumulate(const float *s, float *e, int32_t n, int64_t d, float gamma, hipStream_t stream);
+hipError_t launch_ef_clear_kept(const int32_t *idx, int32_t n, int64_t k, float *e, int64_t d, hipStream_t stream);
+hipError_t launch_fill_zero(float *v, int64_t d, hipStream_t stream);
+
 // Plain streaming kernels for measuring what the HBM delivers: one read of `n16` 16-byte words (their sum goes
 // to sink[0]), and a copy.
 hipError_t launch_hbm_read(const void *src, int64_t n16, float *sink, hipStream_t stream);

@@ -1,0 +1,127 @@
+"""GPU parity of the original error feedback (Algorithm 4; ef21_step with EF21_CLASSIC_EF through the C
+ABI) against the CPU oracle: messages and errors bit for bit from an oracle-supplied state, x within 1e-5
+relative per coordinate plus the rounding of the fp32 sum over workers, f(x^t) within 1e-4 over a run."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from helpers import same_bits
+from paper_2106_05203_amd import workloads
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2106_05203_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    return torch, binding
+
+
+def to_gpu(torch, a, dtype=np.float32):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
+
+
+def test_hand_worked_example(gpu):
+    torch, binding = gpu
+    ex = json.load(open(os.path.join(HERE, "golden", "ef_hand_example.json")))
+    with binding.EF21(ex["n"], ex["d"], ex["k"], ex["gamma"]) as h:
+        h.set_state(to_gpu(torch, ex["x0"]), to_gpu(torch, np.zeros((ex["n"], ex["d"]))), None)
+        for r in (0, 1):
+            h.step(to_gpu(torch, ex[f"grads_round{r}"]), binding.CLASSIC_EF)
+            torch.cuda.synchronize()
+            x, e, _ = (t.cpu().numpy() for t in h.get_state())
+            idx, val = (t.cpu().numpy() for t in h.get_messages())
+            want = ex["expect"][f"round{r}"]
+            assert e.tolist() == want["e"] and x.tolist() == want["x"]
+            assert idx.tolist() == want["msg_idx"] and val.tolist() == want["msg_val"]
+
+
+@pytest.mark.parametrize("n,d,k", [(1, 1, 1), (4, 100, 1), (6, 1001, 37), (20, 2000, 20), (5, 70001, 700),
+                                   (3, 300_000, 3000), (3, 300_000, 60_000)])
+def test_rounds_from_oracle_state(gpu, oracle, n, d, k):
+    torch, binding = gpu
+    print(f"EF round case n={n} d={d} k={k}", flush=True)
+    rng = np.random.default_rng(n * 1000 + d + k)
+    gamma = float(np.float32(0.3))                      # the library keeps gamma in fp32
+    x0 = rng.standard_normal(d).astype(np.float32)
+    e0 = (0.2 * rng.standard_normal((n, d))).astype(np.float32)
+    st = oracle.EFState(x0.astype(np.float64), e0.astype(np.float64))
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, e0), None)
+        for t in range(3):
+            grads = rng.standard_normal((n, d)).astype(np.float32)
+            if t == 1:
+                grads[:, ::5] = 0.0
+            x_before = st.x.copy()
+            oracle.ef_iteration(st, grads.astype(np.float64), k, gamma)
+            h.step(to_gpu(torch, grads), binding.CLASSIC_EF)
+            torch.cuda.synchronize()
+            x, e, mean_w = (a.cpu().numpy() for a in h.get_state())
+            idx, val = (a.cpu().numpy() for a in h.get_messages())
+            assert np.array_equal(idx, st.msg_idx), f"round {t}: message positions"
+            assert same_bits(val, st.msg_val.astype(np.float32)), f"round {t}: message values"
+            assert same_bits(e, st.e.astype(np.float32)), f"round {t}: errors"
+            w = np.zeros((n, d))
+            np.put_along_axis(w, st.msg_idx.astype(np.int64), st.msg_val, axis=1)
+            budget = (n + 2) * 2.0 ** -24 * np.abs(w).mean(axis=0) + 2.0 ** -23 * np.abs(x_before)
+            assert np.all(np.abs(x - st.x) <= 1e-5 * np.abs(st.x) + budget), f"round {t}: x"
+            assert np.all(np.abs(mean_w - w.mean(axis=0)) <= 1e-5 * np.abs(w.mean(axis=0)) + budget)
+            h.set_state(to_gpu(torch, st.x), None, None)
+
+
+def test_identity_compressor_gives_gradient_descent_like_ef21(gpu):
+    """Theorem 3's setting on the GPU: with k = d the compressor is the identity, EF and EF21 (started
+    from g_i^0 = grad f_i(x^0), the printed loop order) and gradient descent visit the same iterates, up to fp32."""
+    torch, binding = gpu
+    rng = np.random.default_rng(12)
+    n, d, gamma = 4, 64, float(np.float32(0.25))
+    targets = rng.standard_normal((n, d)).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    x_gd = x0.astype(np.float64)
+    with binding.EF21(n, d, d, gamma) as ef, binding.EF21(n, d, d, gamma) as ef21:
+        ef.set_state(to_gpu(torch, x0), to_gpu(torch, np.zeros((n, d))), None)
+        ef21.set_state(to_gpu(torch, x0), to_gpu(torch, x0[None, :] - targets), None)
+        for t in range(10):
+            g_gd = x_gd[None, :] - targets
+            x_gd = x_gd - gamma * g_gd.mean(axis=0)
+            x_ef = ef.get_x().cpu().numpy()
+            ef.step(to_gpu(torch, x_ef[None, :] - targets), binding.CLASSIC_EF)
+            # EF21 as printed: step with g^t, then the gradients at the new x
+            x_21 = ef21.get_x().cpu().numpy() - gamma * ef21.get_state()[2].cpu().numpy()
+            ef21.step(to_gpu(torch, x_21[None, :] - targets), binding.ORDER_STEP_FIRST)
+            assert np.allclose(ef.get_x().cpu().numpy(), x_gd, rtol=1e-5, atol=1e-5), f"EF, round {t}"
+            assert np.allclose(ef21.get_x().cpu().numpy(), x_gd, rtol=1e-5, atol=1e-5), f"EF21, round {t}"
+            assert not ef.get_state()[1].any(), "nothing is dropped, so no error is left"
+
+
+def test_run_on_a_dense_problem(gpu, oracle):
+    """Fifty rounds of EF with the library's own gradients on config 0's problem: f(x^t) within 1e-4."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C0"]
+    n, d, m, k = c["n"], c["d"], c["m"], 2
+    gamma = float(np.float32(c["gamma"]))
+    W = workloads.logreg_dense(n, d, m, seed=4)
+    P = oracle.LogRegDense(W.A, W.y, c["lam"])
+    st = oracle.EFState(np.zeros(d), np.zeros((n, d)))
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_problem_dense(to_gpu(torch, W.A), to_gpu(torch, W.y), c["lam"])
+        h.set_state(to_gpu(torch, st.x), to_gpu(torch, st.e), None)
+        for t in range(50):
+            oracle.ef_iteration(st, P.grads, k, gamma)
+            h.step(None, binding.CLASSIC_EF)
+            f_ref, f_gpu = P.loss(st.x), P.loss(h.get_x().cpu().numpy().astype(np.float64))
+            assert abs(f_gpu - f_ref) <= 1e-4 * abs(f_ref), f"round {t}: {f_gpu} vs {f_ref}"
+
+
+def test_flag_combinations_are_rejected(gpu):
+    torch, binding = gpu
+    with binding.EF21(2, 10, 3, 0.1) as h:
+        for flags in (binding.CLASSIC_EF | binding.PLUS, binding.CLASSIC_EF | binding.ORDER_STEP_FIRST, 8):
+            with pytest.raises(binding.EF21Error):
+                h.step(to_gpu(torch, np.zeros((2, 10))), flags)
