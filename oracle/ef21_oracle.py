@@ -167,6 +167,47 @@ class LogRegCSR:
         return np.stack([self.grad_i(i, x) for i in range(self.n)])
 
 
+# --------------------------------------------------------------- objective of Section 5.2 (least squares)
+class LeastSquaresDense:
+    """f_i(x) = (1/m) sum_l (a_il^T x - b_il)^2  (+ lam sum_j x_j^2 / (1 + x_j^2), zero in the paper's
+    function), A [n][m][d] dense fp32 rows, b [n][m]; numpy in fp64."""
+
+    def __init__(self, A, b, lam: float = 0.0):
+        self.A = np.ascontiguousarray(A, dtype=np.float32)
+        self.b = np.ascontiguousarray(b, dtype=np.float32)
+        self.n, self.m, self.d = self.A.shape
+        assert self.b.shape == (self.n, self.m)
+        self.lam = float(lam)
+
+    def _reg(self, x):
+        return self.lam * float(np.sum(x * x / (1.0 + x * x))), 2.0 * self.lam * x / (1.0 + x * x) ** 2
+
+    def loss_i(self, i: int, x) -> float:
+        x = _f64(x)
+        r = self.A[i].astype(np.float64) @ x - self.b[i].astype(np.float64)
+        return float(np.mean(r * r)) + self._reg(x)[0]
+
+    def grad_i(self, i: int, x) -> np.ndarray:
+        x = _f64(x)
+        Ai = self.A[i].astype(np.float64)
+        r = Ai @ x - self.b[i].astype(np.float64)
+        return (2.0 / self.m) * (Ai.T @ r) + self._reg(x)[1]
+
+    def loss(self, x) -> float:
+        return sum(self.loss_i(i, x) for i in range(self.n)) / self.n
+
+    def grads(self, x) -> np.ndarray:
+        return np.stack([self.grad_i(i, x) for i in range(self.n)])
+
+
+def densify_csr(rowptr, col, val, n: int, m: int, d: int) -> np.ndarray:
+    """[n][m][d] dense copy of a CSR matrix over n*m rows (small problems only)."""
+    D = np.zeros((n * m, d), dtype=np.float32)
+    for r in range(n * m):
+        D[r, col[rowptr[r]:rowptr[r + 1]]] = val[rowptr[r]:rowptr[r + 1]]
+    return D.reshape(n, m, d)
+
+
 # ------------------------------------------------------------------ Algorithm 2 (EF21, multi-node)
 def round_storage(a, storage_f32: bool) -> np.ndarray:
     a = _f64(a).copy()
