@@ -107,6 +107,17 @@ int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *co
                          const float *y, int64_t m, float lambda);
 
 /*
+ * The per-row loss of the attached problem (default EF21_LOSS_LOGISTIC).  With EF21_LOSS_LEAST_SQUARES the
+ * objective is the one of Section 5.2,
+ *   f_i(x) = (1/m) sum_l (a_il^T x - y_il)^2  (+ the regulariser of eq. (9) times lambda; pass lambda = 0 for
+ *   the paper's function), y holding the targets b_il,
+ * whose gradient is (2/m) sum_l (a_il^T x - y_il) a_il: the same kernels with another derivative per row.
+ * Takes effect from the next gradient.  EF21_EINVAL: unknown value.
+ */
+enum { EF21_LOSS_LOGISTIC = 0, EF21_LOSS_LEAST_SQUARES = 1 };
+int ef21_set_loss(ef21_handle h, int loss);
+
+/*
  * State of Algorithm 2.  set: copies x [d] and g_i [n][d] into the handle (either may be NULL
  * = keep); g [d] NULL means "recompute g = (1/n) sum_i g_i" (the algorithm's input line).
  * get: copies the handle's state out; any pointer may be NULL.

@@ -16,13 +16,14 @@ LIB_PATH = os.path.join(_HERE, "libef21.so")
 
 EF21_OK, EF21_EINVAL, EF21_ENOMEM, EF21_EHIP, EF21_ESTATE = 0, -1, -2, -3, -4
 ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS, CLASSIC_EF = 0, 1, 2, 4
+LOSS_LOGISTIC, LOSS_LEAST_SQUARES = 0, 1
 
 # every symbol include/ef21.h declares
 SYMBOLS = (
     "ef21_last_error", "ef21_create", "ef21_destroy", "ef21_set_stream", "ef21_topk",
     "ef21_set_problem_dense", "ef21_set_problem_csr", "ef21_set_state", "ef21_get_state",
     "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
-    "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices",
+    "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices", "ef21_set_loss",
 )
 K_COUNT = 10
 
@@ -65,6 +66,7 @@ def load_library() -> C.CDLL:
     lib.ef21_get_timing.argtypes = [p, p, p, C.c_int]
     lib.ef21_kernel_name.argtypes = [C.c_int]
     lib.ef21_get_choices.argtypes = [p, p, p]
+    lib.ef21_set_loss.argtypes = [p, C.c_int]
     lib.ef21_hbm_read.argtypes = [p, C.c_int64, p, p]
     lib.ef21_hbm_copy.argtypes = [p, p, C.c_int64, p]
     for name in SYMBOLS[2:]:
@@ -213,6 +215,10 @@ class EF21:
         with torch.cuda.device(self.device):
             _check(self._lib.ef21_get_messages(self._h, idx.data_ptr(), val.data_ptr()))
         return idx, val
+
+    def set_loss(self, loss: int) -> None:
+        with torch.cuda.device(self.device):
+            _check(self._lib.ef21_set_loss(self._h, int(loss)))
 
     def get_choices(self):
         """(branch [n] int32: 1 = plain compressor chosen, distortions [n][2] float64: B_i, M_i) of the last

@@ -80,6 +80,7 @@ struct ef21_ctx {
     const int32_t *col = nullptr;
     int64_t m = 0;
     float lambda = 0.f;
+    int loss = 0;                   // EF21_LOSS_*
     // owned buffers for the problem path and the long-row Top-k
     float *grad = nullptr;
     void *scratch = nullptr;
@@ -204,10 +205,10 @@ int enqueue_local_grad(ef21_ctx *c, const float *x, float *out, ef21::GradParts 
     if (defer) *defer = ef21::GradParts();
     if (c->kind == kDense)
         st = ef21::launch_logreg_grad_dense(c->A, c->y, x, out, c->n, c->m, c->d, c->lambda, c->scratch, c->stream,
-                                            mk, defer);
+                                            mk, defer, c->loss);
     else
         st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->nnz,
-                                          c->lambda, c->csr_indexed ? c->csr_index : nullptr, c->stream, mk);
+                                          c->lambda, c->csr_indexed ? c->csr_index : nullptr, c->stream, mk, c->loss);
     if (st != hipSuccess) return fail_hip(st, "gradient kernel launch");
     return EF21_OK;
 }
@@ -381,6 +382,13 @@ int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *co
     h->y = y;
     h->m = m;
     h->lambda = lambda;
+    return EF21_OK;
+}
+
+int ef21_set_loss(ef21_handle h, int loss) {
+    if (int rc = check_handle(h)) return rc;
+    if (loss != EF21_LOSS_LOGISTIC && loss != EF21_LOSS_LEAST_SQUARES) return fail(EF21_EINVAL, "unknown loss");
+    h->loss = loss;
     return EF21_OK;
 }
 

@@ -30,6 +30,13 @@ __device__ __forceinline__ float4 stream_load4(const float *p) {
 __device__ __forceinline__ float stream_load(const float *p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ int32_t stream_load(const int32_t *p) { return __builtin_nontemporal_load(p); }
 
+// Derivative in z of the per-row loss of a linear model, z = a^T x:
+//   kLossLogistic       log(1 + exp(-y z))  (Section 5, eq. (9)):   -y / (1 + exp(y z))
+//   kLossLeastSquares   (z - y)^2           (Section 5.2):          2 (z - y)
+__device__ __forceinline__ float loss_derivative(float y, float z, int loss) {
+    return loss == 1 /* kLossLeastSquares */ ? 2.0f * (z - y) : -y / (1.0f + expf(y * z));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);

@@ -85,13 +85,17 @@ hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int
 // g = (1/n) sum_i g_i (input line of Algorithm 2), summed in worker order.
 hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hipStream_t stream);
 
+// `loss` below: the per-row loss of the linear model (LossKind in device_utils.h): logistic (eq. (9)) or squared.
+enum { kLossLogistic = 0, kLossLeastSquares = 1 };
+
 // Gradient of eq. (9) for all workers, dense rows.  scratch: logreg_dense_scratch_bytes.  With defer != nullptr
 // the last reduction may be left to the consumer: then *defer describes the partial sums (they live in
 // scratch until the next call) and grad is not written; defer->part == nullptr means grad was written.
 size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d);
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
                                     int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
-                                    const Marker &mk = Marker(), GradParts *defer = nullptr);
+                                    const Marker &mk = Marker(), GradParts *defer = nullptr,
+                                    int loss = kLossLogistic);
 
 // Gradient of eq. (9) for all workers, CSR rows with nnz entries in all.  `index`
 // (logreg_csr_index_bytes bytes, owned by the caller) is built once per problem by logreg_csr_build_index
@@ -104,7 +108,8 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
                                   int64_t d, int64_t nnz, void *index, hipStream_t stream, bool *usable);
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
-                                  float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker());
+                                  float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker(),
+                                  int loss = kLossLogistic);
 
 // Algorithm 3 (EF21+), lines 7 and 8, for all workers: from the gradients s [n][d], the estimators g_i [n][d]
 // (updated in place) and the two Top-k results (idx_b, val_b) = C(s), (idx_m, val_m) = C(s - g_i), all [n][k]:

@@ -35,17 +35,13 @@ DensePlan dense_plan(int32_t n, int64_t m) {
     return {rows, (m + rows - 1) / rows};
 }
 
-__device__ __forceinline__ float residual(float y, float z) {   // -y / (1 + exp(y z))
-    return -y / (1.0f + expf(y * z));
-}
-
 // ------------------------------------------------------------------ dense, one pass over A
 template <int VEC, int NQ, int ROWS>
 __global__ __launch_bounds__(kThreads) void logreg_dense_fused_kernel(const float *__restrict__ A,
                                                                       const float *__restrict__ y,
                                                                       const float *__restrict__ x,
                                                                       float *__restrict__ part, int64_t m,
-                                                                      int64_t d, int64_t rows_per_wg) {
+                                                                      int64_t d, int64_t rows_per_wg, int loss) {
     constexpr int kCols = NQ * kWave * VEC;   // columns covered by one wavefront
     __shared__ float red[kCols];
     const int64_t worker = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
@@ -100,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_fused_kernel(const floa
         for (int r = 0; r < ROWS; ++r) s[r] = wave_sum(s[r]);
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            const float coef = l + r < l1 ? residual(yl[r], s[r]) : 0.f;
+            const float coef = l + r < l1 ? loss_derivative(yl[r], s[r], loss) : 0.f;
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
@@ -130,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_residual_kernel(const f
                                                                          const float *__restrict__ y,
                                                                          const float *__restrict__ x,
                                                                          float *__restrict__ r, int64_t rows,
-                                                                         int64_t d) {
+                                                                         int64_t d, int loss) {
     const int lane = lane_id();
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
     for (int64_t l = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; l < rows; l += nwaves) {
@@ -138,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_residual_kernel(const f
         float s = 0.f;
         for (int64_t c = lane; c < d; c += kWave) s = fmaf(row[c], x[c], s);
         s = wave_sum(s);
-        if (lane == 0) r[l] = residual(y[l], s);
+        if (lane == 0) r[l] = loss_derivative(y[l], s, loss);
     }
 }
 
@@ -168,10 +164,10 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_finish_kernel(const flo
 
 template <int VEC, int NQ>
 void launch_fused(const float *A, const float *y, const float *x, float *part, int32_t n, int64_t m, int64_t d,
-                  const DensePlan &pl, hipStream_t stream) {
+                  const DensePlan &pl, int loss, hipStream_t stream) {
     constexpr int ROWS = NQ * VEC <= 32 ? 2 : 1;     // two rows in flight while their registers fit
     hipLaunchKernelGGL((logreg_dense_fused_kernel<VEC, NQ, ROWS>), dim3((unsigned)pl.chunks, (unsigned)n),
-                       dim3(kThreads), 0, stream, A, y, x, part, m, d, pl.rows_per_wg);
+                       dim3(kThreads), 0, stream, A, y, x, part, m, d, pl.rows_per_wg, loss);
 }
 
 }  // namespace
@@ -183,28 +179,28 @@ size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d) {
 
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
                                     int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
-                                    const Marker &mk, GradParts *defer) {
+                                    const Marker &mk, GradParts *defer, int loss) {
     if (defer) *defer = GradParts();
     const DensePlan pl = dense_plan(n, m);
     float *part = (float *)scratch;
     float *resid = part + (size_t)n * pl.chunks * d;
     const bool vec4 = (d % 4 == 0) && ((uintptr_t)A % 16 == 0);
     bool fused = true;
-    if (vec4 && d <= 256) launch_fused<4, 1>(A, y, x, part, n, m, d, pl, stream);
-    else if (vec4 && d <= 512) launch_fused<4, 2>(A, y, x, part, n, m, d, pl, stream);
-    else if (vec4 && d <= 1024) launch_fused<4, 4>(A, y, x, part, n, m, d, pl, stream);
-    else if (vec4 && d <= 2048) launch_fused<4, 8>(A, y, x, part, n, m, d, pl, stream);
-    else if (vec4 && d <= 4096) launch_fused<4, 16>(A, y, x, part, n, m, d, pl, stream);
-    else if (d <= 128) launch_fused<1, 2>(A, y, x, part, n, m, d, pl, stream);
-    else if (d <= 512) launch_fused<1, 8>(A, y, x, part, n, m, d, pl, stream);
-    else if (d <= 2048) launch_fused<1, 32>(A, y, x, part, n, m, d, pl, stream);
+    if (vec4 && d <= 256) launch_fused<4, 1>(A, y, x, part, n, m, d, pl, loss, stream);
+    else if (vec4 && d <= 512) launch_fused<4, 2>(A, y, x, part, n, m, d, pl, loss, stream);
+    else if (vec4 && d <= 1024) launch_fused<4, 4>(A, y, x, part, n, m, d, pl, loss, stream);
+    else if (vec4 && d <= 2048) launch_fused<4, 8>(A, y, x, part, n, m, d, pl, loss, stream);
+    else if (vec4 && d <= 4096) launch_fused<4, 16>(A, y, x, part, n, m, d, pl, loss, stream);
+    else if (d <= 128) launch_fused<1, 2>(A, y, x, part, n, m, d, pl, loss, stream);
+    else if (d <= 512) launch_fused<1, 8>(A, y, x, part, n, m, d, pl, loss, stream);
+    else if (d <= 2048) launch_fused<1, 32>(A, y, x, part, n, m, d, pl, loss, stream);
     else fused = false;
     if (!fused) {
         const int64_t rows = (int64_t)n * m;
         int64_t blocks = (rows + kWaves - 1) / kWaves;
         if (blocks > 16384) blocks = 16384;
         hipLaunchKernelGGL(logreg_dense_residual_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, A, y, x,
-                           resid, rows, d);
+                           resid, rows, d, loss);
         hipLaunchKernelGGL(logreg_dense_atr_kernel,
                            dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)pl.chunks, (unsigned)n),
                            dim3(kThreads), 0, stream, A, resid, part, m, d, pl.rows_per_wg);

@@ -40,10 +40,6 @@ constexpr int64_t kCoefLdsRows = 16384;   // m up to this: coef vector in LDS (6
 constexpr int kRangeCols = 12288;     // at most this many columns per range (48 KB of LDS as fp32)
 constexpr int kMaxRanges = 64;
 
-__device__ __forceinline__ float residual(float y, float z) {   // -y / (1 + exp(y z))
-    return -y / (1.0f + expf(y * z));
-}
-
 __device__ __forceinline__ float regulariser_grad(float xj, float lambda) {
     const float q = 1.0f + xj * xj;
     return 2.0f * lambda * xj / (q * q);
@@ -451,12 +447,12 @@ __global__ __launch_bounds__(kWave) void csc_fill_kernel(const int64_t *__restri
 // products (added in range order)
 __global__ __launch_bounds__(kThreads) void csr_coef_kernel(const float *__restrict__ y,
                                                             const float *__restrict__ zpart, int R, int64_t rows,
-                                                            float inv_m, float *__restrict__ coef) {
+                                                            float inv_m, float *__restrict__ coef, int loss) {
     const int64_t row = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (row >= rows) return;
     float z = 0.f;
     for (int r = 0; r < R; ++r) z += zpart[(int64_t)r * rows + row];
-    coef[row] = residual(y[row], z) * inv_m;
+    coef[row] = loss_derivative(y[row], z, loss) * inv_m;
 }
 
 // ---- pass 2: gradient columns from the column-major copy.  Dynamic LDS: m floats if COEF_LDS.
@@ -514,7 +510,7 @@ __global__ __launch_bounds__(kThreads) void csr_atomic_kernel(const int64_t *__r
                                                               const float *__restrict__ val,
                                                               const float *__restrict__ y,
                                                               const float *__restrict__ x, float *grad, int64_t rows,
-                                                              int64_t m, int64_t d, float inv_m) {
+                                                              int64_t m, int64_t d, float inv_m, int loss) {
     const int lane = lane_id();
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
     for (int64_t l = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; l < rows; l += nwaves) {
@@ -526,7 +522,7 @@ __global__ __launch_bounds__(kThreads) void csr_atomic_kernel(const int64_t *__r
             if (c < (uint64_t)d) s = fmaf(val[p], x[c], s);
         }
         s = wave_sum(s);
-        const float coef = residual(y[l], s) * inv_m;
+        const float coef = loss_derivative(y[l], s, loss) * inv_m;
         float *g = grad + (l / m) * d;
         for (int64_t p = p0 + lane; p < p1; p += kWave) {
             const uint32_t c = (uint32_t)col[p];
@@ -594,7 +590,7 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
 
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
-                                  float lambda, const void *index, hipStream_t stream, const Marker &mk) {
+                                  float lambda, const void *index, hipStream_t stream, const Marker &mk, int loss) {
     const int64_t rows = (int64_t)n * m;
     if (index) {
         IndexLayout ix;
@@ -615,7 +611,7 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
                            ix.R, ix.Wc);
         mk(K_GRAD_MAIN);
         hipLaunchKernelGGL(csr_coef_kernel, dim3((unsigned)((rows + kThreads - 1) / kThreads)), dim3(kThreads), 0,
-                           stream, y, ix.zpart, ix.R, rows, 1.0f / (float)m, ix.coef);
+                           stream, y, ix.zpart, ix.R, rows, 1.0f / (float)m, ix.coef, loss);
         mk(K_GRAD_AUX);
         const dim3 grid((unsigned)((d + kCscCols - 1) / kCscCols), (unsigned)n);
         static_assert(kCoefLdsRows <= kIdx16Rows, "a coefficient vector that fits LDS has 16-bit row indices");
@@ -637,7 +633,7 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
                        lambda);
     mk(K_GRAD_AUX);
     hipLaunchKernelGGL(csr_atomic_kernel, dim3(row_blocks(rows)), dim3(kThreads), 0, stream, rowptr, col, val, y, x,
-                       grad, rows, m, d, 1.0f / (float)m);
+                       grad, rows, m, d, 1.0f / (float)m, loss);
     mk(K_GRAD_MAIN);
     return hipGetLastError();
 }
