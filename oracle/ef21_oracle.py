@@ -208,6 +208,45 @@ def densify_csr(rowptr, col, val, n: int, m: int, d: int) -> np.ndarray:
     return D.reshape(n, m, d)
 
 
+# --------------------------------------------------------------- stochastic gradients (Algorithm 5)
+def restrict_rows(problem, i: int, rows):
+    """Worker i's objective over the listed rows only (a one-worker problem of the same class): the
+    minibatch estimator of Algorithm 5 is the gradient of this function.  A row listed twice counts twice."""
+    rows = np.asarray(rows, dtype=np.int64)
+    assert rows.ndim == 1 and rows.size > 0 and rows.min() >= 0 and rows.max() < problem.m
+    if isinstance(problem, LogRegDense):
+        return LogRegDense(problem.A[i][rows][None], problem.y[i][rows][None], problem.lam)
+    if isinstance(problem, LeastSquaresDense):
+        return LeastSquaresDense(problem.A[i][rows][None], problem.b[i][rows][None], problem.lam)
+    if isinstance(problem, LogRegCSR):
+        rp = [0]
+        cols, vals = [], []
+        for l in rows:
+            p0, p1 = problem.rowptr[i * problem.m + l], problem.rowptr[i * problem.m + l + 1]
+            cols.append(problem.col[p0:p1])
+            vals.append(problem.val[p0:p1])
+            rp.append(rp[-1] + int(p1 - p0))
+        return LogRegCSR(np.array(rp), np.concatenate(cols) if cols else np.zeros(0, np.int32),
+                         np.concatenate(vals) if vals else np.zeros(0, np.float32), problem.y[i][rows], 1,
+                         rows.size, problem.d, problem.lam)
+    raise TypeError(type(problem))
+
+
+def minibatch_grads(problem, x, batch) -> np.ndarray:
+    """ghat_i = (1/tau) sum over l in batch[i] of the gradient of row l's loss, plus the regulariser's
+    gradient (line 5 of Algorithm 5; the experiments draw the batch without replacement).  batch: [n][tau]
+    row indices in [0, m), drawn by the caller."""
+    batch = np.asarray(batch, dtype=np.int64)
+    assert batch.ndim == 2 and batch.shape[0] == problem.n
+    return np.stack([restrict_rows(problem, i, batch[i]).grad_i(0, x) for i in range(problem.n)])
+
+
+def iteration_stochastic(state: "EF21State", problem, batch, k: int, gamma: float, order: str = "grad_first",
+                         storage_f32: bool = True) -> None:
+    """One iteration of Algorithm 5: Algorithm 2 with the minibatch estimator in the place of the gradient."""
+    iteration(state, lambda x: minibatch_grads(problem, x, batch), k, gamma, order=order, storage_f32=storage_f32)
+
+
 # ------------------------------------------------------------------ Algorithm 2 (EF21, multi-node)
 def round_storage(a, storage_f32: bool) -> np.ndarray:
     a = _f64(a).copy()
