@@ -107,6 +107,23 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
         h.set_state(x0, torch.zeros((n, d), device="cuda"), None)
         wall_e, _ = timed_loop(torch, lambda i: h.step(None, binding.CLASSIC_EF), steps, warmup)
         out["classic_ef"] = {"value": round(1e3 / wall_e, 2), "unit": "EF iterations/s", "ms_per_step": round(wall_e, 5)}
+    if name == "C2":      # and under Algorithm 5: minibatches of m/8 rows per worker, drawn without replacement, a
+        tau = m // 8      # fresh one every iteration (eight batches prepared in HBM, the draw is the caller's)
+        rng = np.random.default_rng(c["seed"] + 5)
+        batches = [dev(torch, np.stack([rng.choice(m, size=tau, replace=False) for _ in range(n)]), np.int32)
+                   for _ in range(8)]
+        h.set_state(x0, torch.zeros((n, d), device="cuda"), None)
+
+        def sto(i):
+            h.set_minibatch(batches[i % 8])
+            h.step()
+        wall_s, _ = timed_loop(torch, sto, steps, warmup)
+        pk, _ = kernel_times(torch, h, sto, steps)
+        h.set_minibatch(None)
+        gbytes = 4.0 * n * tau * d + 8.0 * n * tau + 4.0 * d
+        out["ef21_stochastic"] = {"value": round(1e3 / wall_s, 2), "unit": "Algorithm 5 iterations/s", "tau": tau,
+                                  "ms_per_step": round(wall_s, 5), "grad_main_ms": round(pk["grad_main"], 5),
+                                  "grad_main_GBps": round(gbytes / (pk["grad_main"] * 1e-3) / 1e9, 1)}
     if name == "C0":      # launch-bound: the same iterations replayed from a HIP graph of 10 captured steps
         out["hip_graph_10_steps"] = graph_replay(torch, h, steps)
     return out, (W, h)
@@ -341,6 +358,7 @@ def main() -> int:
         "iteration_frac_of_hbm_peak": head["iteration_frac_of_hbm_peak"],
         "ef21_plus": head.get("ef21_plus"),
         "classic_ef": head.get("classic_ef"),
+        "ef21_stochastic": head.get("ef21_stochastic"),
         "workloads": extra,
     }
     print(json.dumps(line), flush=True)

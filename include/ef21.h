@@ -118,6 +118,21 @@ enum { EF21_LOSS_LOGISTIC = 0, EF21_LOSS_LEAST_SQUARES = 1 };
 int ef21_set_loss(ef21_handle h, int loss);
 
 /*
+ * Stochastic gradients (Algorithm 5, the extension of Algorithm 2 in the appendix): from the next gradient
+ * on, worker i's gradient is replaced by the minibatch estimator
+ *   ghat_i = (1/tau) sum over l in rows[i][0..tau) of the gradient of row l's loss  +  the regulariser's,
+ * in ef21_local_grad and in every variant of ef21_step.  rows: device, int32 [n][tau], row numbers inside
+ * the worker's m rows, drawn by the caller (the library draws no random numbers); borrowed and read at
+ * every gradient, so the caller redraws a batch by rewriting the buffer (stream-ordered) or by another call.
+ * A row listed twice counts twice; an entry outside [0, m) contributes nothing and is never dereferenced
+ * (the division stays by tau).  tau == 0 (rows ignored): back to the full gradient.  Attaching a problem
+ * resets it.  Dense rows run the ordinary kernels over the listed rows (bitwise reproducible); CSR rows take
+ * one wavefront per listed row and global fp32 atomics (reproducible to rounding), work proportional to
+ * the batch.  EF21_ESTATE without a problem; EF21_EINVAL: tau outside [0, m], or rows NULL with tau > 0.
+ */
+int ef21_set_minibatch(ef21_handle h, const int32_t *rows, int64_t tau);
+
+/*
  * State of Algorithm 2.  set: copies x [d] and g_i [n][d] into the handle (either may be NULL
  * = keep); g [d] NULL means "recompute g = (1/n) sum_i g_i" (the algorithm's input line).
  * get: copies the handle's state out; any pointer may be NULL.

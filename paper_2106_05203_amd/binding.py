@@ -23,7 +23,7 @@ SYMBOLS = (
     "ef21_last_error", "ef21_create", "ef21_destroy", "ef21_set_stream", "ef21_topk",
     "ef21_set_problem_dense", "ef21_set_problem_csr", "ef21_set_state", "ef21_get_state",
     "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
-    "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices", "ef21_set_loss",
+    "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices", "ef21_set_loss", "ef21_set_minibatch",
 )
 K_COUNT = 10
 
@@ -67,6 +67,7 @@ def load_library() -> C.CDLL:
     lib.ef21_kernel_name.argtypes = [C.c_int]
     lib.ef21_get_choices.argtypes = [p, p, p]
     lib.ef21_set_loss.argtypes = [p, C.c_int]
+    lib.ef21_set_minibatch.argtypes = [p, p, C.c_int64]
     lib.ef21_hbm_read.argtypes = [p, C.c_int64, p, p]
     lib.ef21_hbm_copy.argtypes = [p, p, C.c_int64, p]
     for name in SYMBOLS[2:]:
@@ -138,6 +139,7 @@ class EF21:
         self.n, self.d, self.k, self.gamma = int(n), int(d), int(k), float(gamma)
         self.device = torch.device(device)
         self._keep = []     # borrowed problem tensors stay alive with the handle
+        self._batch = None  # and the rows of the minibatch
         with torch.cuda.device(self.device):
             self._h = self._lib.ef21_create(self.n, self.d, self.k, self.gamma)
         if not self._h:
@@ -177,6 +179,7 @@ class EF21:
             _check(self._lib.ef21_set_problem_dense(self._h, _dev(A, torch.float32), _dev(y, torch.float32, (n, m)), m,
                                                     float(lam)))
         self._keep = [A, y]
+        self._batch = None
 
     def set_problem_csr(self, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, y: torch.Tensor, m: int,
                         lam: float) -> None:
@@ -187,6 +190,7 @@ class EF21:
                                                   _dev(val, torch.float32), _dev(y, torch.float32, (self.n, m)), m,
                                                   float(lam)))
         self._keep = [rowptr, col, val, y]
+        self._batch = None
 
     # -- state
     def set_state(self, x=None, g_i=None, g=None) -> None:
@@ -219,6 +223,19 @@ class EF21:
     def set_loss(self, loss: int) -> None:
         with torch.cuda.device(self.device):
             _check(self._lib.ef21_set_loss(self._h, int(loss)))
+
+    def set_minibatch(self, rows: "torch.Tensor | None") -> None:
+        """rows: int32 [n][tau] on the device (kept alive by the handle and read at every gradient), or None
+        for full gradients."""
+        with torch.cuda.device(self.device):
+            if rows is None:
+                _check(self._lib.ef21_set_minibatch(self._h, None, 0))
+                self._batch = None
+                return
+            assert rows.dtype == torch.int32 and rows.is_cuda and rows.is_contiguous() and rows.dim() == 2
+            assert rows.shape[0] == self.n
+            _check(self._lib.ef21_set_minibatch(self._h, rows.data_ptr(), int(rows.shape[1])))
+            self._batch = rows
 
     def get_choices(self):
         """(branch [n] int32: 1 = plain compressor chosen, distortions [n][2] float64: B_i, M_i) of the last

@@ -81,6 +81,7 @@ struct ef21_ctx {
     int64_t m = 0;
     float lambda = 0.f;
     int loss = 0;                   // EF21_LOSS_*
+    ef21::RowBatch batch;           // Algorithm 5 (borrowed); tau == 0: full gradients
     // owned buffers for the problem path and the long-row Top-k
     float *grad = nullptr;
     void *scratch = nullptr;
@@ -205,10 +206,11 @@ int enqueue_local_grad(ef21_ctx *c, const float *x, float *out, ef21::GradParts 
     if (defer) *defer = ef21::GradParts();
     if (c->kind == kDense)
         st = ef21::launch_logreg_grad_dense(c->A, c->y, x, out, c->n, c->m, c->d, c->lambda, c->scratch, c->stream,
-                                            mk, defer, c->loss);
+                                            mk, defer, c->loss, c->batch);
     else
         st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, x, out, c->n, c->m, c->d, c->nnz,
-                                          c->lambda, c->csr_indexed ? c->csr_index : nullptr, c->stream, mk, c->loss);
+                                          c->lambda, c->csr_indexed ? c->csr_index : nullptr, c->stream, mk, c->loss,
+                                          c->batch);
     if (st != hipSuccess) return fail_hip(st, "gradient kernel launch");
     return EF21_OK;
 }
@@ -344,6 +346,7 @@ int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_
     if (!(lambda >= 0.f) || !std::isfinite(lambda)) return fail(EF21_EINVAL, "lambda must be finite and >= 0");
     if (int rc = ensure_problem_buffers(h, ef21::logreg_dense_scratch_bytes(h->n, m, h->d))) return rc;
     h->kind = kDense;
+    h->batch = ef21::RowBatch();
     h->A = A;
     h->y = y;
     h->m = m;
@@ -376,6 +379,7 @@ int ef21_set_problem_csr(ef21_handle h, const int64_t *rowptr, const int32_t *co
     }
     h->nnz = nnz;
     h->kind = kCSR;
+    h->batch = ef21::RowBatch();
     h->rowptr = rowptr;
     h->col = col;
     h->val = val;
@@ -389,6 +393,19 @@ int ef21_set_loss(ef21_handle h, int loss) {
     if (int rc = check_handle(h)) return rc;
     if (loss != EF21_LOSS_LOGISTIC && loss != EF21_LOSS_LEAST_SQUARES) return fail(EF21_EINVAL, "unknown loss");
     h->loss = loss;
+    return EF21_OK;
+}
+
+int ef21_set_minibatch(ef21_handle h, const int32_t *rows, int64_t tau) {
+    if (int rc = check_handle(h)) return rc;
+    if (h->kind == kNone) return fail(EF21_ESTATE, "no problem attached");
+    if (tau < 0 || tau > h->m) return fail(EF21_EINVAL, "tau must be in [0, m]");
+    if (tau > 0 && !rows) return fail(EF21_EINVAL, "rows is NULL");
+    h->batch = ef21::RowBatch();
+    if (tau > 0) {
+        h->batch.rows = rows;
+        h->batch.tau = tau;
+    }
     return EF21_OK;
 }
 

@@ -88,6 +88,13 @@ hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hi
 // `loss` below: the per-row loss of the linear model (LossKind in device_utils.h): logistic (eq. (9)) or squared.
 enum { kLossLogistic = 0, kLossLeastSquares = 1 };
 
+// The minibatch of Algorithm 5: worker i's gradient estimator sums the rows rows[i][0..tau) of its m rows
+// (tau <= m; an entry outside [0, m) contributes nothing) and divides by tau.  tau == 0: all rows, the gradient.
+struct RowBatch {
+    const int32_t *rows = nullptr;   // device, [n][tau]
+    int64_t tau = 0;
+};
+
 // Gradient of eq. (9) for all workers, dense rows.  scratch: logreg_dense_scratch_bytes.  With defer != nullptr
 // the last reduction may be left to the consumer: then *defer describes the partial sums (they live in
 // scratch until the next call) and grad is not written; defer->part == nullptr means grad was written.
@@ -95,21 +102,22 @@ size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d);
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
                                     int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
                                     const Marker &mk = Marker(), GradParts *defer = nullptr,
-                                    int loss = kLossLogistic);
+                                    int loss = kLossLogistic, RowBatch batch = RowBatch());
 
 // Gradient of eq. (9) for all workers, CSR rows with nnz entries in all.  `index`
 // (logreg_csr_index_bytes bytes, owned by the caller) is built once per problem by logreg_csr_build_index
 // and holds per-row column-range offsets, a range-major and a column-major copy of the matrix (6 bytes per
 // entry each) and scratch for the two-pass kernels.  The build synchronises the stream and reports whether those
 // kernels can be used (every row's columns ascending and inside [0, d), fewer than 2^31 entries per
-// worker); pass index = nullptr to launch_logreg_grad_csr otherwise.
+// worker); pass index = nullptr to launch_logreg_grad_csr otherwise.  Under a row batch the work is
+// proportional to the batch: one wavefront per listed row and global fp32 atomics, whatever the index.
 size_t logreg_csr_index_bytes(int32_t n, int64_t m, int64_t d, int64_t nnz);
 hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, const float *val, int32_t n, int64_t m,
                                   int64_t d, int64_t nnz, void *index, hipStream_t stream, bool *usable);
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
                                   float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker(),
-                                  int loss = kLossLogistic);
+                                  int loss = kLossLogistic, RowBatch batch = RowBatch());
 
 // Algorithm 3 (EF21+), lines 7 and 8, for all workers: from the gradients s [n][d], the estimators g_i [n][d]
 // (updated in place) and the two Top-k results (idx_b, val_b) = C(s), (idx_m, val_m) = C(s - g_i), all [n][k]:

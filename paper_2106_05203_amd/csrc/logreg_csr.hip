@@ -510,10 +510,18 @@ __global__ __launch_bounds__(kThreads) void csr_atomic_kernel(const int64_t *__r
                                                               const float *__restrict__ val,
                                                               const float *__restrict__ y,
                                                               const float *__restrict__ x, float *grad, int64_t rows,
-                                                              int64_t m, int64_t d, float inv_m, int loss) {
+                                                              int64_t m, int64_t d, float inv_m, int loss,
+                                                              const int32_t *__restrict__ batch, int64_t m_full) {
     const int lane = lane_id();
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
-    for (int64_t l = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; l < rows; l += nwaves) {
+    // rows = n * m entries; under a batch, entry e of worker e / m names one of that worker's m_full rows
+    for (int64_t e = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; e < rows; e += nwaves) {
+        int64_t l = e;
+        if (batch) {
+            const uint32_t b = (uint32_t)batch[e];
+            if (b >= (uint64_t)m_full) continue;        // outside the worker's rows: contributes nothing
+            l = (e / m) * m_full + b;
+        }
         const int64_t p0 = rowptr[l], p1 = rowptr[l + 1];
         float s = 0.f;
         // a column index outside [0, d) is skipped rather than dereferenced
@@ -523,7 +531,7 @@ __global__ __launch_bounds__(kThreads) void csr_atomic_kernel(const int64_t *__r
         }
         s = wave_sum(s);
         const float coef = loss_derivative(y[l], s, loss) * inv_m;
-        float *g = grad + (l / m) * d;
+        float *g = grad + (e / m) * d;
         for (int64_t p = p0 + lane; p < p1; p += kWave) {
             const uint32_t c = (uint32_t)col[p];
             if (c < (uint64_t)d) atomicAdd(g + c, coef * val[p]);
@@ -590,9 +598,11 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
 
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
-                                  float lambda, const void *index, hipStream_t stream, const Marker &mk, int loss) {
+                                  float lambda, const void *index, hipStream_t stream, const Marker &mk, int loss,
+                                  RowBatch batch) {
+    const int32_t *listed = batch.tau > 0 ? batch.rows : nullptr;
     const int64_t rows = (int64_t)n * m;
-    if (index) {
+    if (index && !listed) {
         IndexLayout ix;
         index_layout(n, m, d, nnz, (char *)const_cast<void *>(index), &ix);
         static bool configured = false;
@@ -632,8 +642,10 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
     hipLaunchKernelGGL(csr_regulariser_kernel, dim3((unsigned)rb, (unsigned)n), dim3(kThreads), 0, stream, x, grad, d,
                        lambda);
     mk(K_GRAD_AUX);
-    hipLaunchKernelGGL(csr_atomic_kernel, dim3(row_blocks(rows)), dim3(kThreads), 0, stream, rowptr, col, val, y, x,
-                       grad, rows, m, d, 1.0f / (float)m, loss);
+    const int64_t per_worker = listed ? batch.tau : m;
+    hipLaunchKernelGGL(csr_atomic_kernel, dim3(row_blocks((int64_t)n * per_worker)), dim3(kThreads), 0, stream, rowptr,
+                       col, val, y, x, grad, (int64_t)n * per_worker, per_worker, d, 1.0f / (float)per_worker, loss,
+                       listed, m);
     mk(K_GRAD_MAIN);
     return hipGetLastError();
 }
