@@ -437,6 +437,36 @@ def theta_beta(alpha: float):
     return 1.0 - r, (1.0 - alpha) / (1.0 - r)
 
 
+def smoothness_constants(problem) -> np.ndarray:
+    """L_i of the smoothness assumption of Section 3.4 for every worker, from the definition: the gradient of
+    f_i is Lipschitz with  c * lambda_max((1/m) A_i^T A_i) + 2 lam,  c the largest curvature of the per-row
+    loss in its margin (1/4 for the logistic loss of eq. (9), 2 for the square of Section 5.2) and 2 the
+    largest curvature of t^2 / (1 + t^2).  Exact symmetric eigenvalues (numpy); CSR problems are made dense,
+    so small sizes only."""
+    if isinstance(problem, LogRegCSR):
+        A = densify_csr(problem.rowptr, problem.col, problem.val, problem.n, problem.m, problem.d)
+        c = 0.25
+    else:
+        A = problem.A
+        c = 2.0 if isinstance(problem, LeastSquaresDense) else 0.25
+    out = np.empty(problem.n)
+    for i in range(problem.n):
+        Ai = A[i].astype(np.float64)
+        out[i] = c * np.linalg.eigvalsh(Ai.T @ Ai / problem.m)[-1] + 2.0 * problem.lam
+    return out
+
+
+def theory_stepsize(L_i, alpha: float, L: float = None) -> float:
+    """The largest stepsize Theorem 1 allows: 1 / (L + Ltilde sqrt(beta / theta)), Ltilde the quadratic mean of
+    the L_i; L defaults to their arithmetic mean (an upper bound on the smoothness constant of f, as noted
+    before the theorem).  alpha = k / d for Top-k."""
+    L_i = _f64(L_i)
+    theta, beta = theta_beta(alpha)
+    if L is None:
+        L = float(np.mean(L_i))
+    return 1.0 / (L + float(np.sqrt(np.mean(L_i * L_i))) * float(np.sqrt(beta / theta)))
+
+
 def distortion(state: EF21State, grads) -> float:
     """G^t = (1/n) sum_i ||g_i - grad f_i(x)||^2, eq. (8)."""
     diff = state.g_i - _f64(grads)
