@@ -133,6 +133,24 @@ int ef21_set_loss(ef21_handle h, int loss);
 int ef21_set_minibatch(ef21_handle h, const int32_t *rows, int64_t tau);
 
 /*
+ * The largest stepsize Theorem 1 allows for the attached problem (Section 3.4, the bound on gamma in the theorem),
+ *   gamma = 1 / (L + Ltilde sqrt(beta / theta)),   sqrt(beta / theta) = (1 + sqrt(1 - alpha)) / alpha - 1,
+ * alpha = k / d for Top-k, Ltilde the quadratic mean of the workers' smoothness constants
+ *   L_i = c lambda_max((1/m) A_i^T A_i) + 2 lambda
+ * (c = 1/4 for the logistic loss, 2 for least squares: the largest curvature of the per-row loss; 2 is the
+ * largest curvature of t^2 / (1 + t^2)), and L = c lambda_max((1/(n m)) sum_i A_i^T A_i) + 2 lambda for f itself.
+ * The eigenvalues come from `iterations` steps of the power iteration on the GPU (each step two passes of
+ * the gradient kernels over the problem), started from a fixed positive vector; the estimate |M v| for the
+ * unit vector v of the last step approaches lambda_max from below, so few iterations give a stepsize that is
+ * too large by the same factor: 100 to 300 steps bring problems without a dominant direction within about one
+ * per cent.  gamma, L, L_i [n]: host memory, each may be NULL.  Uses the handle's loss, lambda and k, and all
+ * rows whatever ef21_set_minibatch says; the handle's stepsize is not changed.  Allocates (n + 2) d floats for
+ * the call, overwrites the handle's gradient buffer, and returns after the stream has drained.
+ * EF21_ESTATE without a problem; EF21_EINVAL: iterations outside [1, 10^6]; EF21_ENOMEM.
+ */
+int ef21_theory_stepsize(ef21_handle h, int32_t iterations, double *gamma, double *L, double *L_i);
+
+/*
  * State of Algorithm 2.  set: copies x [d] and g_i [n][d] into the handle (either may be NULL
  * = keep); g [d] NULL means "recompute g = (1/n) sum_i g_i" (the algorithm's input line).
  * get: copies the handle's state out; any pointer may be NULL.

@@ -23,7 +23,7 @@ SYMBOLS = (
     "ef21_last_error", "ef21_create", "ef21_destroy", "ef21_set_stream", "ef21_topk",
     "ef21_set_problem_dense", "ef21_set_problem_csr", "ef21_set_state", "ef21_get_state",
     "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
-    "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices", "ef21_set_loss", "ef21_set_minibatch",
+    "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices", "ef21_set_loss", "ef21_set_minibatch", "ef21_theory_stepsize",
 )
 K_COUNT = 10
 
@@ -68,6 +68,7 @@ def load_library() -> C.CDLL:
     lib.ef21_get_choices.argtypes = [p, p, p]
     lib.ef21_set_loss.argtypes = [p, C.c_int]
     lib.ef21_set_minibatch.argtypes = [p, p, C.c_int64]
+    lib.ef21_theory_stepsize.argtypes = [p, C.c_int32, p, p, p]
     lib.ef21_hbm_read.argtypes = [p, C.c_int64, p, p]
     lib.ef21_hbm_copy.argtypes = [p, p, C.c_int64, p]
     for name in SYMBOLS[2:]:
@@ -236,6 +237,14 @@ class EF21:
             assert rows.shape[0] == self.n
             _check(self._lib.ef21_set_minibatch(self._h, rows.data_ptr(), int(rows.shape[1])))
             self._batch = rows
+
+    def theory_stepsize(self, iterations: int = 200):
+        """(gamma, L, L_i [n]) of Theorem 1 for the attached problem, eigenvalues by power iteration on the GPU."""
+        gamma, L = C.c_double(), C.c_double()
+        L_i = (C.c_double * self.n)()
+        with torch.cuda.device(self.device):
+            _check(self._lib.ef21_theory_stepsize(self._h, int(iterations), C.byref(gamma), C.byref(L), L_i))
+        return gamma.value, L.value, list(L_i)
 
     def get_choices(self):
         """(branch [n] int32: 1 = plain compressor chosen, distortions [n][2] float64: B_i, M_i) of the last

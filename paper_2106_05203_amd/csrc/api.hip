@@ -448,6 +448,76 @@ int ef21_local_grad(ef21_handle h, const float *x, float *out_grad) {
     return enqueue_local_grad(h, x ? x : h->x, out_grad);
 }
 
+// (1/m) A_i^T A_i v_i for every worker (v one row per worker, or one shared row): the gradient kernels with the
+// per-row loss z^2 / 2, no regulariser, all rows.
+static int enqueue_gram_product(ef21_ctx *c, const float *v, int64_t v_stride, float *out) {
+    hipError_t st;
+    if (c->kind == kDense)
+        st = ef21::launch_logreg_grad_dense(c->A, c->y, v, out, c->n, c->m, c->d, 0.f, c->scratch, c->stream,
+                                            ef21::Marker(), nullptr, ef21::kLossHalfSquare, ef21::RowBatch(), v_stride);
+    else
+        st = ef21::launch_logreg_grad_csr(c->rowptr, c->col, c->val, c->y, v, out, c->n, c->m, c->d, c->nnz, 0.f,
+                                          c->csr_indexed ? c->csr_index : nullptr, c->stream, ef21::Marker(),
+                                          ef21::kLossHalfSquare, ef21::RowBatch(), v_stride);
+    if (st != hipSuccess) return fail_hip(st, "gradient kernel launch");
+    return EF21_OK;
+}
+
+int ef21_theory_stepsize(ef21_handle h, int32_t iterations, double *gamma, double *L, double *L_i) {
+    if (int rc = check_handle(h)) return rc;
+    if (h->kind == kNone) return fail(EF21_ESTATE, "no problem attached (ef21_set_problem_dense / _csr)");
+    if (iterations < 1 || iterations > 1000000) return fail(EF21_EINVAL, "iterations must be in [1, 10^6]");
+    const int32_t n = h->n;
+    const int64_t d = h->d;
+    // rows 0..n-1: the workers' vectors; row n: the vector of the whole problem; row n+1: its product
+    float *v = nullptr;
+    double *stats = nullptr;
+    if (hipMalloc((void **)&v, sizeof(float) * (size_t)(n + 2) * (size_t)d) != hipSuccess ||
+        hipMalloc((void **)&stats, sizeof(double) * 2 * (size_t)(n + 1)) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(v);
+        return fail(EF21_ENOMEM, "hipMalloc of the power iteration's vectors failed");
+    }
+    float *v_all = v + (size_t)n * d, *w_all = v_all + d;
+    int rc = EF21_OK;
+    hipError_t st = ef21::launch_power_start(v, n + 1, d, h->stream);
+    for (int32_t it = 0; it < iterations && st == hipSuccess && rc == EF21_OK; ++it) {
+        rc = enqueue_gram_product(h, v, d, h->grad);                         // w_i = (1/m) A_i^T A_i v_i
+        if (rc != EF21_OK) break;
+        st = ef21::launch_power_step(h->grad, v, n, d, stats, h->stream);
+        if (st != hipSuccess) break;
+        rc = enqueue_gram_product(h, v_all, 0, h->grad);                     // (1/n) sum_i (1/m) A_i^T A_i v
+        if (rc != EF21_OK) break;
+        st = ef21::launch_mean_rows(h->grad, w_all, n, d, h->stream);
+        if (st != hipSuccess) break;
+        st = ef21::launch_power_step(w_all, v_all, 1, d, stats + 2 * (size_t)n, h->stream);
+    }
+    std::vector<double> host(2 * (size_t)(n + 1));
+    if (st == hipSuccess && rc == EF21_OK)
+        st = hipMemcpyAsync(host.data(), stats, sizeof(double) * host.size(), hipMemcpyDeviceToHost, h->stream);
+    const hipError_t sync = hipStreamSynchronize(h->stream);        // also before the vectors are freed
+    (void)hipFree(v);
+    (void)hipFree(stats);
+    if (rc != EF21_OK) return rc;
+    if (st != hipSuccess) return fail_hip(st, "power iteration");
+    if (sync != hipSuccess) return fail_hip(sync, "power iteration");
+    // curvature of the per-row loss in its margin, and of lambda t^2 / (1 + t^2)
+    const double c = h->loss == EF21_LOSS_LEAST_SQUARES ? 2.0 : 0.25, reg = 2.0 * (double)h->lambda;
+    double sum_sq = 0.0;
+    for (int32_t i = 0; i < n; ++i) {
+        const double Li = c * host[2 * (size_t)i + 1] + reg;
+        if (L_i) L_i[i] = Li;
+        sum_sq += Li * Li;
+    }
+    const double L_all = c * host[2 * (size_t)n + 1] + reg;
+    if (L) *L = L_all;
+    if (gamma) {
+        const double alpha = (double)h->k / (double)d, r = sqrt(1.0 - alpha);
+        *gamma = 1.0 / (L_all + sqrt(sum_sq / n) * ((1.0 + r) / alpha - 1.0));
+    }
+    return EF21_OK;
+}
+
 // Buffers of Algorithm 3, allocated by the first EF21_PLUS step of a handle.
 static int ensure_plus_buffers(ef21_ctx *c) {
     if (c->plus_bm) return EF21_OK;

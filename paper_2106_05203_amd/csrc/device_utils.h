@@ -33,7 +33,9 @@ __device__ __forceinline__ int32_t stream_load(const int32_t *p) { return __buil
 // Derivative in z of the per-row loss of a linear model, z = a^T x:
 //   kLossLogistic       log(1 + exp(-y z))  (Section 5, eq. (9)):   -y / (1 + exp(y z))
 //   kLossLeastSquares   (z - y)^2           (Section 5.2):          2 (z - y)
+//   kLossHalfSquare     z^2 / 2 (no target; its "gradient" is (1/m) A^T A x, used by the power iteration): z
 __device__ __forceinline__ float loss_derivative(float y, float z, int loss) {
+    if (loss == 2 /* kLossHalfSquare */) return z;
     return loss == 1 /* kLossLeastSquares */ ? 2.0f * (z - y) : -y / (1.0f + expf(y * z));
 }
 

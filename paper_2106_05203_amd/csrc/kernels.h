@@ -86,7 +86,9 @@ hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int
 hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hipStream_t stream);
 
 // `loss` below: the per-row loss of the linear model (LossKind in device_utils.h): logistic (eq. (9)) or squared.
-enum { kLossLogistic = 0, kLossLeastSquares = 1 };
+// kLossHalfSquare (z^2 / 2, no target) is internal: its gradient is (1/m) A_i^T A_i x, the product the power
+// iteration needs.  x_stride below: 0 = one x [d] for all workers, d = a row of x [n][d] per worker.
+enum { kLossLogistic = 0, kLossLeastSquares = 1, kLossHalfSquare = 2 };
 
 // The minibatch of Algorithm 5: worker i's gradient estimator sums the rows rows[i][0..tau) of its m rows
 // (tau <= m; an entry outside [0, m) contributes nothing) and divides by tau.  tau == 0: all rows, the gradient.
@@ -102,7 +104,7 @@ size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d);
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
                                     int64_t m, int64_t d, float lambda, void *scratch, hipStream_t stream,
                                     const Marker &mk = Marker(), GradParts *defer = nullptr,
-                                    int loss = kLossLogistic, RowBatch batch = RowBatch());
+                                    int loss = kLossLogistic, RowBatch batch = RowBatch(), int64_t x_stride = 0);
 
 // Gradient of eq. (9) for all workers, CSR rows with nnz entries in all.  `index`
 // (logreg_csr_index_bytes bytes, owned by the caller) is built once per problem by logreg_csr_build_index
@@ -117,7 +119,7 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
                                   float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker(),
-                                  int loss = kLossLogistic, RowBatch batch = RowBatch());
+                                  int loss = kLossLogistic, RowBatch batch = RowBatch(), int64_t x_stride = 0);
 
 // Algorithm 3 (EF21+), lines 7 and 8, for all workers: from the gradients s [n][d], the estimators g_i [n][d]
 // (updated in place) and the two Top-k results (idx_b, val_b) = C(s), (idx_m, val_m) = C(s - g_i), all [n][k]:
@@ -127,6 +129,12 @@ size_t plus_scratch_bytes(int32_t n, int64_t d);
 hipError_t launch_plus_choose(const float *s, float *g_i, int32_t n, int64_t d, int64_t k, const int32_t *idx_b,
                               const float *val_b, const int32_t *idx_m, const float *val_m, void *scratch,
                               int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream);
+
+// Power iteration for the smoothness constants of Section 3.4: v [rows][d] <- a fixed positive start vector;
+// and one step: stats[row] = (v^T w / v^T v, |w| / |v|) as two doubles, v <- w / |w|, for w = M v, M symmetric
+// positive semidefinite (both numbers are lower bounds of its largest eigenvalue).
+hipError_t launch_power_start(float *v, int32_t rows, int64_t d, hipStream_t stream);
+hipError_t launch_power_step(const float *w, float *v, int32_t rows, int64_t d, double *stats, hipStream_t stream);
 
 // Algorithm 4 (EF): e <- e + gamma s over all n * d entries; e <- 0 at the kept positions idx [n][k]; v <- 0.
 hipError_t launch_ef_accumulate(const float *s, float *e, int32_t n, int64_t d, float gamma, hipStream_t stream);

@@ -60,10 +60,11 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_fused_kernel(const floa
                                                                       float *__restrict__ part, int64_t m,
                                                                       int64_t d, int64_t rows_per_wg, int loss,
                                                                       const int32_t *__restrict__ batch,
-                                                                      int64_t m_full) {
+                                                                      int64_t m_full, int64_t x_stride) {
     constexpr int kCols = NQ * kWave * VEC;   // columns covered by one wavefront
     __shared__ float red[kCols];
     const int64_t worker = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
+    x += worker * x_stride;                   // 0: one x for all workers
     const int wave = threadIdx.x / kWave, lane = lane_id();
 
     float xr[NQ][VEC], acc[NQ][VEC];
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_residual_kernel(const f
                                                                          float *__restrict__ r, int64_t rows,
                                                                          int64_t d, int loss, int64_t m,
                                                                          const int32_t *__restrict__ batch,
-                                                                         int64_t m_full) {
+                                                                         int64_t m_full, int64_t x_stride) {
     const int lane = lane_id();
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
     for (int64_t l = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave; l < rows; l += nwaves) {
@@ -170,8 +171,9 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_residual_kernel(const f
             src = (l / m) * m_full + b;
         }
         const float *row = A + src * d;
+        const float *xw = x + (l / m) * x_stride;
         float s = 0.f;
-        for (int64_t c = lane; c < d; c += kWave) s = fmaf(row[c], x[c], s);
+        for (int64_t c = lane; c < d; c += kWave) s = fmaf(row[c], xw[c], s);
         s = wave_sum(s);
         if (lane == 0) r[l] = loss_derivative(y[src], s, loss);
     }
@@ -204,10 +206,13 @@ __global__ __launch_bounds__(kThreads) void logreg_dense_atr_kernel(const float 
 __global__ __launch_bounds__(kThreads) void logreg_dense_finish_kernel(const float *__restrict__ part,
                                                                        const float *__restrict__ x,
                                                                        float *__restrict__ grad, int64_t chunks,
-                                                                       int64_t m, int64_t d, float lambda) {
+                                                                       int64_t m, int64_t d, float lambda,
+                                                                       int64_t x_stride) {
     const int64_t worker = blockIdx.y;
     const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (c < d) grad[worker * d + c] = dense_grad_entry(part + worker * chunks * d, chunks, d, c, x[c], m, lambda);
+    if (c < d)
+        grad[worker * d + c] =
+            dense_grad_entry(part + worker * chunks * d, chunks, d, c, x[worker * x_stride + c], m, lambda);
 }
 
 struct DenseArgs {
@@ -218,7 +223,7 @@ struct DenseArgs {
     DensePlan pl;
     int loss;
     const int32_t *batch;
-    int64_t m_full;
+    int64_t m_full, x_stride;
 };
 
 template <int VEC, int NQ>
@@ -227,10 +232,10 @@ void launch_fused(const DenseArgs &a, hipStream_t stream) {
     const dim3 grid((unsigned)a.pl.chunks, (unsigned)a.n);
     if (a.batch)
         hipLaunchKernelGGL((logreg_dense_fused_kernel<VEC, NQ, ROWS, true>), grid, dim3(kThreads), 0, stream, a.A, a.y,
-                           a.x, a.part, a.m, a.d, a.pl.rows_per_wg, a.loss, a.batch, a.m_full);
+                           a.x, a.part, a.m, a.d, a.pl.rows_per_wg, a.loss, a.batch, a.m_full, a.x_stride);
     else
         hipLaunchKernelGGL((logreg_dense_fused_kernel<VEC, NQ, ROWS, false>), grid, dim3(kThreads), 0, stream, a.A, a.y,
-                           a.x, a.part, a.m, a.d, a.pl.rows_per_wg, a.loss, a.batch, a.m_full);
+                           a.x, a.part, a.m, a.d, a.pl.rows_per_wg, a.loss, a.batch, a.m_full, a.x_stride);
 }
 
 }  // namespace
@@ -241,7 +246,7 @@ size_t logreg_dense_scratch_bytes(int32_t n, int64_t m, int64_t d) {
 
 hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float *x, float *grad, int32_t n,
                                     int64_t m_full, int64_t d, float lambda, void *scratch, hipStream_t stream,
-                                    const Marker &mk, GradParts *defer, int loss, RowBatch rb) {
+                                    const Marker &mk, GradParts *defer, int loss, RowBatch rb, int64_t x_stride) {
     if (defer) *defer = GradParts();
     const int32_t *batch = rb.tau > 0 ? rb.rows : nullptr;
     const int64_t m = batch ? rb.tau : m_full;         // rows summed per worker (tau <= m_full, checked by the caller)
@@ -249,7 +254,7 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
     float *part = (float *)scratch;
     float *resid = part + (size_t)n * max_chunks(n, m_full) * d;
     const bool vec4 = (d % 4 == 0) && ((uintptr_t)A % 16 == 0);
-    const DenseArgs a{A, y, x, part, n, m, d, pl, loss, batch, m_full};
+    const DenseArgs a{A, y, x, part, n, m, d, pl, loss, batch, m_full, x_stride};
     bool fused = true;
     if (vec4 && d <= 256) launch_fused<4, 1>(a, stream);
     else if (vec4 && d <= 512) launch_fused<4, 2>(a, stream);
@@ -265,7 +270,7 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
         int64_t blocks = (rows + kWaves - 1) / kWaves;
         if (blocks > 16384) blocks = 16384;
         hipLaunchKernelGGL(logreg_dense_residual_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, A, y, x,
-                           resid, rows, d, loss, m, batch, m_full);
+                           resid, rows, d, loss, m, batch, m_full, x_stride);
         hipLaunchKernelGGL(logreg_dense_atr_kernel,
                            dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)pl.chunks, (unsigned)n),
                            dim3(kThreads), 0, stream, A, resid, part, m, d, pl.rows_per_wg, batch, m_full);
@@ -273,12 +278,12 @@ hipError_t launch_logreg_grad_dense(const float *A, const float *y, const float 
     mk(K_GRAD_MAIN);
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;
-    if (defer && fused) {      // the consumer finishes the sums itself (dense_grad_entry)
+    if (defer && fused && x_stride == 0) {      // the consumer finishes the sums itself (dense_grad_entry)
         *defer = GradParts{part, pl.chunks, m, x, lambda};
         return hipSuccess;
     }
     hipLaunchKernelGGL(logreg_dense_finish_kernel, dim3((unsigned)((d + kThreads - 1) / kThreads), (unsigned)n),
-                       dim3(kThreads), 0, stream, part, x, grad, pl.chunks, m, d, lambda);
+                       dim3(kThreads), 0, stream, part, x, grad, pl.chunks, m, d, lambda, x_stride);
     mk(K_GRAD_AUX);
     return hipGetLastError();
 }

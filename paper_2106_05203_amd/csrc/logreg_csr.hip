@@ -306,7 +306,8 @@ __global__ __launch_bounds__(kCscThreads) void csrr_dot_kernel(const int64_t *__
                                                                const uint16_t *__restrict__ rcol,
                                                                const float *__restrict__ rval,
                                                                const float *__restrict__ x, float *__restrict__ zpart,
-                                                               int64_t m, int64_t d, int R, int64_t Wc) {
+                                                               int64_t m, int64_t d, int R, int64_t Wc,
+                                                               int64_t x_stride) {
     extern __shared__ float x_lds[];
     __shared__ __attribute__((aligned(16))) float tiles[kCscWaves][kTile];
     const int range = blockIdx.x % R;
@@ -314,7 +315,7 @@ __global__ __launch_bounds__(kCscThreads) void csrr_dot_kernel(const int64_t *__
     const int wave = threadIdx.x / kWave, lane = lane_id();
     const int64_t c0 = (int64_t)range * Wc;
     const int64_t width = c0 + Wc < d ? Wc : d - c0;
-    for (int64_t j = threadIdx.x; j < width; j += kCscThreads) x_lds[j] = x[c0 + j];
+    for (int64_t j = threadIdx.x; j < width; j += kCscThreads) x_lds[j] = x[worker * x_stride + c0 + j];
     __syncthreads();
     const int64_t l_first = (chunk * kCscWaves + wave) * (kCscGroups * kWave);
     if (l_first >= m) return;                                   // the whole wavefront; no barrier follows
@@ -464,7 +465,7 @@ __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__
                                                                const int64_t *__restrict__ rowptr,
                                                                const float *__restrict__ coef,
                                                                const float *__restrict__ x, float *__restrict__ grad,
-                                                               int64_t m, int64_t d, float lambda) {
+                                                               int64_t m, int64_t d, float lambda, int64_t x_stride) {
     extern __shared__ float coef_lds[];
     __shared__ __attribute__((aligned(16))) float tiles[kCscWaves][kTile];
     const int64_t worker = blockIdx.y;
@@ -491,18 +492,18 @@ __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__
 #pragma unroll
     for (int g = 0; g < kCscGroups; ++g) {
         const int64_t c = cb + g * kWave + lane;
-        if (c < d) grad[worker * d + c] = acc[g] + regulariser_grad(x[c], lambda);
+        if (c < d) grad[worker * d + c] = acc[g] + regulariser_grad(x[worker * x_stride + c], lambda);
     }
 }
 
 // ---- fallback: global atomics, any column order
 __global__ __launch_bounds__(kThreads) void csr_regulariser_kernel(const float *__restrict__ x,
                                                                    float *__restrict__ grad, int64_t d,
-                                                                   float lambda) {
+                                                                   float lambda, int64_t x_stride) {
     const int64_t worker = blockIdx.y;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x; c < d; c += stride)
-        grad[worker * d + c] = regulariser_grad(x[c], lambda);
+        grad[worker * d + c] = regulariser_grad(x[worker * x_stride + c], lambda);
 }
 
 __global__ __launch_bounds__(kThreads) void csr_atomic_kernel(const int64_t *__restrict__ rowptr,
@@ -511,7 +512,8 @@ __global__ __launch_bounds__(kThreads) void csr_atomic_kernel(const int64_t *__r
                                                               const float *__restrict__ y,
                                                               const float *__restrict__ x, float *grad, int64_t rows,
                                                               int64_t m, int64_t d, float inv_m, int loss,
-                                                              const int32_t *__restrict__ batch, int64_t m_full) {
+                                                              const int32_t *__restrict__ batch, int64_t m_full,
+                                                              int64_t x_stride) {
     const int lane = lane_id();
     const int64_t nwaves = (int64_t)gridDim.x * kWaves;
     // rows = n * m entries; under a batch, entry e of worker e / m names one of that worker's m_full rows
@@ -523,11 +525,12 @@ __global__ __launch_bounds__(kThreads) void csr_atomic_kernel(const int64_t *__r
             l = (e / m) * m_full + b;
         }
         const int64_t p0 = rowptr[l], p1 = rowptr[l + 1];
+        const float *xw = x + (e / m) * x_stride;
         float s = 0.f;
         // a column index outside [0, d) is skipped rather than dereferenced
         for (int64_t p = p0 + lane; p < p1; p += kWave) {
             const uint32_t c = (uint32_t)col[p];
-            if (c < (uint64_t)d) s = fmaf(val[p], x[c], s);
+            if (c < (uint64_t)d) s = fmaf(val[p], xw[c], s);
         }
         s = wave_sum(s);
         const float coef = loss_derivative(y[l], s, loss) * inv_m;
@@ -599,7 +602,7 @@ hipError_t logreg_csr_build_index(const int64_t *rowptr, const int32_t *col, con
 hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, const float *val, const float *y,
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
                                   float lambda, const void *index, hipStream_t stream, const Marker &mk, int loss,
-                                  RowBatch batch) {
+                                  RowBatch batch, int64_t x_stride) {
     const int32_t *listed = batch.tau > 0 ? batch.rows : nullptr;
     const int64_t rows = (int64_t)n * m;
     if (index && !listed) {
@@ -618,7 +621,7 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
         const int64_t row_chunks = (m + kCscCols - 1) / kCscCols;
         hipLaunchKernelGGL(csrr_dot_kernel, dim3((unsigned)(ix.R * row_chunks), (unsigned)n), dim3(kCscThreads),
                            sizeof(float) * (size_t)ix.Wc, stream, ix.bstart, ix.rptr, ix.rcol, ix.rval, x, ix.zpart, m, d,
-                           ix.R, ix.Wc);
+                           ix.R, ix.Wc, x_stride);
         mk(K_GRAD_MAIN);
         hipLaunchKernelGGL(csr_coef_kernel, dim3((unsigned)((rows + kThreads - 1) / kThreads)), dim3(kThreads), 0,
                            stream, y, ix.zpart, ix.R, rows, 1.0f / (float)m, ix.coef, loss);
@@ -627,25 +630,25 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
         static_assert(kCoefLdsRows <= kIdx16Rows, "a coefficient vector that fits LDS has 16-bit row indices");
         if (m <= kCoefLdsRows)
             hipLaunchKernelGGL((csc_grad_kernel<true, uint16_t>), grid, dim3(kCscThreads), sizeof(float) * (size_t)m, stream,
-                               ix.colptr, (const uint16_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
+                               ix.colptr, (const uint16_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda, x_stride);
         else if (m <= kIdx16Rows)
             hipLaunchKernelGGL((csc_grad_kernel<false, uint16_t>), grid, dim3(kCscThreads), 0, stream, ix.colptr,
-                               (const uint16_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
+                               (const uint16_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda, x_stride);
         else
             hipLaunchKernelGGL((csc_grad_kernel<false, int32_t>), grid, dim3(kCscThreads), 0, stream, ix.colptr,
-                               (const int32_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda);
+                               (const int32_t *)ix.csc_row, ix.csc_val, rowptr, ix.coef, x, grad, m, d, lambda, x_stride);
         mk(K_GRAD_MAIN);
         return hipGetLastError();
     }
     int64_t rb = (d + kThreads - 1) / kThreads;
     if (rb > 1024) rb = 1024;
     hipLaunchKernelGGL(csr_regulariser_kernel, dim3((unsigned)rb, (unsigned)n), dim3(kThreads), 0, stream, x, grad, d,
-                       lambda);
+                       lambda, x_stride);
     mk(K_GRAD_AUX);
     const int64_t per_worker = listed ? batch.tau : m;
     hipLaunchKernelGGL(csr_atomic_kernel, dim3(row_blocks((int64_t)n * per_worker)), dim3(kThreads), 0, stream, rowptr,
                        col, val, y, x, grad, (int64_t)n * per_worker, per_worker, d, 1.0f / (float)per_worker, loss,
-                       listed, m);
+                       listed, m, x_stride);
     mk(K_GRAD_MAIN);
     return hipGetLastError();
 }
