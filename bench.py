@@ -94,8 +94,13 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
     out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", "ms_per_step": round(wall, 5),
            "ms_per_step_events": round(ev, 5), "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()},
            "iteration_algorithmic_bytes": 4 * n * m * d + 4 * n * m + 12 * n * d + 24 * n * k + 12 * d}
-    out["roofline"] = roofline(4.0 * n * m * d + 4.0 * n * m + 4.0 * d, per_kernel["grad_main"],
-                               "logreg_dense_fused_kernel (grad_main)", MEASURED_TRAFFIC_BYTES.get(f"{name}/grad_main"))
+    if "grad_main" in per_kernel:
+        out["roofline"] = roofline(4.0 * n * m * d + 4.0 * n * m + 4.0 * d, per_kernel["grad_main"],
+                                   "logreg_dense_fused_kernel (grad_main)",
+                                   MEASURED_TRAFFIC_BYTES.get(f"{name}/grad_main"))
+    else:                 # the whole iteration is one kernel
+        out["roofline"] = roofline(out["iteration_algorithmic_bytes"], per_kernel["small_step"],
+                                   "small_step_kernel (the whole iteration)", None)
     out["iteration_frac_of_hbm_peak"] = round(out["iteration_algorithmic_bytes"] / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     if name == "C2":      # the same problem under Algorithm 3 (EF21+): two Top-k selections and the choice per worker
         wall_p, _ = timed_loop(torch, lambda i: h.step(None, binding.PLUS), steps, warmup)
@@ -124,7 +129,11 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
         out["ef21_stochastic"] = {"value": round(1e3 / wall_s, 2), "unit": "Algorithm 5 iterations/s", "tau": tau,
                                   "ms_per_step": round(wall_s, 5), "grad_main_ms": round(pk["grad_main"], 5),
                                   "grad_main_GBps": round(gbytes / (pk["grad_main"] * 1e-3) / 1e9, 1)}
-    if name == "C0":      # launch-bound: the same iterations replayed from a HIP graph of 10 captured steps
+    if name == "C0":      # launch-bound: the default is the one-launch iteration; beside it the separate kernels,
+        wall_sep, _ = timed_loop(torch, lambda i: h.step(None, binding.SEPARATE_KERNELS), steps, warmup)
+        out["separate_kernels"] = {"value": round(1e3 / wall_sep, 2), "unit": "EF21 iterations/s",
+                                   "ms_per_step": round(wall_sep, 5)}
+        # and the same iterations replayed from a HIP graph of 10 captured steps
         out["hip_graph_10_steps"] = graph_replay(torch, h, steps)
     return out, (W, h)
 

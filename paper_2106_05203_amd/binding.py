@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libef21.so")
 
 EF21_OK, EF21_EINVAL, EF21_ENOMEM, EF21_EHIP, EF21_ESTATE = 0, -1, -2, -3, -4
-ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS, CLASSIC_EF = 0, 1, 2, 4
+ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS, CLASSIC_EF, SEPARATE_KERNELS = 0, 1, 2, 4, 8
 LOSS_LOGISTIC, LOSS_LEAST_SQUARES = 0, 1
 
 # every symbol include/ef21.h declares
@@ -25,7 +25,7 @@ SYMBOLS = (
     "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
     "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices", "ef21_set_loss", "ef21_set_minibatch", "ef21_theory_stepsize",
 )
-K_COUNT = 10
+K_COUNT = 11
 
 
 class EF21Error(RuntimeError):

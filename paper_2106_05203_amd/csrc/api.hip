@@ -88,6 +88,7 @@ struct ef21_ctx {
     size_t scratch_bytes = 0;
     void *topk_ws = nullptr;
     void *agg_index = nullptr;      // runs of the messages per coordinate sub-block (scratch of line 8)
+    void *tickets = nullptr;        // counters of the one-launch iteration (zero between launches)
     void *csr_index = nullptr;      // column-range index of the attached CSR problem
     bool csr_indexed = false;
     int64_t nnz = 0;                // entries of the attached CSR problem
@@ -174,6 +175,7 @@ void free_ctx(ef21_ctx *c) {
     (void)hipFree(c->topk_ws);
     (void)hipFree(c->csr_index);
     (void)hipFree(c->agg_index);
+    (void)hipFree(c->tickets);
     (void)hipFree(c->plus_idx);
     (void)hipFree(c->plus_val);
     (void)hipFree(c->plus_scratch);
@@ -345,6 +347,15 @@ int ef21_set_problem_dense(ef21_handle h, const float *A, const float *y, int64_
     if (m < 1 || m >= ((int64_t)1 << 31)) return fail(EF21_EINVAL, "m must be in [1, 2^31)");
     if (!(lambda >= 0.f) || !std::isfinite(lambda)) return fail(EF21_EINVAL, "lambda must be finite and >= 0");
     if (int rc = ensure_problem_buffers(h, ef21::logreg_dense_scratch_bytes(h->n, m, h->d))) return rc;
+    if (!h->tickets && ef21::small_step_applies(A, h->n, m, h->d, h->k)) {
+        const size_t bytes = ef21::small_step_ticket_bytes(h->n);
+        if (hipMalloc(&h->tickets, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            h->tickets = nullptr;
+            return fail(EF21_ENOMEM, "hipMalloc of the iteration's counters failed");
+        }
+        EF21_HIP(hipMemsetAsync(h->tickets, 0, bytes, h->stream));
+    }
     h->kind = kDense;
     h->batch = ef21::RowBatch();
     h->A = A;
@@ -582,11 +593,13 @@ static int enqueue_classic_ef(ef21_ctx *h, const float *grads, const ef21::Marke
 
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
     if (int rc = check_handle(h)) return rc;
-    if (flags > (EF21_ORDER_STEP_FIRST | EF21_PLUS) && flags != EF21_CLASSIC_EF)
-        return fail(EF21_EINVAL, "unknown flags (EF21_CLASSIC_EF combines with no other flag)");
+    if (flags & ~(uint32_t)(EF21_ORDER_STEP_FIRST | EF21_PLUS | EF21_CLASSIC_EF | EF21_SEPARATE_KERNELS))
+        return fail(EF21_EINVAL, "unknown flags");
+    if ((flags & EF21_CLASSIC_EF) && (flags & (EF21_ORDER_STEP_FIRST | EF21_PLUS)))
+        return fail(EF21_EINVAL, "EF21_CLASSIC_EF combines with neither an order nor EF21_PLUS");
     if (!grads && h->kind == kNone)
         return fail(EF21_ESTATE, "grads is NULL and no problem is attached to compute them from");
-    if (flags == EF21_CLASSIC_EF) {
+    if (flags & EF21_CLASSIC_EF) {
         const ef21::Marker mk0 = marker_of(h);
         mk0(-1);
         if (!grads) {
@@ -617,6 +630,16 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
             mk(ef21::K_MODEL_STEP);
             if (st != hipSuccess) return fail_hip(st, "model step launch");
         }
+        return EF21_OK;
+    }
+    if (!grads && h->kind == kDense && h->tickets && h->batch.tau == 0 && !(flags & EF21_SEPARATE_KERNELS) &&
+        ef21::small_step_applies(h->A, h->n, h->m, h->d, h->k)) {
+        // lines 5, 6, 8 (and 3) in one launch
+        hipError_t st = ef21::launch_small_step(h->A, h->y, h->x, h->g, h->g_i, h->n, h->m, h->d, h->k, h->lambda,
+                                                h->gamma, h->loss, !step_first, h->scratch, h->tickets, h->msg_idx,
+                                                h->msg_val, h->stream);
+        mk(ef21::K_SMALL_STEP);
+        if (st != hipSuccess) return fail_hip(st, "iteration kernel launch");
         return EF21_OK;
     }
     ef21::GradParts parts;
@@ -694,7 +717,7 @@ int ef21_hbm_copy(void *dst, const void *src, int64_t bytes, void *hip_stream) {
 const char *ef21_kernel_name(int kernel_class) {
     static const char *names[EF21_K_COUNT] = {"grad_main",   "grad_aux",   "topk_row",  "topk_collect", "topk_select",
                                               "topk_refine", "topk_count", "topk_emit", "model_step",
-                                              "plus"};
+                                              "plus",        "small_step"};
     return (kernel_class >= 0 && kernel_class < EF21_K_COUNT) ? names[kernel_class] : "";
 }
 

@@ -18,6 +18,7 @@ enum KernelId {
     K_TOPK_EMIT,       // long rows, large k: ordered emission (+ fused update)
     K_MODEL_STEP,      // g <- g + mean of the messages and / or x <- x - gamma g
     K_PLUS,            // Algorithm 3: distortions, choice and update of g_i, mean of the rows
+    K_SMALL_STEP,      // the whole iteration of Algorithm 2 in one launch (small dense problems)
     K_COUNT
 };
 
@@ -120,6 +121,17 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
                                   const float *x, float *grad, int32_t n, int64_t m, int64_t d, int64_t nnz,
                                   float lambda, const void *index, hipStream_t stream, const Marker &mk = Marker(),
                                   int loss = kLossLogistic, RowBatch batch = RowBatch(), int64_t x_stride = 0);
+
+// Small dense problems: lines 5, 6, 8 (and 3 if take_step) of Algorithm 2 in ONE launch, from the problem and the
+// state, with the arithmetic of the separate kernels (gradient, row Top-k with update, aggregation), so the
+// results are the same bits.  small_step_applies says whether the shape qualifies (d <= 1024, n * k <= 2048,
+// n * m * d <= 2^24, ...).  scratch: logreg_dense_scratch_bytes; tickets: small_step_ticket_bytes(n) bytes,
+// zero before the first launch (the kernel leaves them zero).
+bool small_step_applies(const float *A, int32_t n, int64_t m, int64_t d, int64_t k);
+size_t small_step_ticket_bytes(int32_t n);
+hipError_t launch_small_step(const float *A, const float *y, float *x, float *g, float *g_i, int32_t n, int64_t m,
+                             int64_t d, int64_t k, float lambda, float gamma, int loss, bool take_step, void *scratch,
+                             void *tickets, int32_t *msg_idx, float *msg_val, hipStream_t stream);
 
 // Algorithm 3 (EF21+), lines 7 and 8, for all workers: from the gradients s [n][d], the estimators g_i [n][d]
 // (updated in place) and the two Top-k results (idx_b, val_b) = C(s), (idx_m, val_m) = C(s - g_i), all [n][k]:

@@ -3,7 +3,10 @@
 // and the long-row path's per-row select / rescue kernels.  1024 threads per workgroup.
 //
 // The k largest magnitudes of a row are found on the 31-bit magnitude key (fp32 bits with the sign
-// cleared): three histogram passes (12 + 10 + 9 bits, LDS histograms) fix the key T of the k-th
+// cleared): a histogram pass over the top 12 bits (LDS histogram) finds the bin that holds the k-th largest
+// magnitude; the entries of that bin, usually a few dozen, are gathered and ranked against one another
+// (two more histogram passes, 10 + 9 bits, when the bin is crowded; no histogram at all for rows of at most
+// 256 entries, which are ranked whole), which fixes the key T of the k-th
 // largest magnitude and the number q of entries equal to T that are still needed; an ordered
 // emission then writes every entry with key > T and the first q entries with key == T, in
 // ascending position order (ties go to the lower index).
@@ -19,13 +22,20 @@ constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kBits1 = 12, kBits2 = 10, kBits3 = 9;   // 31 key bits
 static_assert(kBits1 + kBits2 + kBits3 == 31, "digits must cover the magnitude key");
 
+constexpr int kRankMax = 256;   // a selected bin with at most this many entries is ranked directly
+
 struct RowShared {
     uint32_t hist[1 << kBits1];
     uint32_t wave_a[kRowWaves];
     uint32_t wave_b[kRowWaves];
     uint32_t bin;     // selected digit
     uint32_t need;    // entries still needed from inside the selected bin
+    uint32_t ncand;   // entries gathered from the selected bin
+    uint32_t cand_key[kRankMax];
+    uint32_t cand_idx[kRankMax];
+    uint32_t cand_rank[kRankMax];   // low half: gathered entries with a larger key; high half: equal key, lower position
 };
+static_assert(kRankMax <= 0xffff, "two counts of at most kRankMax share one word");
 
 template <bool DIFF>
 __device__ __forceinline__ float load_v(const float *a, const float *b, int64_t e) {
@@ -87,18 +97,69 @@ __device__ void row_topk_on(RowShared &s, const TopkArgs &p, int64_t row, ValueF
     const int64_t d = p.d;
 
     // ---- threshold key T and tie quota q ------------------------------------------------
-    hist_pass(s, d, value, 31, 0u, kBits2 + kBits3, 1 << kBits1);
-    select_bin(s, 1 << kBits1, (uint32_t)p.k);
-    const uint32_t d1 = s.bin;
-    uint32_t need = s.need;
-    hist_pass(s, d, value, kBits2 + kBits3, d1, kBits3, 1 << kBits2);
-    select_bin(s, 1 << kBits2, need);
-    const uint32_t d12 = (d1 << kBits2) | s.bin;
-    need = s.need;
-    hist_pass(s, d, value, kBits3, d12, 0, 1 << kBits3);
-    select_bin(s, 1 << kBits3, need);
-    const uint32_t T = (d12 << kBits3) | s.bin;
-    const uint32_t q = s.need;   // 1 <= q <= number of entries with key == T
+    // rows of at most kRankMax entries: every entry is a candidate and the histogram is skipped
+    const bool whole_row = d <= kRankMax;
+    uint32_t d1 = 0u, need = (uint32_t)p.k, in_bin = (uint32_t)d;
+    if (!whole_row) {
+        hist_pass(s, d, value, 31, 0u, kBits2 + kBits3, 1 << kBits1);
+        select_bin(s, 1 << kBits1, (uint32_t)p.k);
+        d1 = s.bin;
+        need = s.need;
+        in_bin = s.hist[d1];
+    }
+    if (threadIdx.x == 0) s.ncand = 0u;
+    if (threadIdx.x < kRankMax) s.cand_rank[threadIdx.x] = 0u;
+    __syncthreads();                             // everybody has read hist[d1] before either branch reuses hist
+    uint32_t T, q;
+    if (in_bin <= (uint32_t)kRankMax) {
+        // the bin's entries side by side (in any order), then every one counts those that go before it in the
+        // order (larger key first, lower position first among equal keys): the one that `need - 1` others
+        // precede is the last entry kept, its key is T, and q counts it and the equal keys before it
+        for (int64_t e = threadIdx.x; e < d; e += kRowThreads) {
+            const uint32_t key = mag_key(value(e));
+            if (whole_row || (key >> (kBits2 + kBits3)) == d1) {
+                const uint32_t at = atomicAdd(&s.ncand, 1u);
+                s.cand_key[at] = key;
+                s.cand_idx[at] = (uint32_t)e;
+            }
+        }
+        __syncthreads();
+        // c * c comparisons over all threads: thread t compares entry t mod c with one slice of the others
+        const uint32_t c = s.ncand;
+        const uint32_t parts = (uint32_t)kRowThreads / c, per = (c + parts - 1u) / parts;
+        if (threadIdx.x < c * parts) {
+            const uint32_t i = threadIdx.x % c, j0 = (threadIdx.x / c) * per;
+            const uint32_t j1 = j0 + per < c ? j0 + per : c;
+            const uint32_t my_key = s.cand_key[i], my_idx = s.cand_idx[i];
+            uint32_t counts = 0u;
+#pragma unroll 8
+            for (uint32_t j = j0; j < j1; ++j) {
+                const uint32_t kj = s.cand_key[j], ij = s.cand_idx[j];
+                counts += (kj > my_key ? 1u : 0u) + ((kj == my_key && ij < my_idx) ? 0x10000u : 0u);
+            }
+            if (counts) atomicAdd(&s.cand_rank[i], counts);
+        }
+        __syncthreads();
+        if (threadIdx.x < c) {
+            const uint32_t r = s.cand_rank[threadIdx.x], larger = r & 0xffffu, equal_before = r >> 16;
+            if (larger + equal_before == need - 1u) {          // exactly one thread
+                s.bin = s.cand_key[threadIdx.x];
+                s.need = equal_before + 1u;
+            }
+        }
+        __syncthreads();
+        T = s.bin;
+        q = s.need;
+    } else {
+        hist_pass(s, d, value, kBits2 + kBits3, d1, kBits3, 1 << kBits2);
+        select_bin(s, 1 << kBits2, need);
+        const uint32_t d12 = (d1 << kBits2) | s.bin;
+        need = s.need;
+        hist_pass(s, d, value, kBits3, d12, 0, 1 << kBits3);
+        select_bin(s, 1 << kBits3, need);
+        T = (d12 << kBits3) | s.bin;
+        q = s.need;   // 1 <= q <= number of entries with key == T
+    }
 
     // ---- ordered emission: each wavefront owns a contiguous piece of the row -------------
     const int wave = threadIdx.x / kWave;

@@ -122,6 +122,6 @@ def test_run_on_a_dense_problem(gpu, oracle):
 def test_flag_combinations_are_rejected(gpu):
     torch, binding = gpu
     with binding.EF21(2, 10, 3, 0.1) as h:
-        for flags in (binding.CLASSIC_EF | binding.PLUS, binding.CLASSIC_EF | binding.ORDER_STEP_FIRST, 8):
+        for flags in (binding.CLASSIC_EF | binding.PLUS, binding.CLASSIC_EF | binding.ORDER_STEP_FIRST, 16):
             with pytest.raises(binding.EF21Error):
                 h.step(to_gpu(torch, np.zeros((2, 10))), flags)

@@ -169,6 +169,6 @@ def test_errors(gpu):
         with pytest.raises(binding.EF21Error):
             h.get_choices()                       # no EF21+ step yet
         with pytest.raises(binding.EF21Error):
-            h.step(to_gpu(torch, np.zeros((2, 10))), 8)       # unknown flag
+            h.step(to_gpu(torch, np.zeros((2, 10))), 16)      # unknown flag
         with pytest.raises(binding.EF21Error):
             h.step(None, binding.PLUS)            # no problem attached
