@@ -38,6 +38,9 @@ constexpr int kSamplePer = kSample / kBlk;
 constexpr int kPieceLen = 256, kPieces = kSample / kPieceLen;
 constexpr int kMaxSlots = 4096;              // slots (wavefront pieces) per row
 constexpr int kSelCap = 28672;               // candidate keys the select kernel holds in LDS
+// Rows expected to keep more candidates than this take the many-workgroup stages: their four launches cost about
+// 28 us whatever k is, the one-workgroup select grows with the candidates and passes that at about 12 000.
+constexpr int kSelectMax = 12288;
 constexpr int kCandThreads = 1024;           // count / emit workgroups (large k): one wavefront per slot
 constexpr int kCandWaves = kCandThreads / kWave;
 constexpr int kHistThreads = 512;            // candidate histogram workgroups (large k)
@@ -893,7 +896,7 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;
 
-    if (expected_candidates(p.d, p.k) <= (double)kSelCap) {
+    if (expected_candidates(p.d, p.k) <= (double)kSelectMax) {
         if (upd) st = launch_select<true, true>(p, w, stream);
         else if (diff) st = launch_select<true, false>(p, w, stream);
         else st = launch_select<false, false>(p, w, stream);
