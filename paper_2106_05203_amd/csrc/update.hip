@@ -53,39 +53,31 @@ constexpr int kAggSub = 2048;
 constexpr int kAggWaves = kThreads / kWave;
 
 __global__ __launch_bounds__(kThreads) void message_index_kernel(const int32_t *__restrict__ idx, int64_t k,
-                                                                 int64_t nblk, int32_t *__restrict__ start) {
+                                                                 int64_t nblk, int32_t sub,
+                                                                 int32_t *__restrict__ start) {
     const int64_t w = blockIdx.y;
     const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (p >= k) return;
     const int32_t *row = idx + w * k;
     int32_t *out = start + w * (nblk + 1);
-    const int64_t b_cur = row[p] / kAggSub;
-    const int64_t b_prev = p > 0 ? row[p - 1] / kAggSub : -1;
+    const int64_t b_cur = row[p] / sub;
+    const int64_t b_prev = p > 0 ? row[p - 1] / sub : -1;
     for (int64_t b = b_prev + 1; b <= b_cur; ++b) out[b] = (int32_t)p;     // first entry of sub-block b
     if (p == k - 1)
         for (int64_t b = b_cur + 1; b <= nblk; ++b) out[b] = (int32_t)k;
 }
 
-template <bool STEP, bool VEC4>
-__global__ __launch_bounds__(kThreads) void aggregate_kernel(const int32_t *__restrict__ idx,
-                                                             const float *__restrict__ val,
-                                                             const int32_t *__restrict__ start, int32_t n, int64_t k,
-                                                             int64_t d, int64_t nblk, float *__restrict__ g,
-                                                             float *__restrict__ x, float inv_n, float neg_gamma) {
-    __shared__ float lds[kAggWaves][kAggSub];
-    const int wave = threadIdx.x / kWave, lane = lane_id();
-    const int64_t b = (int64_t)blockIdx.x * kAggWaves + wave;
-    if (b >= nblk) return;
-    float *acc = lds[wave];
-    const int64_t c0 = b * kAggSub;
-    const int64_t c1 = c0 + kAggSub < d ? c0 + kAggSub : d;
-    for (int j = lane; j < kAggSub; j += kWave) acc[j] = 0.f;
+// The runs of workers [w_lo, w_hi) inside sub-block b (columns from c0) added to `acc`, worker after worker, by
+// the calling wavefront.
+__device__ __forceinline__ void add_runs(const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                         const int32_t *__restrict__ start, int64_t nblk, int64_t b, int64_t k,
+                                         int32_t w_lo, int32_t w_hi, float *acc, int64_t c0, int lane) {
     constexpr int kInFlight = 8;                     // workers whose runs are loaded together
-    for (int32_t w0 = 0; w0 < n; w0 += kWave) {
+    for (int32_t w0 = w_lo; w0 < w_hi; w0 += kWave) {
         const int32_t w = w0 + lane;
-        const int32_t s0 = w < n ? start[(int64_t)w * (nblk + 1) + b] : 0;
-        const int32_t s1 = w < n ? start[(int64_t)w * (nblk + 1) + b + 1] : 0;
-        const int32_t tile = n - w0 < kWave ? n - w0 : kWave;
+        const int32_t s0 = w < w_hi ? start[(int64_t)w * (nblk + 1) + b] : 0;
+        const int32_t s1 = w < w_hi ? start[(int64_t)w * (nblk + 1) + b + 1] : 0;
+        const int32_t tile = w_hi - w0 < kWave ? w_hi - w0 : kWave;
         for (int32_t t0 = 0; t0 < tile; t0 += kInFlight) {
             int32_t e[kInFlight], len[kInFlight];
             int64_t base[kInFlight];
@@ -108,6 +100,23 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const int32_t *__re
             }
         }
     }
+}
+
+template <bool STEP, bool VEC4>
+__global__ __launch_bounds__(kThreads) void aggregate_kernel(const int32_t *__restrict__ idx,
+                                                             const float *__restrict__ val,
+                                                             const int32_t *__restrict__ start, int32_t n, int64_t k,
+                                                             int64_t d, int64_t nblk, float *__restrict__ g,
+                                                             float *__restrict__ x, float inv_n, float neg_gamma) {
+    __shared__ float lds[kAggWaves][kAggSub];
+    const int wave = threadIdx.x / kWave, lane = lane_id();
+    const int64_t b = (int64_t)blockIdx.x * kAggWaves + wave;
+    if (b >= nblk) return;
+    float *acc = lds[wave];
+    const int64_t c0 = b * kAggSub;
+    const int64_t c1 = c0 + kAggSub < d ? c0 + kAggSub : d;
+    for (int j = lane; j < kAggSub; j += kWave) acc[j] = 0.f;
+    add_runs(idx, val, start, nblk, b, k, 0, n, acc, c0, lane);
     if (VEC4) {
         for (int64_t j = c0 + lane * 4; j < c1; j += kWave * 4) {
             const float4 a4 = *reinterpret_cast<const float4 *>(acc + (j - c0));
@@ -132,6 +141,41 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(const int32_t *__re
             g[j] = gj;
             if (STEP) x[j] = fmaf(neg_gamma, gj, x[j]);
         }
+    }
+}
+
+// Many workers (n >= kManyWorkers): the chain of n dependent additions per sub-block is what takes the time, so
+// a workgroup of four wavefronts shares ONE sub-block of kManySub columns: wavefront j adds the j-th quarter of
+// the workers (in worker order) into its own accumulator, and the four are then added in order,
+// ((a0 + a1) + a2) + a3: a fixed association, so g stays bitwise reproducible.
+constexpr int kManyWorkers = 16, kManySub = 256;
+static_assert(kManySub == kThreads, "one column per thread in the last step");
+
+template <bool STEP>
+__global__ __launch_bounds__(kThreads) void aggregate_many_kernel(const int32_t *__restrict__ idx,
+                                                                  const float *__restrict__ val,
+                                                                  const int32_t *__restrict__ start, int32_t n,
+                                                                  int64_t k, int64_t d, int64_t nblk,
+                                                                  float *__restrict__ g, float *__restrict__ x,
+                                                                  float inv_n, float neg_gamma) {
+    __shared__ float lds[kAggWaves][kManySub];
+    const int wave = threadIdx.x / kWave, lane = lane_id();
+    const int64_t b = blockIdx.x, c0 = b * kManySub;
+    const int64_t j = c0 + threadIdx.x;
+    const float gj = j < d ? g[j] : 0.f;                     // fetched while the runs are added
+    const float xj = STEP && j < d ? x[j] : 0.f;
+    float *acc = lds[wave];
+    for (int t = lane; t < kManySub; t += kWave) acc[t] = 0.f;
+    const int32_t quarter = (n + kAggWaves - 1) / kAggWaves;
+    const int32_t w_lo = wave * quarter < n ? wave * quarter : n;
+    const int32_t w_hi = w_lo + quarter < n ? w_lo + quarter : n;
+    add_runs(idx, val, start, nblk, b, k, w_lo, w_hi, acc, c0, lane);
+    __syncthreads();
+    if (j < d) {
+        const float a = ((lds[0][threadIdx.x] + lds[1][threadIdx.x]) + lds[2][threadIdx.x]) + lds[3][threadIdx.x];
+        const float gn = fmaf(a, inv_n, gj);
+        g[j] = gn;
+        if (STEP) x[j] = fmaf(neg_gamma, gn, xj);
     }
 }
 
@@ -254,8 +298,8 @@ hipError_t launch_model_step(float *x, const float *g, int64_t d, float gamma, h
     return hipGetLastError();
 }
 
-size_t aggregate_index_bytes(int32_t n, int64_t d) {
-    return sizeof(int32_t) * (size_t)n * ((size_t)((d + kAggSub - 1) / kAggSub) + 1);
+size_t aggregate_index_bytes(int32_t n, int64_t d) {      // for the shorter of the two sub-block lengths
+    return sizeof(int32_t) * (size_t)n * ((size_t)((d + kManySub - 1) / kManySub) + 1);
 }
 
 hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int64_t k, int64_t d, float *g, float *x,
@@ -270,10 +314,22 @@ hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int
                                d, g, x, inv_n, -gamma);
         return hipGetLastError();
     }
-    const int64_t nblk = (d + kAggSub - 1) / kAggSub;
     int32_t *start = (int32_t *)index;
+    if (n >= kManyWorkers) {
+        const int64_t nblk = (d + kManySub - 1) / kManySub;
+        hipLaunchKernelGGL(message_index_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads), (unsigned)n),
+                           dim3(kThreads), 0, stream, idx, k, nblk, kManySub, start);
+        if (x)
+            hipLaunchKernelGGL(aggregate_many_kernel<true>, dim3((unsigned)nblk), dim3(kThreads), 0, stream, idx, val,
+                               start, n, k, d, nblk, g, x, inv_n, -gamma);
+        else
+            hipLaunchKernelGGL(aggregate_many_kernel<false>, dim3((unsigned)nblk), dim3(kThreads), 0, stream, idx, val,
+                               start, n, k, d, nblk, g, x, inv_n, -gamma);
+        return hipGetLastError();
+    }
+    const int64_t nblk = (d + kAggSub - 1) / kAggSub;
     hipLaunchKernelGGL(message_index_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads), (unsigned)n),
-                       dim3(kThreads), 0, stream, idx, k, nblk, start);
+                       dim3(kThreads), 0, stream, idx, k, nblk, kAggSub, start);
     const dim3 grid((unsigned)((nblk + kAggWaves - 1) / kAggWaves)), block(kThreads);
     const bool vec4 = (d % 4 == 0) && (((uintptr_t)g | (uintptr_t)(x ? x : g)) % 16 == 0);
     if (x && vec4)
