@@ -86,6 +86,33 @@ def test_single_step_from_oracle_state(gpu, oracle, n, d, k, order):
             budget.reset()
 
 
+@pytest.mark.parametrize("n,d,k", [(16, 20_000, 600), (17, 20_000, 600), (33, 70_001, 1500), (67, 16_500, 300)])
+def test_step_with_many_workers_and_clustered_messages(gpu, oracle, n, d, k):
+    """Sixteen workers and more take the aggregation that splits the workers over four wavefronts; the large
+    differences of every worker sit in a few runs of adjacent coordinates (runs longer than a wavefront inside
+    one block of 256 columns, shared by several workers), the rest of the message is scattered."""
+    torch, binding = gpu
+    print(f"many workers n={n} d={d} k={k}", flush=True)
+    rng = np.random.default_rng(n + d + k)
+    gamma = 0.25
+    x0 = rng.standard_normal(d).astype(np.float32)
+    g_i0 = (0.01 * rng.standard_normal((n, d))).astype(np.float32)
+    g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+    grads = (g_i0 + 0.01 * rng.standard_normal((n, d))).astype(np.float32)
+    for i in range(n):
+        for start in (1000 + 40 * (i % 3), d - 300):              # overlapping runs of 200 and 150 coordinates
+            width = 200 if start < d // 2 else 150
+            grads[i, start:start + width] += (1.0 + rng.random(width)).astype(np.float32) * (-1.0) ** i
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    budget = RoundingBudget(n, d, gamma)
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+        oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma)
+        h.step(to_gpu(torch, grads))
+        torch.cuda.synchronize()
+        compare_state(torch, h, st, budget)
+
+
 @pytest.mark.parametrize("k", [5000, 60000])
 def test_step_when_the_sample_misleads(gpu, oracle, k):
     """Long rows whose large differences sit exactly on the 32 sampled pieces: the candidate threshold
