@@ -89,6 +89,37 @@ __device__ void select_bin(RowShared &s, int nbins, uint32_t need) {
     __syncthreads();
 }
 
+// The entries gathered in s.cand_key / s.cand_idx (s.ncand of them, at most kRankMax, in any order; cand_rank
+// zeroed) are ranked against one another in the order "larger key first, lower position first among equal
+// keys": c * c comparisons over all threads, thread t comparing entry t mod c with one slice of the others.  The
+// entry that need - 1 others precede is the last one kept: its key goes to s.bin (the threshold key T) and the
+// number of entries with that key up to and including it to s.need (the tie quota q).  1 <= need <= s.ncand.
+__device__ void rank_gathered(RowShared &s, uint32_t need) {
+    const uint32_t c = s.ncand;
+    const uint32_t parts = (uint32_t)kRowThreads / c, per = (c + parts - 1u) / parts;
+    if (threadIdx.x < c * parts) {
+        const uint32_t i = threadIdx.x % c, j0 = (threadIdx.x / c) * per;
+        const uint32_t j1 = j0 + per < c ? j0 + per : c;
+        const uint32_t my_key = s.cand_key[i], my_idx = s.cand_idx[i];
+        uint32_t counts = 0u;
+#pragma unroll 8
+        for (uint32_t j = j0; j < j1; ++j) {
+            const uint32_t kj = s.cand_key[j], ij = s.cand_idx[j];
+            counts += (kj > my_key ? 1u : 0u) + ((kj == my_key && ij < my_idx) ? 0x10000u : 0u);
+        }
+        if (counts) atomicAdd(&s.cand_rank[i], counts);
+    }
+    __syncthreads();
+    if (threadIdx.x < c) {
+        const uint32_t r = s.cand_rank[threadIdx.x], larger = r & 0xffffu, equal_before = r >> 16;
+        if (larger + equal_before == need - 1u) {          // exactly one thread
+            s.bin = s.cand_key[threadIdx.x];
+            s.need = equal_before + 1u;
+        }
+    }
+    __syncthreads();
+}
+
 // Whole Top-k of one row by the calling workgroup (all kRowThreads threads must call).
 // value(e) yields entry e of the row (the same bits every time it is asked); with UPDATE the emission
 // also applies line 6 of Algorithm 2, g_i[e] = base(e) + value(e), base(e) being the subtracted g_i[e].
@@ -124,30 +155,7 @@ __device__ void row_topk_on(RowShared &s, const TopkArgs &p, int64_t row, ValueF
             }
         }
         __syncthreads();
-        // c * c comparisons over all threads: thread t compares entry t mod c with one slice of the others
-        const uint32_t c = s.ncand;
-        const uint32_t parts = (uint32_t)kRowThreads / c, per = (c + parts - 1u) / parts;
-        if (threadIdx.x < c * parts) {
-            const uint32_t i = threadIdx.x % c, j0 = (threadIdx.x / c) * per;
-            const uint32_t j1 = j0 + per < c ? j0 + per : c;
-            const uint32_t my_key = s.cand_key[i], my_idx = s.cand_idx[i];
-            uint32_t counts = 0u;
-#pragma unroll 8
-            for (uint32_t j = j0; j < j1; ++j) {
-                const uint32_t kj = s.cand_key[j], ij = s.cand_idx[j];
-                counts += (kj > my_key ? 1u : 0u) + ((kj == my_key && ij < my_idx) ? 0x10000u : 0u);
-            }
-            if (counts) atomicAdd(&s.cand_rank[i], counts);
-        }
-        __syncthreads();
-        if (threadIdx.x < c) {
-            const uint32_t r = s.cand_rank[threadIdx.x], larger = r & 0xffffu, equal_before = r >> 16;
-            if (larger + equal_before == need - 1u) {          // exactly one thread
-                s.bin = s.cand_key[threadIdx.x];
-                s.need = equal_before + 1u;
-            }
-        }
-        __syncthreads();
+        rank_gathered(s, need);
         T = s.bin;
         q = s.need;
     } else {

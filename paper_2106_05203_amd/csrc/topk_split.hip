@@ -452,7 +452,9 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
     }
     __syncthreads();
 
-    // radix select over the keys in LDS
+    // radix select over the keys in LDS: the top digit by histogram, then either the selected bin's entries ranked
+    // against one another (at most kRankMax of them; their place in the candidate list is their order among equal
+    // keys) or two more histogram passes
     uint32_t prefix = 0, need = (uint32_t)p.k;
     {
         const int shifts[3] = {kBits2 + kBits3, kBits3, 0};
@@ -469,7 +471,25 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
             select_bin(s, bins[pass], need);
             prefix = (prefix << (pass == 0 ? 0 : (pass == 1 ? kBits2 : kBits3))) | s.bin;
             need = s.need;
+            const uint32_t in_bin = s.hist[s.bin];
+            if (tid == 0) s.ncand = 0u;
+            if (tid < kRankMax) s.cand_rank[tid] = 0u;
             __syncthreads();
+            if (pass == 0 && in_bin <= (uint32_t)kRankMax) {
+                for (uint32_t j = tid; j < M; j += kBlk) {
+                    const uint32_t key = keys[j];
+                    if ((key >> (kBits2 + kBits3)) == prefix) {
+                        const uint32_t at = atomicAdd(&s.ncand, 1u);
+                        s.cand_key[at] = key;
+                        s.cand_idx[at] = j;
+                    }
+                }
+                __syncthreads();
+                rank_gathered(s, need);
+                prefix = s.bin;
+                need = s.need;
+                break;
+            }
         }
     }
     const uint32_t T = prefix, q = need;
