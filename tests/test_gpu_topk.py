@@ -65,6 +65,24 @@ def test_random_small_rows(gpu, oracle, d):
         check(gpu, oracle, V, k)
 
 
+@pytest.mark.parametrize("d", [200, 256, 257, 5000, 9000, 300_000])
+@pytest.mark.parametrize("crowd", [3, 255, 256, 257, 600])
+def test_threshold_inside_a_bin_of_near_equal_magnitudes(gpu, oracle, d, crowd):
+    """`crowd` entries share the twelve leading key bits (values in [1, 1.0625), many of them exactly equal up
+    to sign), a few are larger, the rest tiny; k runs through the crowd, so the threshold key and the tie quota
+    are decided among them: by ranking them directly up to 256, by further histogram passes beyond."""
+    crowd = min(crowd, d - 2)
+    rng = np.random.default_rng(d * 1000 + crowd)
+    V = (1e-4 * rng.standard_normal((4, d))).astype(np.float32)
+    for i in range(4):
+        pos = rng.choice(d, size=crowd + 2, replace=False)
+        vals = 1.0 + rng.integers(0, 8, size=crowd) / 128.0            # 8 distinct magnitudes: heavy ties
+        V[i, pos[:crowd]] = (vals * rng.choice([-1.0, 1.0], size=crowd)).astype(np.float32)
+        V[i, pos[crowd:]] = [3.0, -2.5]
+    for k in sorted({1, 2, 3, 2 + crowd // 3, 2 + crowd // 2, 1 + crowd, 2 + crowd, min(d, 3 + crowd)}):
+        check(gpu, oracle, V, k)
+
+
 @pytest.mark.parametrize("d,k", [(70001, 700), (262144, 5), (300007, 3000), (1_000_003, 999)])
 def test_long_rows_ragged(gpu, oracle, d, k):
     V = workloads.topk_rows(3, d, seed=d % 1000)
