@@ -256,6 +256,15 @@ def bench_grads(torch, binding, workloads, steps: int, warmup: int):
     wall_e, _ = timed_loop(torch, lambda i: h.step(pool[i % 4], binding.CLASSIC_EF), steps, warmup)
     out["classic_ef"] = {"value": round(1e3 / wall_e, 2), "unit": "EF iterations/s (gradients supplied)",
                          "ms_per_step": round(wall_e, 5)}
+    # Algorithm 3 on the same gradients: two Top-k selections, the distortions and the mean of the rows, each a
+    # pass of its own over the long rows
+    h.set_state(torch.zeros(d, device="cuda"), torch.zeros((n, d), device="cuda"), None)
+    wall_p, _ = timed_loop(torch, lambda i: h.step(pool[i % 4], binding.PLUS), max(10, steps // 2), max(3, warmup // 2))
+    pk, pl = kernel_times(torch, h, lambda i: h.step(pool[i % 4], binding.PLUS), max(10, steps // 2))
+    out["ef21_plus"] = {"value": round(1e3 / wall_p, 2), "unit": "EF21+ iterations/s (gradients supplied)",
+                        "ms_per_step": round(wall_p, 5),
+                        "kernel_ms_per_step": {k_: round(v * pl[k_], 5) for k_, v in pk.items()},
+                        "plain_compressor_chosen_last_step": int(h.get_choices()[0].sum().item())}
     dom = "topk_collect" if "topk_collect" in per_kernel else "topk_row"
     out["roofline"] = roofline(8.0 * n * d, per_kernel[dom], f"{dom} (reads grad and g_i once)",
                                MEASURED_TRAFFIC_BYTES.get(f"C4/{dom}"))

@@ -536,7 +536,7 @@ static int ensure_plus_buffers(ef21_ctx *c) {
     EF21_HIP(hipStreamSynchronize(c->stream));
     if (hipMalloc((void **)&c->plus_idx, sizeof(int32_t) * 2 * nk) != hipSuccess ||
         hipMalloc((void **)&c->plus_val, sizeof(float) * 2 * nk) != hipSuccess ||
-        hipMalloc(&c->plus_scratch, ef21::plus_scratch_bytes(c->n, c->d)) != hipSuccess ||
+        hipMalloc(&c->plus_scratch, ef21::plus_scratch_bytes(c->n, c->d, c->k)) != hipSuccess ||
         hipMalloc((void **)&c->plus_branch, sizeof(int32_t) * (size_t)c->n) != hipSuccess ||
         hipMalloc((void **)&c->plus_bm, sizeof(double) * 2 * (size_t)c->n) != hipSuccess) {
         (void)hipGetLastError();

@@ -136,8 +136,8 @@ hipError_t launch_small_step(const float *A, const float *y, float *x, float *g,
 // Algorithm 3 (EF21+), lines 7 and 8, for all workers: from the gradients s [n][d], the estimators g_i [n][d]
 // (updated in place) and the two Top-k results (idx_b, val_b) = C(s), (idx_m, val_m) = C(s - g_i), all [n][k]:
 // BM[i] = (B_i, M_i), branch[i] = 1 where the plain compressor wins (M_i > B_i), (msg_idx, msg_val) = the chosen
-// pairs, and g_i <- b or m accordingly.  scratch: plus_scratch_bytes(n, d) bytes.
-size_t plus_scratch_bytes(int32_t n, int64_t d);
+// pairs, and g_i <- b or m accordingly.  scratch: plus_scratch_bytes(n, d, k) bytes.
+size_t plus_scratch_bytes(int32_t n, int64_t d, int64_t k);
 hipError_t launch_plus_choose(const float *s, float *g_i, int32_t n, int64_t d, int64_t k, const int32_t *idx_b,
                               const float *val_b, const int32_t *idx_m, const float *val_m, void *scratch,
                               int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream);

@@ -42,6 +42,35 @@ __global__ __launch_bounds__(kThreads) void mean_rows_kernel(const float *__rest
     }
 }
 
+// Same sums (per coordinate, the workers in order, in fp64), four coordinates per thread and eight workers'
+// loads in flight; needs d % 4 == 0 and 16-byte aligned pointers.
+__global__ __launch_bounds__(kThreads) void mean_rows_vec4_kernel(const float *__restrict__ g_i,
+                                                                  float *__restrict__ g, int32_t n, int64_t d) {
+    const int64_t stride = (int64_t)gridDim.x * kThreads * 4;
+    constexpr int kInFlight = 8;
+    for (int64_t j = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4; j < d; j += stride) {
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        for (int32_t i0 = 0; i0 < n; i0 += kInFlight) {
+            float4 v[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u)        // a worker past the end re-reads the last one, unused
+                v[u] = stream_load4(g_i + (int64_t)(i0 + u < n ? i0 + u : n - 1) * d + j);
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                if (i0 + u < n) {
+                    s0 += (double)v[u].x;
+                    s1 += (double)v[u].y;
+                    s2 += (double)v[u].z;
+                    s3 += (double)v[u].w;
+                }
+            }
+        }
+        const double nn = (double)n;
+        *reinterpret_cast<float4 *>(g + j) =
+            make_float4((float)(s0 / nn), (float)(s1 / nn), (float)(s2 / nn), (float)(s3 / nn));
+    }
+}
+
 // ---- Algorithm 2, line 8 (and line 3) without atomics ------------------------------------------
 // The coordinates are cut into sub-blocks of kAggSub.  A worker's message is sorted by position, so
 // its entries inside a sub-block are one contiguous run [start[w][b], start[w][b+1]); the runs are
@@ -360,7 +389,10 @@ hipError_t launch_hbm_copy(void *dst, const void *src, int64_t n16, hipStream_t 
 }
 
 hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hipStream_t stream) {
-    hipLaunchKernelGGL(mean_rows_kernel, dim3(grid_for(d, 8192)), dim3(kThreads), 0, stream, g_i, g, n, d);
+    if ((d % 4 == 0) && (((uintptr_t)g_i | (uintptr_t)g) % 16 == 0))
+        hipLaunchKernelGGL(mean_rows_vec4_kernel, dim3(grid_for(d / 4, 8192)), dim3(kThreads), 0, stream, g_i, g, n, d);
+    else
+        hipLaunchKernelGGL(mean_rows_kernel, dim3(grid_for(d, 8192)), dim3(kThreads), 0, stream, g_i, g, n, d);
     return hipGetLastError();
 }
 
