@@ -219,7 +219,10 @@ int enqueue_local_grad(ef21_ctx *c, const float *x, float *out, ef21::GradParts 
 
 int enqueue_topk(const ef21::TopkArgs &p, void *workspace, hipStream_t stream, const ef21::Marker &mk) {
     hipError_t st;
-    if (use_split(p.d) && workspace) {
+    if (use_split(p.d) && p.d <= ef21::kRow16Max && p.k <= ef21::kRow16MaxK && !p.b && !p.parts.part) {
+        st = ef21::launch_topk_row16(p, stream);
+        mk(ef21::K_TOPK_ROW);
+    } else if (use_split(p.d) && workspace) {
         st = ef21::launch_topk_split(p, workspace, stream, mk);
     } else {
         st = ef21::launch_topk_row(p, stream);

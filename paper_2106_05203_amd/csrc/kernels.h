@@ -65,6 +65,12 @@ struct TopkArgs {
 // quickly (and as the reference device path for long rows).
 hipError_t launch_topk_row(const TopkArgs &p, hipStream_t stream);
 
+// One workgroup per row that reads the row once and keeps 16 bits of every key in LDS: rows of 2048 to kRow16Max
+// entries given as they are (p.b == nullptr), k <= kRow16MaxK (meant for rows too long for launch_topk_row's LDS
+// copy).  No workspace.
+constexpr int64_t kRow16Max = 61440, kRow16MaxK = 1024;
+hipError_t launch_topk_row16(const TopkArgs &p, hipStream_t stream);
+
 // Many workgroups per row for long rows.  Workspace layout and size: topk_split_workspace_bytes.
 size_t topk_split_workspace_bytes(int32_t n, int64_t d, int64_t k);
 hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t stream, const Marker &mk = Marker());

@@ -83,6 +83,28 @@ def test_threshold_inside_a_bin_of_near_equal_magnitudes(gpu, oracle, d, crowd):
         check(gpu, oracle, V, k)
 
 
+@pytest.mark.parametrize("d", [16384, 20001, 50000, 61440, 61441])
+@pytest.mark.parametrize("k", [1, 37, 1000, 1024, 1025])
+def test_rows_held_in_lds_as_key_prefixes(gpu, oracle, d, k):
+    """Rows of 16 384 to 61 440 entries with k <= 1024 are selected by one workgroup that keeps 16 bits of every key
+    in LDS (the sizes around those limits take the other kernels).  Rows: Gaussian; heavy exact ties (the list
+    of entries above the bound overflows); a crowded bin of near-equal magnitudes with ties (narrowed by four
+    bits, or given up); fewer non-zeros than k (the threshold is zero); infinities and a row of one value."""
+    rng = np.random.default_rng(d + k)
+    V = rng.standard_normal((7, d)).astype(np.float32)
+    V[1] = np.round(V[1] * 2) / 2
+    V[2] = (1e-3 * rng.standard_normal(d)).astype(np.float32)
+    crowd = rng.choice(d, size=3000, replace=False)
+    V[2, crowd] = ((1.0 + rng.integers(0, 2000, size=3000) / 32768.0) * rng.choice([-1.0, 1.0], size=3000)).astype(np.float32)
+    V[3] = 0.0
+    few = rng.choice(d, size=min(k, 700) // 2 + 1, replace=False)
+    V[3, few] = rng.standard_normal(few.size).astype(np.float32)
+    V[4, rng.choice(d, size=5, replace=False)] = [np.inf, -np.inf, 3e38, -3e38, np.inf]
+    V[5] = -2.5
+    V[6] = (rng.standard_t(3, size=d) * 1e-3).astype(np.float32)
+    check(gpu, oracle, V, k)
+
+
 @pytest.mark.parametrize("d,k", [(70001, 700), (262144, 5), (300007, 3000), (1_000_003, 999)])
 def test_long_rows_ragged(gpu, oracle, d, k):
     V = workloads.topk_rows(3, d, seed=d % 1000)
