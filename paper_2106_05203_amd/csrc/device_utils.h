@@ -45,6 +45,18 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Place of the calling lane's item in a list whose length is `*counter` (LDS): the lanes of a wavefront that
+// have an item (`has`) take consecutive places with ONE atomic for the wavefront.  Every lane of the wavefront
+// must call; the result means something only where `has`.
+__device__ __forceinline__ uint32_t wave_append(bool has, uint32_t *counter) {
+    const uint64_t m = __ballot(has);
+    if (m == 0) return 0u;
+    const int first = __ffsll((long long)m) - 1;
+    uint32_t base = 0u;
+    if (lane_id() == first) base = atomicAdd(counter, popc64(m));
+    return __shfl(base, first, kWave) + lanes_below(m);
+}
+
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
     const int lane = lane_id();
 #pragma unroll

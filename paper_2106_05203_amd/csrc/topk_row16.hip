@@ -63,18 +63,6 @@ __device__ __forceinline__ uint32_t max8(const uint4 &w) {
     return m.x > m.y ? (uint32_t)m.x : (uint32_t)m.y;
 }
 
-// Place of the calling lane's item in a list whose length is `*counter` (LDS): the lanes of a wavefront that
-// have an item (`has`) take consecutive places with ONE atomic for the wavefront.  Every lane of the wavefront
-// must call; the result means something only where `has`.
-__device__ __forceinline__ uint32_t wave_append(bool has, uint32_t *counter) {
-    const uint64_t m = __ballot(has);
-    if (m == 0) return 0u;
-    const int first = __ffsll((long long)m) - 1;
-    uint32_t base = 0u;
-    if (lane_id() == first) base = atomicAdd(counter, popc64(m));
-    return __shfl(base, first, kWave) + lanes_below(m);
-}
-
 constexpr int kChunks = (int)((kRow16Max / 8 + kRowThreads - 1) / kRowThreads);   // 16-byte LDS words per thread: 8
 constexpr int kListMax = 4096;                 // gathered entries (step 3) ...
 constexpr int kWordMax = 4096;                 // ... and 16-byte words that hold one
