@@ -877,6 +877,120 @@ hipError_t launch_select(const TopkArgs &p, const Ws &w, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- k = 1: the entry of largest magnitude
+// Top-1 (the compressor of the paper's first experiment) needs no threshold and no candidates: every thread
+// keeps the best entry of its share as one 64-bit word, key << 32 | ~position (a larger word = a larger
+// magnitude, or the same magnitude at a lower position), the words are reduced over the wavefront and the
+// workgroup, and one 64-bit atomic maximum per workgroup lands in the row's slot (the first two words of the
+// row's histogram in the workspace, which are zero between calls).  A second, tiny kernel turns the slot into
+// the message, applies line 6 and clears the slot.
+constexpr int kArgThreads = 256, kArgWaves = kArgThreads / kWave;
+
+template <int VEC, bool DIFF>
+__global__ __launch_bounds__(kArgThreads) void argmax_stream_kernel(TopkArgs p, Ws w, int64_t piece) {
+    __shared__ unsigned long long best_of_wave[kArgWaves];
+    const int64_t row = blockIdx.y, d = p.d;
+    const float *a = p.a + row * d;
+    const float *b = DIFF ? p.b + row * d : nullptr;
+    const int64_t lo = (int64_t)blockIdx.x * piece, hi = lo + piece < d ? lo + piece : d;
+    unsigned long long best = 0ull;
+    auto see = [&](float v, int64_t e) {
+        const unsigned long long word = ((unsigned long long)mag_key(v) << 32) | (0xffffffffu - (uint32_t)e);
+        best = word > best ? word : best;
+    };
+    if constexpr (VEC == 4) {
+        constexpr int kUnroll = DIFF ? 4 : 8;
+        constexpr int64_t kStep = (int64_t)kArgThreads * 4;
+        int64_t e = lo + (int64_t)threadIdx.x * 4;               // piece % 4 == 0: whole float4s inside [lo, hi)
+        for (; e + (kUnroll - 1) * kStep + 4 <= hi; e += kUnroll * kStep) {
+            float4 va[kUnroll], vb[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                va[u] = stream_load4(a + e + u * kStep);
+                if constexpr (DIFF) vb[u] = stream_load4(b + e + u * kStep);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if constexpr (DIFF) {
+                    va[u].x -= vb[u].x;
+                    va[u].y -= vb[u].y;
+                    va[u].z -= vb[u].z;
+                    va[u].w -= vb[u].w;
+                }
+                const int64_t e0 = e + u * kStep;
+                see(va[u].x, e0);
+                see(va[u].y, e0 + 1);
+                see(va[u].z, e0 + 2);
+                see(va[u].w, e0 + 3);
+            }
+        }
+        for (; e + 4 <= hi; e += kStep) {
+            float4 va = stream_load4(a + e);
+            if constexpr (DIFF) {
+                const float4 vb = stream_load4(b + e);
+                va.x -= vb.x;
+                va.y -= vb.y;
+                va.z -= vb.z;
+                va.w -= vb.w;
+            }
+            see(va.x, e);
+            see(va.y, e + 1);
+            see(va.z, e + 2);
+            see(va.w, e + 3);
+        }
+    } else {
+        for (int64_t e = lo + threadIdx.x; e < hi; e += kArgThreads) see(load_v<DIFF>(a, b, e), e);
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const unsigned long long other = __shfl_xor(best, o, kWave);
+        best = other > best ? other : best;
+    }
+    if (lane_id() == 0) best_of_wave[threadIdx.x / kWave] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int v = 1; v < kArgWaves; ++v) best = best_of_wave[v] > best ? best_of_wave[v] : best;
+        if (lo < hi) atomicMax(reinterpret_cast<unsigned long long *>(w.hist_a + row * kBinsA), best);
+    }
+}
+
+template <bool DIFF, bool UPDATE>
+__global__ __launch_bounds__(kArgThreads) void argmax_finish_kernel(TopkArgs p, Ws w) {
+    const int64_t row = (int64_t)blockIdx.x * kArgThreads + threadIdx.x;
+    if (row >= p.n) return;
+    unsigned long long *slot = reinterpret_cast<unsigned long long *>(w.hist_a + row * kBinsA);
+    const int64_t e = (int64_t)(0xffffffffu - (uint32_t)(*slot & 0xffffffffull));
+    *slot = 0ull;
+    const float bv = DIFF ? p.b[row * p.d + e] : 0.f;
+    const float v = DIFF ? p.a[row * p.d + e] - bv : p.a[row * p.d + e];
+    p.out_idx[row] = (int32_t)e;                                // k == 1: one pair per row
+    p.out_val[row] = v;
+    if (UPDATE) p.g_i[row * p.d + e] = bv + v;                  // Algorithm 2, line 6
+}
+
+hipError_t launch_argmax(const TopkArgs &p, const Ws &w, hipStream_t stream, const Marker &mk) {
+    const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
+    const bool vec4 = (p.d % 4 == 0) && ((uintptr_t)p.a % 16 == 0) && (!diff || (uintptr_t)p.b % 16 == 0);
+    int64_t G = 1024 / p.n;                                     // about four workgroups of 256 per compute unit
+    if (G < 1) G = 1;
+    int64_t piece = (p.d + G - 1) / G;
+    piece = (piece + 3) & ~(int64_t)3;
+    if (piece < 4096) piece = 4096;
+    G = (p.d + piece - 1) / piece;
+    const dim3 grid((unsigned)G, (unsigned)p.n), block(kArgThreads);
+    if (vec4 && diff) hipLaunchKernelGGL((argmax_stream_kernel<4, true>), grid, block, 0, stream, p, w, piece);
+    else if (vec4) hipLaunchKernelGGL((argmax_stream_kernel<4, false>), grid, block, 0, stream, p, w, piece);
+    else if (diff) hipLaunchKernelGGL((argmax_stream_kernel<1, true>), grid, block, 0, stream, p, w, piece);
+    else hipLaunchKernelGGL((argmax_stream_kernel<1, false>), grid, block, 0, stream, p, w, piece);
+    mk(K_TOPK_COLLECT);
+    const dim3 fgrid((unsigned)((p.n + kArgThreads - 1) / kArgThreads));
+    if (upd) hipLaunchKernelGGL((argmax_finish_kernel<true, true>), fgrid, block, 0, stream, p, w);
+    else if (diff) hipLaunchKernelGGL((argmax_finish_kernel<true, false>), fgrid, block, 0, stream, p, w);
+    else hipLaunchKernelGGL((argmax_finish_kernel<false, false>), fgrid, block, 0, stream, p, w);
+    mk(K_TOPK_SELECT);
+    return hipGetLastError();
+}
+
 // candidates the collect pass is expected to keep per row (see sample_rank)
 double expected_candidates(int64_t d, int64_t k) {
     const double ns = d < kSample ? (double)d : (double)kSample;
@@ -905,6 +1019,7 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
     layout(p.n, p.d, (char *)workspace, &w);
     const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
     if (upd && !diff) return hipErrorInvalidValue;
+    if (p.k == 1) return launch_argmax(p, w, stream, mk);
     const bool vec4 = (p.d % 4 == 0) && ((uintptr_t)p.a % 16 == 0) && (!diff || (uintptr_t)p.b % 16 == 0);
     if (vec4 && upd) launch_collect<4, true, true>(p, w, stream);
     else if (vec4 && diff) launch_collect<4, true, false>(p, w, stream);

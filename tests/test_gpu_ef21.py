@@ -59,7 +59,7 @@ def compare_state(torch, h, st, budget, msgs=True, rows=None):
 
 
 @pytest.mark.parametrize("n,d,k", [(1, 1, 1), (4, 100, 1), (3, 1000, 1000), (7, 4099, 41), (20, 2000, 20),
-                                   (5, 70001, 700), (3, 300_000, 3000)])
+                                   (5, 70001, 700), (3, 300_000, 3000), (5, 70001, 1), (3, 300_000, 1), (6, 20_000, 1)])
 @pytest.mark.parametrize("order", ["grad_first", "step_first"])
 def test_single_step_from_oracle_state(gpu, oracle, n, d, k, order):
     torch, binding = gpu

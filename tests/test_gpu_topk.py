@@ -105,7 +105,8 @@ def test_rows_held_in_lds_as_key_prefixes(gpu, oracle, d, k):
     check(gpu, oracle, V, k)
 
 
-@pytest.mark.parametrize("d,k", [(70001, 700), (262144, 5), (300007, 3000), (1_000_003, 999)])
+@pytest.mark.parametrize("d,k", [(70001, 700), (262144, 5), (300007, 3000), (1_000_003, 999), (70001, 1), (1_000_003, 1),
+                                 (262144, 1)])
 def test_long_rows_ragged(gpu, oracle, d, k):
     V = workloads.topk_rows(3, d, seed=d % 1000)
     check(gpu, oracle, V, k)
