@@ -452,11 +452,62 @@ __global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
     }
     __syncthreads();
 
-    // radix select over the keys in LDS: the top digit by histogram, then either the selected bin's entries ranked
-    // against one another (at most kRankMax of them; their place in the candidate list is their order among equal
-    // keys) or two more histogram passes
+    // Radix select over the keys in LDS.  All candidates have key >= key_lo and the threshold lies a little above
+    // it, so the first digit is taken from key - key_lo (12 bits from bit 11, larger differences in the last bin):
+    // the candidates spread over hundreds of bins, where the leading bits of the keys themselves would put them
+    // all into a handful (LDS atomics on the same address are served one after the other).  Then either the
+    // bin's entries ranked against one another (at most kRankMax of them; their place in the candidate list is
+    // their order among equal keys) or the low 11 bits by a second histogram.  A threshold in the last bin
+    // (k tiny against the candidates) is found on the keys' own digits instead.
     uint32_t prefix = 0, need = (uint32_t)p.k;
+    bool found = false;
     {
+        const uint32_t key_lo = w.info[row].key_lo;
+        auto digit_a = [&](uint32_t key) {
+            const uint32_t rel = (key - key_lo) >> kBitsB;
+            return rel < (uint32_t)kBinsA - 1u ? rel : (uint32_t)kBinsA - 1u;
+        };
+        static_assert(kBinsA == kBins1, "the first relative digit uses the 12-bit histogram");
+        for (int i = tid; i < kBinsA; i += kBlk) s.hist[i] = 0u;
+        __syncthreads();
+        for (uint32_t j = tid; j < M; j += kBlk) atomicAdd(&s.hist[digit_a(keys[j])], 1u);
+        __syncthreads();
+        select_bin(s, kBinsA, need);
+        const uint32_t bin_a = s.bin, need_a = s.need, in_bin = s.hist[bin_a];
+        if (tid == 0) s.ncand = 0u;
+        if (tid < kRankMax) s.cand_rank[tid] = 0u;
+        __syncthreads();
+        if (bin_a != (uint32_t)kBinsA - 1u) {
+            found = true;
+            if (in_bin <= (uint32_t)kRankMax) {
+                for (uint32_t j = tid; j < M; j += kBlk) {
+                    const uint32_t key = keys[j];
+                    if (digit_a(key) == bin_a) {
+                        const uint32_t at = atomicAdd(&s.ncand, 1u);
+                        s.cand_key[at] = key;
+                        s.cand_idx[at] = j;
+                    }
+                }
+                __syncthreads();
+                rank_gathered(s, need_a);
+                prefix = s.bin;
+                need = s.need;
+            } else {
+                for (int i = tid; i < kBinsB; i += kBlk) s.hist[i] = 0u;
+                __syncthreads();
+                for (uint32_t j = tid; j < M; j += kBlk) {
+                    const uint32_t key = keys[j];
+                    if (digit_a(key) == bin_a) atomicAdd(&s.hist[(key - key_lo) & ((uint32_t)kBinsB - 1u)], 1u);
+                }
+                __syncthreads();
+                select_bin(s, kBinsB, need_a);
+                prefix = key_lo + ((bin_a << kBitsB) | s.bin);
+                need = s.need;
+            }
+            __syncthreads();
+        }
+    }
+    if (!found) {
         const int shifts[3] = {kBits2 + kBits3, kBits3, 0};
         const int pshifts[3] = {31, kBits2 + kBits3, kBits3};
         const int bins[3] = {kBins1, kBins2, kBins3};
