@@ -86,6 +86,34 @@ def test_single_step_from_oracle_state(gpu, oracle, n, d, k, order):
             budget.reset()
 
 
+def test_single_steps_on_random_shapes(gpu, oracle):
+    """Thirty seeded draws of (n, d, k) across the kernels' ranges, one step each from a random state with
+    supplied gradients: messages and g_i bit for bit, g and x within the rounding budget."""
+    torch, binding = gpu
+    rng = np.random.default_rng(5203)
+    for case in range(30):
+        d = int(np.exp(rng.uniform(0.0, np.log(200_000))))
+        n = int(rng.integers(1, 24))
+        k = int(min(d, max(1, [1, 2, rng.integers(1, 64), d // 100 + 1, d // 3 + 1, d][rng.integers(0, 6)])))
+        if n * d > 3_000_000:
+            n = max(1, 3_000_000 // d)
+        gamma = 0.25
+        print(f"random step case {case}: n={n} d={d} k={k}", flush=True)
+        x0 = rng.standard_normal(d).astype(np.float32)
+        g_i0 = rng.standard_normal((n, d)).astype(np.float32)
+        g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+        grads = (g_i0 + rng.choice([0.0, 0.3], size=(n, d)) * rng.standard_normal((n, d))).astype(np.float32)
+        st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+        budget = RoundingBudget(n, d, gamma)
+        order = "step_first" if case % 3 == 0 else "grad_first"
+        with binding.EF21(n, d, k, gamma) as h:
+            h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+            oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma, order)
+            h.step(to_gpu(torch, grads), binding.ORDER_STEP_FIRST if order == "step_first" else binding.ORDER_GRAD_FIRST)
+            torch.cuda.synchronize()
+            compare_state(torch, h, st, budget)
+
+
 @pytest.mark.parametrize("n,d,k", [(16, 20_000, 600), (17, 20_000, 600), (33, 70_001, 1500), (67, 16_500, 300)])
 def test_step_with_many_workers_and_clustered_messages(gpu, oracle, n, d, k):
     """Sixteen workers and more take the aggregation that splits the workers over four wavefronts; the large

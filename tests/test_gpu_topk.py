@@ -173,6 +173,29 @@ def test_config1_full_size(gpu, oracle, k):
     check(gpu, oracle, W, k)
 
 
+def test_random_shapes(gpu, oracle):
+    """Sixty seeded draws of (n, d, k, kind of row) across all the kernels' ranges of d and k."""
+    rng = np.random.default_rng(2106)
+    for case in range(60):
+        d = int(np.exp(rng.uniform(0.0, np.log(400_000))))
+        n = int(rng.integers(1, 5))
+        k = int(min(d, max(1, [1, 2, rng.integers(1, 64), d // 100 + 1, d // 3 + 1, d][rng.integers(0, 6)])))
+        kind = int(rng.integers(0, 5))
+        if kind == 0:
+            V = rng.standard_normal((n, d))
+        elif kind == 1:
+            V = np.round(rng.standard_normal((n, d)) * 3) / 3          # heavy ties
+        elif kind == 2:
+            V = rng.standard_t(2, size=(n, d)) * 1e-4                  # heavy tails
+        elif kind == 3:
+            V = np.zeros((n, d))
+            nz = rng.integers(0, d, size=max(1, d // 50))
+            V[:, nz] = rng.standard_normal((n, nz.size))               # mostly zeros
+        else:
+            V = np.exp(rng.uniform(-80, 80, size=(n, d))) * rng.choice([-1.0, 1.0], size=(n, d))   # all exponents
+        check(gpu, oracle, V.astype(np.float32), k)
+
+
 def test_deterministic(gpu):
     torch, binding = gpu
     V = torch.from_numpy(workloads.topk_rows(6, 300_000, seed=9)).cuda()
