@@ -138,6 +138,19 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
     return out, (W, h)
 
 
+def device_info(torch) -> dict:
+    """What the runtime reports about the GPU the numbers were taken on."""
+    pr = torch.cuda.get_device_properties(0)
+    out = {"name": pr.name, "compute_units": pr.multi_processor_count,
+           "memory_GiB": round(pr.total_memory / 2 ** 30, 1)}
+    for key, attr in (("arch", "gcnArchName"), ("l2_cache_MiB", "L2_cache_size"), ("wavefront", "warp_size"),
+                      ("lds_per_cu_KiB", "shared_memory_per_multiprocessor")):
+        v = getattr(pr, attr, None)
+        if v is not None:
+            out[key] = round(v / 2 ** 20, 1) if key == "l2_cache_MiB" else (round(v / 1024) if key == "lds_per_cu_KiB" else v)
+    return out
+
+
 def hbm_ceiling(torch, binding, gib: int = 1, reps: int = 10):
     """What the simplest kernels get out of this GPU's HBM: one read of `gib` GiB, and a copy of it."""
     src = torch.zeros(gib << 28, dtype=torch.float32, device="cuda")
@@ -371,6 +384,7 @@ def main() -> int:
                    "k": c2["k"]},
         "roofline": head["roofline"],
         "hbm_measured_ceiling": ceiling,
+        "device": device_info(torch),
         "cpu_baseline": cpu,
         "kernel_ms": head["kernel_ms"],
         "iteration_frac_of_hbm_peak": head["iteration_frac_of_hbm_peak"],
