@@ -42,13 +42,13 @@ enum {
     EF21_ESTATE = -4  /* call not possible in the handle's state (e.g. no problem set)   */
 };
 
-/* flags of ef21_step (one order, optionally or-ed with EF21_PLUS and / or EF21_SEPARATE_KERNELS) */
+/* flags of ef21_step (one order, optionally or-ed with EF21_PLUS or EF21_ONE_LAUNCH) */
 enum {
     EF21_ORDER_GRAD_FIRST = 0u, /* lines 5, 6, 8 at the current x, then line 3 (default)      */
     EF21_ORDER_STEP_FIRST = 1u, /* line 3, then lines 5, 6, 8 at the new x (loop as printed)  */
     EF21_PLUS = 2u,             /* the loop body of Algorithm 3 (EF21+) instead of Algorithm 2 */
     EF21_CLASSIC_EF = 4u,       /* one round of Algorithm 4 (the original EF); no order, no EF21_PLUS */
-    EF21_SEPARATE_KERNELS = 8u  /* never the one-launch iteration of small problems (see ef21_step) */
+    EF21_ONE_LAUNCH = 8u        /* the whole pass as one kernel where the problem qualifies (see ef21_step) */
 };
 
 /* Human-readable text of the calling thread's last failure ("" if none).  Library-owned. */
@@ -182,10 +182,12 @@ int ef21_local_grad(ef21_handle h, const float *x, float *out_grad);
  * entry; line 8 adds the messages per coordinate in worker order in fp32 and applies
  * g + sum * (1/n) as one fused multiply-add; line 3 is one fused multiply-add per coordinate.
  * With supplied gradients every result (messages, g_i, g, x) is bitwise reproducible.
- * Small dense problems (grads NULL, d <= 1024, n * k <= 2048, n * m * d <= 2^24, no minibatch), whose
- * iteration is bound by launch latency, run the whole pass as ONE kernel: the same arithmetic in the same
- * order as the separate gradient, Top-k and aggregation kernels, so the results are the same bits;
- * EF21_SEPARATE_KERNELS in flags asks for the separate kernels all the same (for comparison).
+ * With EF21_ONE_LAUNCH in flags, a small dense problem (grads NULL, d <= 1024, n * k <= 2048,
+ * n * m * d <= 2^24, no minibatch, no EF21_PLUS) runs the whole pass as ONE kernel: the same arithmetic in the
+ * same order as the separate gradient, Top-k and aggregation kernels, so the results are the same bits.  It
+ * saves two launches and pays for them in device-scope fences: measured on par with the separate kernels for
+ * a handful of workers and slower for twenty, hence not the default.  Where the problem does not qualify the
+ * flag changes nothing.
  * EF21_EINVAL: unknown flag bits, or EF21_CLASSIC_EF together with an order or EF21_PLUS.
  */
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags);

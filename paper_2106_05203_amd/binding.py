@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libef21.so")
 
 EF21_OK, EF21_EINVAL, EF21_ENOMEM, EF21_EHIP, EF21_ESTATE = 0, -1, -2, -3, -4
-ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS, CLASSIC_EF, SEPARATE_KERNELS = 0, 1, 2, 4, 8
+ORDER_GRAD_FIRST, ORDER_STEP_FIRST, PLUS, CLASSIC_EF, ONE_LAUNCH = 0, 1, 2, 4, 8
 LOSS_LOGISTIC, LOSS_LEAST_SQUARES = 0, 1
 
 # every symbol include/ef21.h declares

@@ -596,7 +596,7 @@ static int enqueue_classic_ef(ef21_ctx *h, const float *grads, const ef21::Marke
 
 int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
     if (int rc = check_handle(h)) return rc;
-    if (flags & ~(uint32_t)(EF21_ORDER_STEP_FIRST | EF21_PLUS | EF21_CLASSIC_EF | EF21_SEPARATE_KERNELS))
+    if (flags & ~(uint32_t)(EF21_ORDER_STEP_FIRST | EF21_PLUS | EF21_CLASSIC_EF | EF21_ONE_LAUNCH))
         return fail(EF21_EINVAL, "unknown flags");
     if ((flags & EF21_CLASSIC_EF) && (flags & (EF21_ORDER_STEP_FIRST | EF21_PLUS)))
         return fail(EF21_EINVAL, "EF21_CLASSIC_EF combines with neither an order nor EF21_PLUS");
@@ -635,7 +635,7 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
         }
         return EF21_OK;
     }
-    if (!grads && h->kind == kDense && h->tickets && h->batch.tau == 0 && !(flags & EF21_SEPARATE_KERNELS) &&
+    if (!grads && h->kind == kDense && h->tickets && h->batch.tau == 0 && (flags & EF21_ONE_LAUNCH) &&
         ef21::small_step_applies(h->A, h->n, h->m, h->d, h->k)) {
         // lines 5, 6, 8 (and 3) in one launch
         hipError_t st = ef21::launch_small_step(h->A, h->y, h->x, h->g, h->g_i, h->n, h->m, h->d, h->k, h->lambda,

@@ -1,4 +1,4 @@
-"""The one-launch iteration of small dense problems (ef21_step without EF21_SEPARATE_KERNELS): bit for bit the
+"""The one-launch iteration of small dense problems (ef21_step with EF21_ONE_LAUNCH): bit for bit the
 state and the messages of the separate gradient, Top-k and aggregation kernels, step after step, in both loop
 orders and for both losses; and against the CPU oracle through f(x^t) (1e-4) and the first message."""
 import numpy as np
@@ -52,15 +52,15 @@ def test_same_bits_as_the_separate_kernels(gpu, n, d, m, k, order):
             h.set_problem_dense(Ag, yg, 0.1)
             h.set_state(x0, 0.5 * h.local_grad(x0), None)
         for t in range(12):
-            one.step(None, flag)
-            sep.step(None, flag | binding.SEPARATE_KERNELS)
+            one.step(None, flag | binding.ONE_LAUNCH)
+            sep.step(None, flag)
             a, b = one.get_state(), sep.get_state()
             for name, u, v in zip(("x", "g_i", "g"), a, b):
                 assert torch.equal(u, v), f"step {t}: {name} differs"
             (ia, va), (ib, vb) = one.get_messages(), sep.get_messages()
             assert torch.equal(ia, ib) and torch.equal(va, vb), f"step {t}: messages differ"
         one.set_timing(True)
-        one.step(None, flag)
+        one.step(None, flag | binding.ONE_LAUNCH)
         classes = one.get_timing(reset=True)
         one.set_timing(False)
         assert "small_step" in classes and "topk_row" not in classes and "grad_main" not in classes
@@ -79,8 +79,8 @@ def test_least_squares_same_bits(gpu):
             h.set_loss(binding.LOSS_LEAST_SQUARES)
             h.set_state(x0, torch.zeros((n, d), device="cuda"), None)
         for t in range(10):
-            one.step()
-            sep.step(None, binding.SEPARATE_KERNELS)
+            one.step(None, binding.ONE_LAUNCH)
+            sep.step()
             for u, v in zip(one.get_state(), sep.get_state()):
                 assert torch.equal(u, v), f"step {t}"
 
@@ -100,7 +100,7 @@ def test_against_the_oracle(gpu, oracle):
         f0 = P.loss(x0)
         for t in range(60):
             oracle.iteration(st, P.grads, k, gamma)
-            h.step()
+            h.step(None, binding.ONE_LAUNCH)
             if t == 0:        # zero state: the message is the Top-k of the gradient the library itself reports
                 idx, val = h.get_messages()
                 ref_idx, ref_val = oracle.topk_rows(grads0.astype(np.float64), k)
@@ -118,6 +118,13 @@ def test_larger_problems_keep_the_separate_kernels(gpu):
     with binding.EF21(n, d, k, 0.5) as h:
         h.set_problem_dense(to_gpu(torch, A), to_gpu(torch, y), 0.1)
         h.set_timing(True)
+        h.step(None, binding.ONE_LAUNCH)
+        classes = h.get_timing(reset=True)
+        assert "small_step" not in classes and "grad_main" in classes
+    with binding.EF21(4, 100, 3, 0.5) as h:          # and a qualifying problem takes them unless asked
+        A, y, _ = problem(4, 100, 250, 8)
+        h.set_problem_dense(to_gpu(torch, A), to_gpu(torch, y), 0.1)
+        h.set_timing(True)
         h.step()
         classes = h.get_timing(reset=True)
         assert "small_step" not in classes and "grad_main" in classes
@@ -127,9 +134,9 @@ def test_flag_combinations(gpu):
     torch, binding = gpu
     with binding.EF21(2, 16, 2, 0.1) as h:
         g = torch.ones((2, 16), device="cuda")
-        h.step(g, binding.SEPARATE_KERNELS)
-        h.step(g, binding.SEPARATE_KERNELS | binding.PLUS | binding.ORDER_STEP_FIRST)
-        h.step(g, binding.SEPARATE_KERNELS | binding.CLASSIC_EF)
+        h.step(g, binding.ONE_LAUNCH)                      # supplied gradients: the flag changes nothing
+        h.step(g, binding.ONE_LAUNCH | binding.PLUS | binding.ORDER_STEP_FIRST)
+        h.step(g, binding.ONE_LAUNCH | binding.CLASSIC_EF)
         for bad in (16, binding.CLASSIC_EF | binding.PLUS, binding.CLASSIC_EF | binding.ORDER_STEP_FIRST):
             with pytest.raises(binding.EF21Error):
                 h.step(g, bad)
