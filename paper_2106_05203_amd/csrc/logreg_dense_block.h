@@ -160,10 +160,13 @@ inline DenseVariant dense_variant(int64_t d, bool vec4) {
     return {0, 0};
 }
 
-// Two rows of a wavefront in flight while their registers fit.
+// Rows of a wavefront in flight: 32 row entries per lane for narrow rows (a wavefront would otherwise have only
+// a kilobyte or two of loads outstanding; more does not fit the registers of the 1024-thread kernel that shares
+// this code), at most eight rows; two rows of 32 entries per lane; one where a row alone fills the registers.
 template <int VEC, int NQ>
 constexpr int dense_rows_in_flight() {
-    return NQ * VEC <= 32 ? 2 : 1;
+    constexpr int per_lane = NQ * VEC;
+    return per_lane > 32 ? 1 : (per_lane >= 16 ? 2 : (per_lane >= 8 ? 4 : 8));
 }
 
 }  // namespace ef21
