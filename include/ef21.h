@@ -87,6 +87,23 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
               void *hip_stream);
 
 /*
+ * ef21_topk for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results (the same kernels) as ef21_topk, but the workspace
+ * of the long-row path is a 64 MiB array that is part of the library's device image (each GPU the library runs on
+ * holds it until the process ends), so the call allocates nothing, frees nothing and synchronises nothing: it
+ * enqueues kernels on `hip_stream` and returns.  Rows of 16384 entries or more that are not selected by one
+ * workgroup per row (d > 61440 or k > 1024) need about 12 d + 50 000 bytes of workspace per row; a call whose
+ * n rows need more than the 64 MiB (for example more than five rows of 10^6 entries) is rejected with EF21_EINVAL
+ * and a message that gives both sizes -- use ef21_topk for those.  Shorter rows need no workspace and have no limit.
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads) race and
+ * give wrong results; calls that follow one another on a stream, of any shapes, are fine (each call clears the
+ * part of the array that must start at zero with a fill kernel of its own, so it may also be captured into a graph).
+ * Errors otherwise as ef21_topk.
+ */
+int ef21_topk_static(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_idx, float *out_val,
+                     void *hip_stream);
+
+/*
  * Attach the objective of Section 5, eq. (9): logistic loss with the non-convex regulariser,
  *   f_i(x) = (1/m) sum_l log(1 + exp(-y_il a_il^T x)) + lambda sum_j x_j^2 / (1 + x_j^2),
  * each worker holding m rows (each f_i carries the full regulariser, so (1/n) sum_i f_i is

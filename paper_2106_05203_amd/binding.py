@@ -24,6 +24,7 @@ SYMBOLS = (
     "ef21_set_problem_dense", "ef21_set_problem_csr", "ef21_set_state", "ef21_get_state",
     "ef21_get_messages", "ef21_local_grad", "ef21_step", "ef21_set_timing", "ef21_get_timing", "ef21_kernel_name",
     "ef21_hbm_read", "ef21_hbm_copy", "ef21_get_choices", "ef21_set_loss", "ef21_set_minibatch", "ef21_theory_stepsize",
+    "ef21_topk_static",
 )
 K_COUNT = 11
 
@@ -55,6 +56,7 @@ def load_library() -> C.CDLL:
     lib.ef21_destroy.argtypes = [p]
     lib.ef21_set_stream.argtypes = [p, p]
     lib.ef21_topk.argtypes = [p, i32, i64, i64, p, p, p]
+    lib.ef21_topk_static.argtypes = [p, i32, i64, i64, p, p, p]
     lib.ef21_set_problem_dense.argtypes = [p, p, p, i64, f32]
     lib.ef21_set_problem_csr.argtypes = [p, p, p, p, p, i64, f32]
     lib.ef21_set_state.argtypes = [p, p, p, p]
@@ -102,8 +104,8 @@ def _current_stream_ptr() -> int:
 
 
 def ef21_topk(rows: torch.Tensor, k: int, out_idx: torch.Tensor | None = None,
-              out_val: torch.Tensor | None = None):
-    """Batched Top-k (ef21_topk) of rows [n][d] on torch's current stream.
+              out_val: torch.Tensor | None = None, static: bool = False):
+    """Batched Top-k (ef21_topk, or ef21_topk_static if `static`) of rows [n][d] on torch's current stream.
     Returns (idx [n][k] int32 ascending, val [n][k] float32)."""
     lib = load_library()
     if rows.dim() != 2:
@@ -113,8 +115,9 @@ def ef21_topk(rows: torch.Tensor, k: int, out_idx: torch.Tensor | None = None,
         out_idx = torch.empty((n, max(k, 0)), dtype=torch.int32, device=rows.device)
     if out_val is None:
         out_val = torch.empty((n, max(k, 0)), dtype=torch.float32, device=rows.device)
-    _check(lib.ef21_topk(_dev(rows, torch.float32), n, d, k, _dev(out_idx, torch.int32), _dev(out_val, torch.float32),
-                         _current_stream_ptr()))
+    call = lib.ef21_topk_static if static else lib.ef21_topk
+    _check(call(_dev(rows, torch.float32), n, d, k, _dev(out_idx, torch.int32), _dev(out_val, torch.float32),
+                _current_stream_ptr()))
     return out_idx, out_val
 
 

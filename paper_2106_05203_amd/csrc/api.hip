@@ -9,6 +9,12 @@
 #include "../../include/ef21.h"
 #include "kernels.h"
 
+// Workspace of ef21_topk_static: device memory that exists from the moment the library is loaded, so that call
+// never allocates.  Every GPU holds its own copy at its own address; host code reaches it only through the address
+// that hipGetSymbolAddress returns with that GPU current, never through the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local std::string g_last_error;
@@ -46,6 +52,18 @@ struct SharedWorkspace {
     int64_t last_d[64] = {};
 };
 SharedWorkspace g_topk_ws;
+
+// Per-device address of `scratch`.
+struct StaticScratch {
+    std::mutex mu;
+    void *ptr[64] = {};           // per device, looked up on the first call with that device current
+};
+StaticScratch g_static_ws;
+
+// Rows that the long-row path selects with a workspace (the others are selected by one workgroup each, without).
+bool topk_needs_workspace(int64_t d, int64_t k) {
+    return use_split(d) && !(d <= ef21::kRow16Max && k <= ef21::kRow16MaxK);
+}
 
 }  // namespace
 
@@ -339,6 +357,40 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
             g_topk_ws.last_n[dev] = n;
             g_topk_ws.last_d[dev] = d;
         }
+    }
+    ef21::TopkArgs p{rows, nullptr, n, d, k, out_idx, out_val, nullptr};
+    return enqueue_topk(p, ws, stream, ef21::Marker());
+}
+
+int ef21_topk_static(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_idx, float *out_val,
+                     void *hip_stream) {
+    if (int rc = check_topk_sizes(n, d, k)) return rc;
+    if (!rows || !out_idx || !out_val) return fail(EF21_EINVAL, "rows, out_idx and out_val must not be NULL");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    void *ws = nullptr;
+    if (topk_needs_workspace(d, k)) {
+        const size_t need = ef21::topk_split_workspace_bytes(n, d, k);
+        if (need > kStaticScratchBytes)
+            return fail(EF21_EINVAL, "ef21_topk_static: n rows of d entries need " + std::to_string(need) +
+                                         " bytes of workspace, the static scratch holds " +
+                                         std::to_string(kStaticScratchBytes) + " (use ef21_topk)");
+        int dev = 0;
+        EF21_HIP(hipGetDevice(&dev));
+        if (dev < 0 || dev >= 64) return fail(EF21_ESTATE, "device ordinal out of range");
+        {
+            std::lock_guard<std::mutex> lock(g_static_ws.mu);
+            if (!g_static_ws.ptr[dev]) {
+                void *p = nullptr;
+                EF21_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+                if (!p) return fail(EF21_EHIP, "hipGetSymbolAddress returned no address for the static scratch");
+                g_static_ws.ptr[dev] = p;
+            }
+            ws = g_static_ws.ptr[dev];
+        }
+        // The array keeps the last call's contents (of any shape): the control words that must start at zero are
+        // cleared by a fill kernel, every call.
+        hipError_t st = ef21::launch_topk_split_reset(ws, n, d, stream);
+        if (st != hipSuccess) return fail_hip(st, "scratch reset launch");
     }
     ef21::TopkArgs p{rows, nullptr, n, d, k, out_idx, out_val, nullptr};
     return enqueue_topk(p, ws, stream, ef21::Marker());
