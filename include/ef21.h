@@ -58,7 +58,7 @@ const char *ef21_last_error(void);
  * Input line of Algorithm 2: n workers, dimension d, Top-k parameter k (1 <= k <= d), learning
  * rate gamma > 0 (finite).  Allocates, on the current HIP device, the state x [d], g [d],
  * g_i [n][d] (all zero) and the last messages (idx, val) [n][k].  Returns NULL on failure.
- * d must be below 2^31 (indices are int32).
+ * d must be below 2^31 (indices are int32) and n at most 65535 (a worker is a row of the launch grids).
  */
 ef21_handle ef21_create(int32_t n, int64_t d, int64_t k, float gamma);
 
@@ -81,7 +81,7 @@ int ef21_set_stream(ef21_handle h, void *hip_stream);
  * call uses a device workspace that the library keeps per device and grows on demand with
  * hipMalloc (a growing call synchronises the device); concurrent ef21_topk calls on one device
  * share that workspace and must not overlap.
- * EF21_EINVAL: n < 1, d < 1, d >= 2^31, k < 1, k > d, NULL pointer.
+ * EF21_EINVAL: n < 1, n > 65535 (a row is a row of the launch grids), d < 1, d >= 2^31, k < 1, k > d, NULL pointer.
  */
 int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_idx, float *out_val,
               void *hip_stream);

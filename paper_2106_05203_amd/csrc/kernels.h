@@ -4,7 +4,28 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace ef21 {
+
+// Runs `setup` once per HIP device, with that device current: for attributes of a kernel (such as its dynamic LDS
+// limit), which the runtime keeps per device.  Thread-safe; a failed setup is tried again by the next call.
+struct PerDeviceOnce {
+    std::mutex mu;
+    bool done[64] = {};
+    template <class Setup>
+    hipError_t operator()(Setup setup) {
+        int dev = 0;
+        hipError_t st = hipGetDevice(&dev);
+        if (st != hipSuccess) return st;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> lock(mu);
+        if (done[dev]) return hipSuccess;
+        st = setup();
+        if (st == hipSuccess) done[dev] = true;
+        return st;
+    }
+};
 
 // Kernel classes for the optional per-kernel timing of a handle (EF21_K_* in include/ef21.h).
 enum KernelId {
@@ -65,10 +86,11 @@ struct TopkArgs {
 // quickly (and as the reference device path for long rows).
 hipError_t launch_topk_row(const TopkArgs &p, hipStream_t stream);
 
-// One workgroup per row that reads the row once and keeps 16 bits of every key in LDS: rows of 2048 to kRow16Max
-// entries given as they are (p.b == nullptr), k <= kRow16MaxK (meant for rows too long for launch_topk_row's LDS
-// copy).  No workspace.
-constexpr int64_t kRow16Max = 61440, kRow16MaxK = 1024;
+// One workgroup per row that reads the row once and keeps 16 bits of every key in LDS: rows of kRow16Min to
+// kRow16Max entries given as they are (p.b == nullptr), k <= kRow16MaxK (meant for rows too long for
+// launch_topk_row's LDS copy; the lower limit keeps the kernel's later use of the row copy's LDS, 15 KB of bitmap
+// and prefix words, inside the 2 d bytes of the copy).  No workspace.  Other shapes: hipErrorInvalidValue.
+constexpr int64_t kRow16Min = 16384, kRow16Max = 61440, kRow16MaxK = 1024;
 hipError_t launch_topk_row16(const TopkArgs &p, hipStream_t stream);
 
 // Many workgroups per row for long rows.  Workspace layout and size: topk_split_workspace_bytes.

@@ -608,16 +608,16 @@ hipError_t launch_logreg_grad_csr(const int64_t *rowptr, const int32_t *col, con
     if (index && !listed) {
         IndexLayout ix;
         index_layout(n, m, d, nnz, (char *)const_cast<void *>(index), &ix);
-        static bool configured = false;
-        if (!configured) {
+        static PerDeviceOnce configured;
+        const hipError_t cfg = configured([] {
             hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csrr_dot_kernel),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, sizeof(float) * kRangeCols);
             if (st == hipSuccess)
                 st = hipFuncSetAttribute(reinterpret_cast<const void *>(&csc_grad_kernel<true, uint16_t>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, sizeof(float) * kCoefLdsRows);
-            if (st != hipSuccess) return st;
-            configured = true;
-        }
+            return st;
+        });
+        if (cfg != hipSuccess) return cfg;
         const int64_t row_chunks = (m + kCscCols - 1) / kCscCols;
         hipLaunchKernelGGL(csrr_dot_kernel, dim3((unsigned)(ix.R * row_chunks), (unsigned)n), dim3(kCscThreads),
                            sizeof(float) * (size_t)ix.Wc, stream, ix.bstart, ix.rptr, ix.rcol, ix.rval, x, ix.zpart, m, d,

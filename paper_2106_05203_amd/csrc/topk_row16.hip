@@ -370,14 +370,13 @@ __global__ __launch_bounds__(kRowThreads) void topk_row16_kernel(TopkArgs p) {
 template <bool VEC4>
 hipError_t launch(const TopkArgs &p, hipStream_t stream) {
     const size_t dyn = sizeof(uint16_t) * (((size_t)p.d + 7) & ~(size_t)7);
-    static bool configured = false;            // per instantiation; the attribute is a property of the function
-    if (!configured) {
-        hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_row16_kernel<VEC4>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)(sizeof(uint16_t) * (size_t)kRow16Max));
-        if (st != hipSuccess) return st;
-        configured = true;
-    }
+    static PerDeviceOnce configured;           // per instantiation: the attribute belongs to the function
+    const hipError_t cfg = configured([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_row16_kernel<VEC4>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)(sizeof(uint16_t) * (size_t)kRow16Max));
+    });
+    if (cfg != hipSuccess) return cfg;
     hipLaunchKernelGGL((topk_row16_kernel<VEC4>), dim3((unsigned)p.n), dim3(kRowThreads), dyn, stream, p);
     return hipGetLastError();
 }
@@ -385,7 +384,7 @@ hipError_t launch(const TopkArgs &p, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_topk_row16(const TopkArgs &p, hipStream_t stream) {
-    if (p.b || p.g_i || p.parts.part || p.d > kRow16Max || p.d < 2 * kRowThreads || p.k > kRow16MaxK)
+    if (p.b || p.g_i || p.parts.part || p.d > kRow16Max || p.d < kRow16Min || p.k > kRow16MaxK)
         return hipErrorInvalidValue;
     const bool vec4 = (p.d % 4 == 0) && ((uintptr_t)p.a % 16 == 0);
     return vec4 ? launch<true>(p, stream) : launch<false>(p, stream);

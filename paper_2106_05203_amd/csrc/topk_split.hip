@@ -174,10 +174,7 @@ __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b
 // Per-wavefront staging ring in LDS: candidates are appended here and leave for the slot in global
 // memory 64 at a time, as one full-width store per array, instead of as many scattered 4-byte stores.
 // With UPDATE a candidate also carries b + v, the value g_i takes at its position if it is kept.
-#ifndef EF21_RING
-#define EF21_RING 128
-#endif
-constexpr uint32_t kRing = EF21_RING;        // entries of a staging ring (power of two, >= 128)
+constexpr uint32_t kRing = 128;              // entries of a staging ring (power of two, >= 128)
 struct StageRing {
     int32_t idx[kRing];
     float val[kRing];
@@ -920,13 +917,12 @@ void launch_collect(const TopkArgs &p, const Ws &w, hipStream_t stream) {
 template <bool DIFF, bool UPDATE>
 hipError_t launch_select(const TopkArgs &p, const Ws &w, hipStream_t stream) {
     constexpr size_t kDyn = sizeof(uint32_t) * kSelCap;
-    static bool configured = false;    // per instantiation; the attribute is a property of the function
-    if (!configured) {
-        hipError_t st = hipFuncSetAttribute(reinterpret_cast<const void *>(&split_select_kernel<DIFF, UPDATE>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDyn);
-        if (st != hipSuccess) return st;
-        configured = true;
-    }
+    static PerDeviceOnce configured;   // per instantiation: the attribute belongs to the function
+    const hipError_t cfg = configured([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(&split_select_kernel<DIFF, UPDATE>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDyn);
+    });
+    if (cfg != hipSuccess) return cfg;
     hipLaunchKernelGGL((split_select_kernel<DIFF, UPDATE>), dim3((unsigned)p.n), dim3(kBlk), kDyn, stream, p, w);
     return hipGetLastError();
 }
