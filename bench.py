@@ -252,13 +252,14 @@ def bench_grads(torch, binding, workloads, steps: int, warmup: int):
     c = workloads.CONFIGS["C4"]
     n, d, k = c["n"], c["d"], c["k"]
     log(f"C4: generating Student-t gradients n={n} d={d}")
-    base = dev(torch, workloads.student_t_grads(n, d, seed=c["seed"]))
-    # four distinct gradient sets (1.4 GB in all): the host-drawn set, and copies of it rotated along
-    # the coordinate axis and across workers -- same distribution, different values at every position
-    pool = [base] + [torch.roll(base, shifts=(j, 1_000_003 * j), dims=(0, 1)).contiguous() for j in (1, 2, 3)]
+    # "drawn fresh each step": a pool of NP independent gradient sets made on the device (358 MB each, every one
+    # larger than the caches), cycled.  (A short pool of rotated copies of one set makes the selection threshold
+    # jump with the pool's period, which independent draws do not.)
+    NP = 8
+    pool = workloads.student_t_grads_on_device(n, d, NP, seed=c["seed"])
     h = binding.EF21(n, d, k, c["gamma"])
-    wall, ev = timed_loop(torch, lambda i: h.step(pool[i % 4]), steps, warmup)
-    per_kernel, launches = kernel_times(torch, h, lambda i: h.step(pool[i % 4]), steps)
+    wall, ev = timed_loop(torch, lambda i: h.step(pool[i % NP]), steps, warmup)
+    per_kernel, launches = kernel_times(torch, h, lambda i: h.step(pool[i % NP]), steps)
     it_bytes = 8 * n * d + 12 * d + 24 * n * k
     out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s (gradients supplied)", "ms_per_step": round(wall, 5),
            "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()}, "iteration_algorithmic_bytes": it_bytes,
@@ -266,14 +267,14 @@ def bench_grads(torch, binding, workloads, steps: int, warmup: int):
            "topk_elements_per_s": round(n * d / (sum(v for k_, v in per_kernel.items() if k_.startswith("topk")) * 1e-3), 1)}
     # the comparison method on the same gradients: Algorithm 4 rewrites its whole state e_i every round
     h.set_state(torch.zeros(d, device="cuda"), torch.zeros((n, d), device="cuda"), None)
-    wall_e, _ = timed_loop(torch, lambda i: h.step(pool[i % 4], binding.CLASSIC_EF), steps, warmup)
+    wall_e, _ = timed_loop(torch, lambda i: h.step(pool[i % NP], binding.CLASSIC_EF), steps, warmup)
     out["classic_ef"] = {"value": round(1e3 / wall_e, 2), "unit": "EF iterations/s (gradients supplied)",
                          "ms_per_step": round(wall_e, 5)}
     # Algorithm 3 on the same gradients: two Top-k selections, the distortions and the mean of the rows, each a
     # pass of its own over the long rows
     h.set_state(torch.zeros(d, device="cuda"), torch.zeros((n, d), device="cuda"), None)
-    wall_p, _ = timed_loop(torch, lambda i: h.step(pool[i % 4], binding.PLUS), max(10, steps // 2), max(3, warmup // 2))
-    pk, pl = kernel_times(torch, h, lambda i: h.step(pool[i % 4], binding.PLUS), max(10, steps // 2))
+    wall_p, _ = timed_loop(torch, lambda i: h.step(pool[i % NP], binding.PLUS), max(10, steps // 2), max(3, warmup // 2))
+    pk, pl = kernel_times(torch, h, lambda i: h.step(pool[i % NP], binding.PLUS), max(10, steps // 2))
     out["ef21_plus"] = {"value": round(1e3 / wall_p, 2), "unit": "EF21+ iterations/s (gradients supplied)",
                         "ms_per_step": round(wall_p, 5),
                         "kernel_ms_per_step": {k_: round(v * pl[k_], 5) for k_, v in pk.items()},

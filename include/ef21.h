@@ -92,8 +92,8 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
  * of the long-row path is a 64 MiB array that is part of the library's device image (each GPU the library runs on
  * holds it until the process ends), so the call allocates nothing, frees nothing and synchronises nothing: it
  * enqueues kernels on `hip_stream` and returns.  Rows of 16384 entries or more that are not selected by one
- * workgroup per row (d > 61440 or k > 1024) need about 12 d + 50 000 bytes of workspace per row; a call whose
- * n rows need more than the 64 MiB (for example more than five rows of 10^6 entries) is rejected with EF21_EINVAL
+ * workgroup per row (d > 61440 or k > 1024) need about 8 d + 90 000 bytes of workspace per row; a call whose
+ * n rows need more than the 64 MiB (for example more than eight rows of 10^6 entries) is rejected with EF21_EINVAL
  * and a message that gives both sizes -- use ef21_topk for those.  Shorter rows need no workspace and have no limit.
  * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads) race and
  * give wrong results; calls that follow one another on a stream, of any shapes, are fine (each call clears the

@@ -235,8 +235,13 @@ int enqueue_local_grad(ef21_ctx *c, const float *x, float *out, ef21::GradParts 
     return EF21_OK;
 }
 
-int enqueue_topk(const ef21::TopkArgs &p, void *workspace, hipStream_t stream, const ef21::Marker &mk) {
+// index_ready (may be nullptr): the message index of the aggregation, asked for through p.agg_start, was written.
+int enqueue_topk(ef21::TopkArgs p, void *workspace, hipStream_t stream, const ef21::Marker &mk,
+                 bool *index_ready = nullptr) {
     hipError_t st;
+    const bool split = use_split(p.d) && workspace && !(p.d <= ef21::kRow16Max && p.k <= ef21::kRow16MaxK && !p.b && !p.parts.part);
+    if (!(split && p.k > 1)) p.agg_start = nullptr;
+    if (index_ready) *index_ready = p.agg_start != nullptr;
     if (use_split(p.d) && p.d <= ef21::kRow16Max && p.k <= ef21::kRow16MaxK && !p.b && !p.parts.part) {
         st = ef21::launch_topk_row16(p, stream);
         mk(ef21::K_TOPK_ROW);
@@ -248,6 +253,15 @@ int enqueue_topk(const ef21::TopkArgs &p, void *workspace, hipStream_t stream, c
     }
     if (st != hipSuccess) return fail_hip(st, "Top-k kernel launch");
     return EF21_OK;
+}
+
+// Asks the Top-k (long rows only) to write the index of the messages that launch_aggregate would otherwise build.
+void want_message_index(const ef21_ctx *c, ef21::TopkArgs *p) {
+    const int shift = ef21::aggregate_index_shift(c->n, c->k, c->d);
+    if (shift < 0) return;
+    p->agg_start = (int32_t *)c->agg_index;
+    p->agg_shift = shift;
+    p->agg_nblk = ((c->d - 1) >> shift) + 1;
 }
 
 // The long-row workspace of a handle keeps one layout for life: zero its control part once.
@@ -616,8 +630,10 @@ static int enqueue_plus(ef21_ctx *h, const float *grads, const ef21::Marker &mk)
     int32_t *idx_b = h->plus_idx, *idx_m = h->plus_idx + nk;
     float *val_b = h->plus_val, *val_m = h->plus_val + nk;
     ef21::TopkArgs plain{grads, nullptr, h->n, h->d, h->k, idx_b, val_b, nullptr};        // line 5: C(s)
+    plain.warm = 2;
     if (int rc = enqueue_topk(plain, h->topk_ws, h->stream, mk)) return rc;
     ef21::TopkArgs markov{grads, h->g_i, h->n, h->d, h->k, idx_m, val_m, nullptr};        // line 6: C(s - g_i)
+    markov.warm = 1;
     if (int rc = enqueue_topk(markov, h->topk_ws, h->stream, mk)) return rc;
     hipError_t st = ef21::launch_plus_choose(grads, h->g_i, h->n, h->d, h->k, idx_b, val_b, idx_m, val_m,
                                              h->plus_scratch, h->plus_branch, h->plus_bm, h->msg_idx, h->msg_val,
@@ -634,13 +650,16 @@ static int enqueue_classic_ef(ef21_ctx *h, const float *grads, const ef21::Marke
     mk(ef21::K_PLUS);
     if (st != hipSuccess) return fail_hip(st, "EF accumulation launch");
     ef21::TopkArgs p{h->g_i, nullptr, h->n, h->d, h->k, h->msg_idx, h->msg_val, nullptr};            // w_i = C(p_i)
-    if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk)) return rc;
+    p.warm = 1;
+    bool index_ready = false;
+    want_message_index(h, &p);
+    if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk, &index_ready)) return rc;
     st = ef21::launch_ef_clear_kept(h->msg_idx, h->n, h->k, h->g_i, h->d, h->stream);               // e_i = p_i - w_i
     if (st == hipSuccess) st = ef21::launch_fill_zero(h->g, h->d, h->stream);
     mk(ef21::K_PLUS);
     if (st != hipSuccess) return fail_hip(st, "EF error update launch");
     st = ef21::launch_aggregate(h->msg_idx, h->msg_val, h->n, h->k, h->d, h->g, h->x, 1.0f, h->agg_index,
-                                h->stream);                                                         // x - mean w
+                                h->stream, index_ready);                                            // x - mean w
     mk(ef21::K_MODEL_STEP);
     if (st != hipSuccess) return fail_hip(st, "aggregation launch");
     return EF21_OK;
@@ -705,10 +724,13 @@ int ef21_step(ef21_handle h, const float *grads, uint32_t flags) {
     }
     // lines 5 and 6: Top-k of grads - g_i, fused with the update of g_i
     ef21::TopkArgs p{grads, h->g_i, h->n, h->d, h->k, h->msg_idx, h->msg_val, h->g_i, parts};
-    if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk)) return rc;
+    p.warm = 1;
+    bool index_ready = false;
+    want_message_index(h, &p);
+    if (int rc = enqueue_topk(p, h->topk_ws, h->stream, mk, &index_ready)) return rc;
     // line 8 from the messages, and (default order) line 3 in the same pass over the coordinates
     hipError_t st = ef21::launch_aggregate(h->msg_idx, h->msg_val, h->n, h->k, h->d, h->g, step_first ? nullptr : h->x,
-                                           h->gamma, h->agg_index, h->stream);
+                                           h->gamma, h->agg_index, h->stream, index_ready);
     mk(ef21::K_MODEL_STEP);
     if (st != hipSuccess) return fail_hip(st, "aggregation launch");
     return EF21_OK;

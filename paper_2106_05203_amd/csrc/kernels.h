@@ -79,6 +79,14 @@ struct TopkArgs {
     float *g_i;
     GradParts parts;   // if parts.part != nullptr the rows of `a` are these unreduced gradients (`a` is not read);
                        // launch_topk_row only, d <= 8192, b != nullptr
+    int32_t warm;      // launch_topk_split only: 0, or 1 .. 2 = the row thresholds of the last call that named the
+                       // same number on this workspace serve as the first guess of this call's (the result never
+                       // depends on it; meant for consecutive iterations of one algorithm on one state)
+    // launch_topk_split with k > 1 only: if agg_start != nullptr the emission also writes the index that
+    // launch_aggregate needs of the messages (aggregate_index_shift), so that its own indexing kernel can be skipped
+    int32_t *agg_start;
+    int32_t agg_shift;
+    int64_t agg_nblk;
 };
 
 // One workgroup per row, four radix passes over the row plus an ordered emission.  Needs no
@@ -105,11 +113,16 @@ hipError_t launch_model_step(float *x, const float *g, int64_t d, float gamma, h
 
 // Algorithm 2, line 8: g <- g + (1/n) sum_i c_i from the messages (idx, val) [n][k] (positions ascending
 // and distinct inside a row), summed in worker order, without atomics; if x != nullptr followed, in the
-// same pass over the coordinates, by line 3 with the new g.  `index`: aggregate_index_bytes(n, d) bytes
-// of scratch, overwritten by every call.
+// same pass over the coordinates, by line 3 with the new g.
+// `index`: aggregate_index_bytes(n, d) bytes of scratch, overwritten by every call.
+// The index: start[w][b] = first pair of worker w's message at or beyond coordinate b << shift, for the blocks
+// b = 0 .. nblk of 2^shift coordinates (start[w][nblk] = k), int32 [n][nblk + 1].  aggregate_index_shift gives the
+// shift that launch_aggregate uses for a shape (nblk = ceil(d / 2^shift)), or -1 if it uses no index for it.
+// index_ready: the caller has already written the index (launch_topk_split can); otherwise a kernel of the call does.
 size_t aggregate_index_bytes(int32_t n, int64_t d);
+int aggregate_index_shift(int32_t n, int64_t k, int64_t d);
 hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int64_t k, int64_t d, float *g, float *x,
-                            float gamma, void *index, hipStream_t stream);
+                            float gamma, void *index, hipStream_t stream, bool index_ready = false);
 
 // g = (1/n) sum_i g_i (input line of Algorithm 2), summed in worker order.
 hipError_t launch_mean_rows(const float *g_i, float *g, int32_t n, int64_t d, hipStream_t stream);

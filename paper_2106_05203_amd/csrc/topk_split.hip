@@ -2,28 +2,30 @@
 // itself read ONCE.
 //
 // Same selection rule as the one-workgroup kernel (31-bit magnitude key, ties to the lower index,
-// ascending output).  Pipeline:
+// ascending output).  Three kernels:
 //
-//   collect   Every workgroup first looks at the same fixed sample of its row (32 evenly spaced
-//             pieces of 256 entries), finds in LDS a key `key_lo` that, with overwhelming
-//             probability, at least k entries of the row reach, and then streams its part of the
-//             row.  Each wavefront owns a contiguous piece of the row and appends the entries
-//             with key >= key_lo ("candidates", a few per cent of the row) in position order to
-//             its own slot of the workspace.  No atomics, no fences, no inter-workgroup traffic.
-//   then, on the candidates only, either
-//   select    (small k) one workgroup per row: candidate keys into LDS, radix select there, ordered
-//             emission of the k kept entries (+ line 6 of Algorithm 2); or
-//   hist x2, count, emit   (large k) the same steps spread over several workgroups per row,
-//             chained by kernel boundaries: a kernel merges its LDS histograms into the row's
-//             global one with a few atomics per bin, the NEXT kernel's workgroups each scan the
-//             merged histogram in their prologue.  The candidates' keys lie at or above key_lo and
-//             the threshold key T a little above it, so the two digits are taken from key - key_lo:
-//             12 bits from bit 11 upwards (a window of one octave; keys beyond it share the last
-//             bin), then the low 11 bits.
+//   collect   A key `key_lo` that (almost surely) at least k entries of the row reach is fixed first: from the
+//             threshold key T of the previous call on the same quantity, lowered by a few per cent (warm start:
+//             inside ef21_step consecutive iterations select nearly the same T), else from a fixed sample of the
+//             row (32 evenly spaced pieces of 256 entries) that every workgroup of the row looks at.  Then each
+//             wavefront streams a contiguous piece of the row and appends the entries with key >= key_lo
+//             ("candidates", one or two per cent of the row) in position order to its own slot of the workspace,
+//             counting them into the workgroup's LDS histogram of (key - key_lo) >> shift on the way (4096 bins;
+//             keys beyond the window share the last bin).  The workgroup's histogram is added to the row's with
+//             one atomic per non-empty bin.  No fences, no waiting.
+//   count     Prologue of every workgroup: the bin that holds T, from the row's histogram.  Body, one wavefront
+//             per slot: the slot's number of candidates in higher bins, and the candidates of T's bin (a handful)
+//             appended to the row's short "tie list".
+//   emit      Prologue: the tie list ranked in LDS (larger key first, lower position first) gives T and the number
+//             q of entries equal to T to keep; the counts of the earlier slots give the output offset.  Body, one
+//             wavefront per slot: ordered emission of the k kept entries (+ line 6 of Algorithm 2 on request).
 //
-// The estimate can be wrong (fewer than k candidates, or T beyond the window); the row is then selected by the exact
-// one-workgroup algorithm on the original data (inside `select`, or by an extra workgroup of the
-// `count` kernel), so the result never depends on the sample.  Slots have the capacity of their piece, so any input fits.
+// The guess can be wrong: fewer than k candidates, T beyond the histogram's window, or a crowded bin (more
+// than kTieCap entries, i.e. very many equal magnitudes at the threshold).  After a warm start a second collect
+// pass (normally a launch that ends at once) redoes such a row from the sample; a row that still fails is selected
+// by the exact one-workgroup algorithm on the original data (an extra workgroup of the count kernel), so the
+// result never depends on the guess.  Slots have the capacity of their piece, so any input fits.
+#include <algorithm>
 #include <cmath>
 
 #include "topk_row_impl.h"
@@ -31,38 +33,49 @@
 namespace ef21 {
 namespace {
 
-constexpr int kBlk = kRowThreads;            // collect / select / rescue workgroups
+constexpr int kBlk = kRowThreads;            // collect / rescue workgroups
 constexpr int kBlkWaves = kBlk / kWave;
 constexpr int kSample = 8192;                // sampled entries per row
 constexpr int kSamplePer = kSample / kBlk;
 constexpr int kPieceLen = 256, kPieces = kSample / kPieceLen;
 constexpr int kMaxSlots = 4096;              // slots (wavefront pieces) per row
-constexpr int kSelCap = 28672;               // candidate keys the select kernel holds in LDS
-// Rows expected to keep more candidates than this take the many-workgroup stages: their four launches cost about
-// 28 us whatever k is, the one-workgroup select grows with the candidates and passes that at about 12 000.
-constexpr int kSelectMax = 12288;
-constexpr int kCandThreads = 1024;           // count / emit workgroups (large k): one wavefront per slot
+constexpr int kCandThreads = 1024;           // count / emit workgroups: one wavefront per slot
 constexpr int kCandWaves = kCandThreads / kWave;
-constexpr int kHistThreads = 512;            // candidate histogram workgroups (large k)
-constexpr int kCandBlocks = 16;              // ... of which each row gets this many
-constexpr int kBins1 = 1 << kBits1, kBins2 = 1 << kBits2, kBins3 = 1 << kBits3;
-constexpr int kBitsA = 12, kBitsB = 11;        // large k: digits of key - key_lo
-constexpr int kBinsA = 1 << kBitsA, kBinsB = 1 << kBitsB;
+constexpr int kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
+constexpr int kHistBins = 4096;              // bins of the candidates' histogram
+static_assert(kHistBins == kBins1, "the candidates' histogram lives in RowShared::hist");
+static_assert(kCandThreads == kRowThreads && kBlk == kRowThreads, "the rescue runs the one-workgroup algorithm");
+// Bin width of the candidates' histogram as a shift of the key.  From a sample T lies up to a fraction of an octave
+// above key_lo: the window is one octave (2^23 keys).  After a warm start key_lo is kWarmBelow keys (1/8 octave,
+// 8.3 %) below the previous T and the window half an octave, so a threshold between 0.92 and 1.3 times the
+// previous one is found by the first pass: narrower bins, fewer entries to rank.  A candidate costs little (an
+// 8-byte store), a failed guess a second pass over the row, hence the generous margin.
+constexpr uint32_t kShiftCold = 11, kShiftWarm = 10;
+constexpr uint32_t kWarmBelow = 1u << 20;
+constexpr int kTieCap = 1024;                // entries of T's bin that are ranked directly (one per thread)
+constexpr int kWarmSlots = 2;                // remembered thresholds per row (TopkArgs::warm = 1 .. kWarmSlots)
+enum CollectMode { kColdPass = 0, kWarmPass = 1, kSecondPass = 2 };
 
-struct RowInfo {
-    uint32_t failed, M;       // the estimate failed (see above); number of candidates
-    uint32_t bin_a, need_a;   // first digit of T - key_lo; entries still needed from that bin
-    uint32_t T, q;            // threshold key; number of entries equal to T to keep
-    uint32_t key_lo, pad;     // lower bound of the candidate keys (from collect)
+struct __attribute__((aligned(64))) RowInfo {     // one cache line per row
+    uint32_t key_lo, shift;       // lower bound of the candidate keys and bin width (first collect pass)
+    uint32_t key_lo2, shift2;     // ... of the second pass, valid if use2
+    uint32_t use2;                // the second pass redid this row: its histogram is hist_b
+    uint32_t warm_used;           // the first pass started from a remembered threshold
+    uint32_t failed;              // the row went to the exact one-workgroup algorithm
+    uint32_t bin_a, need_a;       // bin of T; entries still needed from that bin
+    uint32_t ntie;                // length of the tie list
+    uint32_t M;                   // candidates of the first pass (zero between calls)
+    uint32_t q;                   // number of entries equal to the threshold key T that are kept
+    uint32_t warm_T[kWarmSlots], warm_ok[kWarmSlots];   // thresholds T of earlier calls (the last call's: warm_T[0] if warm == 0)
 };
+static_assert(sizeof(RowInfo) == 64, "one cache line");
 
 struct Ws {
-    uint32_t *hist_a, *hist_b;            // [n][kBinsA], [n][kBinsB], kept zero between calls
+    uint32_t *hist_a, *hist_b;            // [n][kHistBins] each, kept zero between calls
     RowInfo *info;                        // [n]
-    uint32_t *slot_cnt, *slot_gt, *slot_eq;   // [n][nslot]
-    int32_t *cand_idx;                    // [n][nslot][L]
-    float *cand_val;
-    float *cand_new;                      // [n][nslot][L]  b + v of the candidate (new g_i entry if kept)
+    uint32_t *slot_cnt, *slot_above;      // [n][nslot] candidates of a slot; those in bins above T's
+    uint2 *tie;                           // [n][kTieCap] (position, key) of the candidates in T's bin
+    uint2 *cand;                          // [n][nslot][L] (position, value bits) of the candidates
     int64_t L;                            // entries per wavefront piece = slot capacity
     int64_t nslot;                        // pieces per row
     int64_t G;                            // collect workgroups per row
@@ -72,8 +85,7 @@ size_t align256(size_t b) { return (b + 255) / 256 * 256; }
 
 void plan(int32_t n, int64_t d, Ws *w) {
     // one 1024-thread workgroup per CU, two (in two rounds: the kernel's registers let one be resident) for inputs
-    // of 2^26 entries and more: measured on 20 x 10^6 (37.7 against 38.2 us per call) and 8 x 11.2 * 10^6 (168 against
-    // 162 us per collect pass)
+    // of 2^26 entries and more
     int64_t max_g = ((int64_t)n * d >= ((int64_t)1 << 26) ? 512 : 256) / n;
     if (max_g < 1) max_g = 1;
     if (max_g > kMaxSlots / kBlkWaves) max_g = kMaxSlots / kBlkWaves;
@@ -82,7 +94,8 @@ void plan(int32_t n, int64_t d, Ws *w) {
     if (g < 1) g = 1;
     const int64_t pieces = g * kBlkWaves;
     int64_t L = (d + pieces - 1) / pieces;
-    L = (L + 1023) / 1024 * 1024;            // whole load groups (4 steps of 64 lanes x 4 entries)
+    L = (L + 2047) / 2048 * 2048;            // whole load groups (4 steps of 64 lanes x 4 entries), and whole
+                                             // blocks of the aggregation's message index (256 or 2048 coordinates)
     w->L = L;
     w->nslot = (d + L - 1) / L;
     w->G = (w->nslot + kBlkWaves - 1) / kBlkWaves;
@@ -97,20 +110,21 @@ size_t layout(int32_t n, int64_t d, char *base, Ws *w) {
         off += align256(bytes);
         return p;
     };
-    char *h2 = take(sizeof(uint32_t) * (size_t)n * kBinsA);
-    char *h3 = take(sizeof(uint32_t) * (size_t)n * kBinsB);
+    // the leading part (histograms, row records) starts at zero: launch_topk_split_reset
+    char *ha = take(sizeof(uint32_t) * (size_t)n * kHistBins);
+    char *hb = take(sizeof(uint32_t) * (size_t)n * kHistBins);
     char *inf = take(sizeof(RowInfo) * (size_t)n);
     const size_t slots = sizeof(uint32_t) * (size_t)n * tmp.nslot;
-    char *s0 = take(slots), *s1 = take(slots), *s2 = take(slots);
-    char *ci = take(sizeof(int32_t) * (size_t)n * tmp.nslot * tmp.L);
-    char *cv = take(sizeof(float) * (size_t)n * tmp.nslot * tmp.L);
-    char *cn = take(sizeof(float) * (size_t)n * tmp.nslot * tmp.L);
+    char *s0 = take(slots), *s1 = take(slots);
+    char *tl = take(sizeof(uint2) * (size_t)n * kTieCap);
+    char *cd = take(sizeof(uint2) * (size_t)n * tmp.nslot * tmp.L);
     if (w) {
         *w = tmp;
-        w->hist_a = (uint32_t *)h2; w->hist_b = (uint32_t *)h3;
+        w->hist_a = (uint32_t *)ha; w->hist_b = (uint32_t *)hb;
         w->info = (RowInfo *)inf;
-        w->slot_cnt = (uint32_t *)s0; w->slot_gt = (uint32_t *)s1; w->slot_eq = (uint32_t *)s2;
-        w->cand_idx = (int32_t *)ci; w->cand_val = (float *)cv; w->cand_new = (float *)cn;
+        w->slot_cnt = (uint32_t *)s0; w->slot_above = (uint32_t *)s1;
+        w->tie = (uint2 *)tl;
+        w->cand = (uint2 *)cd;
     }
     return off;
 }
@@ -119,6 +133,34 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
     return v;
+}
+
+// Bin of a candidate key (key >= key_lo) in the candidates' histogram.
+__device__ __forceinline__ uint32_t bin_of(uint32_t key, uint32_t key_lo, uint32_t shift) {
+    const uint32_t b = (key - key_lo) >> shift;
+    return b < (uint32_t)kHistBins - 1u ? b : (uint32_t)kHistBins - 1u;
+}
+
+// exclusive prefix sum over the workgroup's threads; total returned through *total
+template <int THREADS>
+__device__ uint32_t cand_block_scan(uint32_t v, uint32_t *lds_wave /*[THREADS / 64]*/, uint32_t *total) {
+    const uint32_t incl = wave_inclusive_scan(v);
+    const int wave = threadIdx.x / kWave;
+    __syncthreads();                       // lds_wave may still be in use by a previous scan
+    if (lane_id() == kWave - 1) lds_wave[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+    for (int v2 = 0; v2 < THREADS / kWave; ++v2) {
+        const uint32_t t = lds_wave[v2];
+        if (v2 < wave) before += t;
+        all += t;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+__device__ void zero_global_hist(uint32_t *hist, int bins) {
+    for (int i = threadIdx.x; i < bins; i += blockDim.x) hist[i] = 0u;
 }
 
 // ---------------------------------------------------------------- collect
@@ -131,8 +173,8 @@ __device__ __forceinline__ uint32_t sample_rank(int64_t k, int64_t ns, int64_t d
     return (uint32_t)ceil(mu + 5.0 * sqrt(mu) + 8.0);
 }
 
-// Lower bound of the candidate keys, identical in every workgroup of a row (it depends on the data
-// only).  22 significant bits; 0 means "every entry is a candidate".
+// Lower bound of the candidate keys from the sample, identical in every workgroup of a row (it depends on
+// the data only).  22 significant bits; 0 means "every entry is a candidate".
 template <bool DIFF>
 __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b, int64_t d, int64_t k) {
     const int64_t ns = d < kSample ? d : kSample;
@@ -171,46 +213,43 @@ __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b
     return key_lo;
 }
 
-// Per-wavefront staging ring in LDS: candidates are appended here and leave for the slot in global
-// memory 64 at a time, as one full-width store per array, instead of as many scattered 4-byte stores.
-// With UPDATE a candidate also carries b + v, the value g_i takes at its position if it is kept.
+// Per-wavefront staging ring in LDS: candidates (position, value bits) are appended here and leave for the slot
+// in global memory 64 at a time, as one full-width 8-byte store, instead of as many scattered stores.
 constexpr uint32_t kRing = 128;              // entries of a staging ring (power of two, >= 128)
 struct StageRing {
-    int32_t idx[kRing];
-    float val[kRing];
-    float nxt[kRing];
+    uint2 e[kRing];
 };
 
-struct SlotPtrs {
-    int32_t *idx;
-    float *val;
-    float *nxt;
+// What a wavefront needs to classify and count candidates.
+struct CandFilter {
+    uint32_t key_lo, shift;
+    uint32_t *hist;          // the workgroup's LDS histogram
 };
 
-// Writes the entries [flushed, flushed + count) of the ring (count <= 64) to the slot.
-template <bool UPDATE>
+// Writes the entries [flushed, flushed + count) of the ring (count <= 64) to the slot and counts them into the
+// histogram (here, with all lanes busy, rather than where they are found, a few lanes at a time).
 __device__ __forceinline__ void ring_to_slot(const StageRing &ring, uint32_t flushed, uint32_t count, int lane,
-                                             const SlotPtrs &slot) {
+                                             uint2 *slot, const CandFilter &f) {
     if ((uint32_t)lane < count) {
-        slot.idx[flushed + lane] = ring.idx[(flushed + lane) & (kRing - 1)];
-        slot.val[flushed + lane] = ring.val[(flushed + lane) & (kRing - 1)];
-        if (UPDATE) slot.nxt[flushed + lane] = ring.nxt[(flushed + lane) & (kRing - 1)];
+        const uint2 rec = ring.e[(flushed + lane) & (kRing - 1)];
+        slot[flushed + lane] = rec;
+        atomicAdd(&f.hist[bin_of(rec.y & 0x7fffffffu, f.key_lo, f.shift)], 1u);
     }
 }
 
 // Appends the candidates among one step's entries (VEC per lane, lane-major order) to the slot.
-// FULL: every entry of the step lies inside the piece, no bounds checks.  bv: the subtracted values.
+// FULL: every entry of the step lies inside the piece, no bounds checks.
 // cnt = candidates so far, flushed = how many of them are already in global memory (cnt - flushed < 64
 // between calls; both are uniform over the wavefront).
-template <int VEC, bool FULL, bool UPDATE>
-__device__ __forceinline__ void append_candidates(const float (&v)[VEC], const float (&bv)[VEC], int64_t e0,
-                                                  int64_t hi, uint32_t key_lo, StageRing &ring, int lane,
-                                                  const SlotPtrs &slot, uint32_t &cnt, uint32_t &flushed) {
+template <int VEC, bool FULL>
+__device__ __forceinline__ void append_candidates(const float (&v)[VEC], int64_t e0, int64_t hi, const CandFilter &f,
+                                                  StageRing &ring, int lane, uint2 *slot, uint32_t &cnt,
+                                                  uint32_t &flushed) {
     bool c[VEC];
     uint32_t below = 0, all = 0;
 #pragma unroll
     for (int t = 0; t < VEC; ++t) {
-        c[t] = (FULL || e0 + t < hi) && mag_key(v[t]) >= key_lo;
+        c[t] = (FULL || e0 + t < hi) && mag_key(v[t]) >= f.key_lo;
         const uint64_t m = __ballot(c[t]);
         below += lanes_below(m);
         all += popc64(m);
@@ -218,13 +257,12 @@ __device__ __forceinline__ void append_candidates(const float (&v)[VEC], const f
     if (all == 0) return;
     uint32_t pos = cnt + below;
     if (all > 64) {        // a dense step would not fit the ring: drain it, then store directly
-        ring_to_slot<UPDATE>(ring, flushed, cnt - flushed, lane, slot);
+        ring_to_slot(ring, flushed, cnt - flushed, lane, slot, f);
 #pragma unroll
         for (int t = 0; t < VEC; ++t) {
             if (c[t]) {
-                slot.idx[pos] = (int32_t)(e0 + t);
-                slot.val[pos] = v[t];
-                if (UPDATE) slot.nxt[pos] = bv[t] + v[t];
+                slot[pos] = make_uint2((uint32_t)(e0 + t), __float_as_uint(v[t]));
+                atomicAdd(&f.hist[bin_of(mag_key(v[t]), f.key_lo, f.shift)], 1u);
                 ++pos;
             }
         }
@@ -235,56 +273,94 @@ __device__ __forceinline__ void append_candidates(const float (&v)[VEC], const f
 #pragma unroll
     for (int t = 0; t < VEC; ++t) {
         if (c[t]) {
-            ring.idx[pos & (kRing - 1)] = (int32_t)(e0 + t);
-            ring.val[pos & (kRing - 1)] = v[t];
-            if (UPDATE) ring.nxt[pos & (kRing - 1)] = bv[t] + v[t];
+            ring.e[pos & (kRing - 1)] = make_uint2((uint32_t)(e0 + t), __float_as_uint(v[t]));
             ++pos;
         }
     }
     cnt += all;
     if (cnt - flushed > kRing - 64) {        // keep room for the next step's candidates (at most 64)
         __builtin_amdgcn_wave_barrier();
-        ring_to_slot<UPDATE>(ring, flushed, 64, lane, slot);
+        ring_to_slot(ring, flushed, 64, lane, slot, f);
         flushed += 64;
     }
 }
 
 // Writes what is left in the ring at the end of a piece.
-template <bool UPDATE>
 __device__ __forceinline__ void drain_ring(const StageRing &ring, uint32_t flushed, uint32_t cnt, int lane,
-                                           const SlotPtrs &slot) {
+                                           uint2 *slot, const CandFilter &f) {
     __builtin_amdgcn_wave_barrier();
     for (; flushed < cnt; flushed += 64)
-        ring_to_slot<UPDATE>(ring, flushed, cnt - flushed < 64 ? cnt - flushed : 64, lane, slot);
+        ring_to_slot(ring, flushed, cnt - flushed < 64 ? cnt - flushed : 64, lane, slot, f);
 }
 
 // A wavefront walks its piece in steps of 64*VEC entries (VEC = 4 needs 16-byte aligned rows), four
 // steps per group.  Whole groups are loaded without any bounds check so that all loads of a group
 // are in flight together; only the last piece of a row has a checked tail.
-template <int VEC, bool DIFF, bool UPDATE>
+// MODE: kColdPass key_lo from the sample; kWarmPass from the threshold remembered in slot p.warm if there is
+// one, else from the sample; kSecondPass: only rows whose warm start failed, from the sample, into hist_b.
+template <int VEC, bool DIFF, int MODE>
 __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
-    static_assert(DIFF || !UPDATE, "the update needs the subtracted g_i");
     __shared__ RowShared s;
     __shared__ StageRing rings[kBlkWaves];
+    __shared__ uint32_t wg_total;
     const int64_t row = blockIdx.y, d = p.d;
     const float *a = p.a + row * d;
     const float *b = DIFF ? p.b + row * d : nullptr;
-    const uint32_t key_lo = estimate_key_lo<DIFF>(s, a, b, d, p.k);
-    if (blockIdx.x == 0 && threadIdx.x == 0) w.info[row].key_lo = key_lo;
+    RowInfo *info = w.info + row;
+    CandFilter f;
+    f.shift = kShiftCold;
+    f.hist = s.hist;
+    uint32_t *merged = w.hist_a + row * kHistBins;
+    uint32_t *row_total = &info->M;
+    if constexpr (MODE == kSecondPass) {
+        // The guess of the first pass held if it kept at least k candidates and the k-th largest of them lies
+        // inside the histogram's window, i.e. fewer than k fell into the last bin: then this pass ends here.
+        const uint32_t warm_used = info->warm_used, M = info->M, beyond = merged[kHistBins - 1];
+        if (!warm_used) return;                      // a cold first pass: what fails goes to the exact algorithm
+        if (M >= (uint32_t)p.k && beyond < (uint32_t)p.k) return;
+        f.key_lo = estimate_key_lo<DIFF>(s, a, b, d, p.k);
+        merged = w.hist_b + row * kHistBins;
+        row_total = nullptr;
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            info->key_lo2 = f.key_lo;
+            info->shift2 = f.shift;
+            info->use2 = 1u;
+        }
+    } else {
+        bool warm = false;
+        if constexpr (MODE == kWarmPass) warm = info->warm_ok[p.warm - 1] != 0u;
+        if (warm) {
+            const uint32_t T = info->warm_T[p.warm - 1];
+            f.key_lo = T > kWarmBelow ? T - kWarmBelow : 0u;
+            f.shift = kShiftWarm;
+        } else {
+            f.key_lo = estimate_key_lo<DIFF>(s, a, b, d, p.k);
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            info->key_lo = f.key_lo;
+            info->shift = f.shift;
+            info->use2 = 0u;
+            info->ntie = 0u;                 // the count kernel appends to the list
+            info->warm_used = warm ? 1u : 0u;
+        }
+    }
+    for (int i = threadIdx.x; i < kHistBins; i += kBlk) s.hist[i] = 0u;
+    if (threadIdx.x == 0) wg_total = 0u;
+    __syncthreads();
 
     const int wave = threadIdx.x / kWave, lane = lane_id();
-    const int64_t slot_no = (int64_t)blockIdx.x * kBlkWaves + wave;
-    if (slot_no < w.nslot) {
+    // the first pass has a wavefront per slot; the second pass, which seldom has work, runs on a small grid
+    for (int64_t slot_no = (int64_t)blockIdx.x * kBlkWaves + wave; slot_no < w.nslot;
+         slot_no += (int64_t)gridDim.x * kBlkWaves) {
         StageRing &ring = rings[wave];
         const int64_t lo = slot_no * w.L;
         const int64_t hi = lo + w.L < d ? lo + w.L : d;
-        const int64_t slot_at = (row * w.nslot + slot_no) * w.L;
-        const SlotPtrs slot{w.cand_idx + slot_at, w.cand_val + slot_at, w.cand_new + slot_at};
+        uint2 *slot = w.cand + (row * w.nslot + slot_no) * w.L;
         uint32_t cnt = 0, flushed = 0;
         constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
         int64_t base = lo;
         for (; base + kGroup <= hi; base += kGroup) {
-            float v[kUnroll][VEC], bv[kUnroll][VEC];
+            float v[kUnroll][VEC];
             if constexpr (VEC == 4) {
                 float4 va[kUnroll], vb[kUnroll];
 #pragma unroll
@@ -296,610 +372,329 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
                 for (int u = 0; u < kUnroll; ++u) {
                     v[u][0] = va[u].x; v[u][1] = va[u].y; v[u][2] = va[u].z; v[u][3] = va[u].w;
                     if constexpr (DIFF) {
-                        bv[u][0] = vb[u].x; bv[u][1] = vb[u].y; bv[u][2] = vb[u].z; bv[u][3] = vb[u].w;
+                        v[u][0] -= vb[u].x; v[u][1] -= vb[u].y; v[u][2] -= vb[u].z; v[u][3] -= vb[u].w;
                     }
                 }
             } else {
+                float vb[kUnroll];
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     v[u][0] = stream_load(a + base + u * kStep + lane);
-                    if constexpr (DIFF) bv[u][0] = stream_load(b + base + u * kStep + lane);
+                    if constexpr (DIFF) vb[u] = stream_load(b + base + u * kStep + lane);
+                }
+                if constexpr (DIFF) {
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u) v[u][0] -= vb[u];
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-#pragma unroll
-                for (int t = 0; t < VEC; ++t) {
-                    if constexpr (DIFF) v[u][t] -= bv[u][t];
-                    else bv[u][t] = 0.f;
-                }
-                append_candidates<VEC, true, UPDATE>(v[u], bv[u], base + u * kStep + lane * VEC, hi, key_lo, ring,
-                                                     lane, slot, cnt, flushed);
-            }
+            for (int u = 0; u < kUnroll; ++u)
+                append_candidates<VEC, true>(v[u], base + u * kStep + lane * VEC, hi, f, ring, lane, slot, cnt, flushed);
         }
         for (; base < hi; base += kStep) {           // checked tail, entry by entry
             const int64_t e0 = base + lane * VEC;
-            float v[VEC], bv[VEC];
+            float v[VEC];
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) {
-                v[t] = e0 + t < hi ? a[e0 + t] : 0.f;
-                bv[t] = DIFF && e0 + t < hi ? b[e0 + t] : 0.f;
-                v[t] -= bv[t];
-            }
-            append_candidates<VEC, false, UPDATE>(v, bv, e0, hi, key_lo, ring, lane, slot, cnt, flushed);
+            for (int t = 0; t < VEC; ++t) v[t] = e0 + t < hi ? load_v<DIFF>(a, b, e0 + t) : 0.f;
+            append_candidates<VEC, false>(v, e0, hi, f, ring, lane, slot, cnt, flushed);
         }
-        drain_ring<UPDATE>(ring, flushed, cnt, lane, slot);
-        if (lane == 0) w.slot_cnt[row * w.nslot + slot_no] = cnt;
+        drain_ring(ring, flushed, cnt, lane, slot, f);
+        if (lane == 0) {
+            w.slot_cnt[row * w.nslot + slot_no] = cnt;
+            atomicAdd(&wg_total, cnt);
+        }
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kHistBins; i += kBlk) {
+        const uint32_t c = s.hist[i];
+        if (c) atomicAdd(merged + i, c);
+    }
+    if (row_total && threadIdx.x == 0 && wg_total) atomicAdd(row_total, wg_total);
 }
 
-// ---------------------------------------------------------------- select (small k): one workgroup per row
-// Each wavefront owns a contiguous range of the row's slots, hence a contiguous range of the flat list
-// of candidates.  With W = the row's largest slot count rounded up to a power of two, a slot is cut into
-// units of min(W, 64) entries: one load instruction serves 64 / W slots if W < 64 (lane = slot * W +
-// entry) or one of the W / 64 steps of a slot otherwise; either way the lanes, the units of a batch and
-// the batches follow the candidate order, and kSlotBatch units are in flight together.  Rows with a slot
-// above kMaxUnitSlot candidates are walked slot by slot instead.
-constexpr int kSlotBatch = 8;
-constexpr uint32_t kMaxUnitSlot = 256;
+// ---------------------------------------------------------------- count
+// A wavefront of the count and emit kernels takes kSPW consecutive slots (one, or two where one would put more
+// than a workgroup on every compute unit).  The first kPre steps of 64 candidates
+// of each (clamped to the slot's capacity, a multiple of 1024) are loaded at the very start of the kernel, together
+// with everything else whose address does not depend on the prologue, so that a workgroup waits for memory once,
+// not once per step of its prologue.
+constexpr int kPre = 4;
 
-template <bool DIFF, bool UPDATE>
-__global__ __launch_bounds__(kBlk) void split_select_kernel(TopkArgs p, Ws w) {
-    __shared__ RowShared s;
-    __shared__ uint32_t off[kMaxSlots + 1];      // exclusive prefix of the slot counts
-    extern __shared__ uint32_t keys[];           // [kSelCap]
-    const int64_t row = blockIdx.x;
+// Grid (slot blocks + 1, n).  Prologue of every workgroup: T's bin from the row's histogram, and whether the row
+// failed (see the head of the file).  The last workgroup of a row is the rescue: it selects a failed row by the
+// exact one-workgroup algorithm on the original data (DIFF and UPDATE matter here only).  The others: a slot's
+// candidates in bins above T's are counted, those in T's bin go to the tie list.
+template <bool DIFF, bool UPDATE, int kSPW>
+__global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws w) {
+    constexpr int kWgSlots = kCandWaves * kSPW;      // slots per workgroup
+    __shared__ RowShared rs;
+    __shared__ uint32_t lds_wave[kCandWaves], lds_out[4];
+    const int64_t row = blockIdx.y;
     const int tid = threadIdx.x, wave = tid / kWave, lane = lane_id();
-    const int nslot = (int)w.nslot;
-    const uint32_t *slot_cnt = w.slot_cnt + row * w.nslot;
-
-    // exclusive scan of the slot counts (four consecutive slots per thread) and their maximum
-    constexpr int kPer = kMaxSlots / kBlk;
-    uint32_t c[kPer], mine = 0, largest = 0;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int sl = tid * kPer + j;
-        c[j] = sl < nslot ? slot_cnt[sl] : 0u;
-        mine += c[j];
-        largest = c[j] > largest ? c[j] : largest;
-    }
-    const uint32_t incl = wave_inclusive_scan(mine);
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) {
-        const uint32_t other = __shfl_xor(largest, o, kWave);
-        largest = other > largest ? other : largest;
-    }
-    if (lane == kWave - 1) s.wave_a[wave] = incl;
-    if (lane == 0) s.wave_b[wave] = largest;
-    __syncthreads();
-    uint32_t run = incl - mine;
-    for (int v = 0; v < wave; ++v) run += s.wave_a[v];
-    largest = 0;
-    for (int v = 0; v < kBlkWaves; ++v) largest = s.wave_b[v] > largest ? s.wave_b[v] : largest;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int sl = tid * kPer + j;
-        off[sl] = run;
-        run += c[j];
-    }
-    if (tid == kBlk - 1) off[kMaxSlots] = run;   // slots beyond nslot count as empty, so off[nslot] = M
-    __syncthreads();
-    const uint32_t M = off[nslot];
-    if (M < (uint32_t)p.k || M > (uint32_t)kSelCap) {    // estimate failed, or too many candidates for LDS
-        row_topk<DIFF, UPDATE>(s, p, row);
-        return;
-    }
-
-    const float *cand_val = w.cand_val + row * w.nslot * w.L;
-    const int32_t *cand_idx = w.cand_idx + row * w.nslot * w.L;
-    const float *cand_new = w.cand_new + row * w.nslot * w.L;
-    // this wavefront's slots [s0, s1) and candidates [lo, hi)
-    const int per_wave = (nslot + kBlkWaves - 1) / kBlkWaves;
-    const int s0 = wave * per_wave < nslot ? wave * per_wave : nslot;
-    const int s1 = s0 + per_wave < nslot ? s0 + per_wave : nslot;
-    const uint32_t lo = off[s0], hi = off[s1];
-    // the units (see above): either several slots per unit or several units per slot
-    uint32_t W = 1;
-    while (W < kMaxUnitSlot && W < largest) W <<= 1;
-    const int slots_per_unit = W < (uint32_t)kWave ? kWave / (int)W : 1;    // slots served by one unit
-    const int units_per_slot = W > (uint32_t)kWave ? (int)W / kWave : 1;    // units a slot is cut into
-    const int lanes_per_slot = W < (uint32_t)kWave ? (int)W : kWave;
-    const int my_slot = lane / lanes_per_slot;        // slot of this lane inside a unit
-    const uint32_t my_e = (uint32_t)(lane % lanes_per_slot);
-    const bool crowded = largest > kMaxUnitSlot;
-    const int n_units = (s1 - s0 + slots_per_unit - 1) / slots_per_unit * units_per_slot;
-    // unit t of this wavefront -> (slot, entry of this lane); slot >= s1 marks a lane without a slot
-    auto unit_slot = [&](int t) { return s0 + (t / units_per_slot) * slots_per_unit + my_slot; };
-    auto unit_entry = [&](int t) { return (uint32_t)(t % units_per_slot) * (uint32_t)kWave + my_e; };
-
-    // candidate keys into LDS
-    if (!crowded) {
-        for (int t0 = 0; t0 < n_units; t0 += kSlotBatch) {
-            float v[kSlotBatch];
-            uint32_t at_key[kSlotBatch];
-            bool in[kSlotBatch];
-#pragma unroll
-            for (int u = 0; u < kSlotBatch; ++u) {
-                const int sl = unit_slot(t0 + u);
-                const uint32_t j = unit_entry(t0 + u);
-                const int slc = sl < s1 ? sl : s1 - 1;
-                const uint32_t first = off[slc], cnt = off[slc + 1] - first;
-                in[u] = t0 + u < n_units && sl < s1 && j < cnt;
-                at_key[u] = first + j;
-                v[u] = cand_val[(int64_t)slc * w.L + (in[u] ? j : 0u)];     // clamped: no load behind a branch
-            }
-#pragma unroll
-            for (int u = 0; u < kSlotBatch; ++u)
-                if (in[u]) keys[at_key[u]] = mag_key(v[u]);
-        }
-    } else {
-        for (int sl = s0; sl < s1; ++sl) {
-            const uint32_t first = off[sl], cnt = off[sl + 1] - first;
-            for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSlotBatch) {
-                float v[kSlotBatch];
-#pragma unroll
-                for (int u = 0; u < kSlotBatch; ++u) {
-                    const uint32_t j = j0 + u * kWave + lane;
-                    v[u] = cand_val[(int64_t)sl * w.L + (j < cnt ? j : 0u)];
-                }
-#pragma unroll
-                for (int u = 0; u < kSlotBatch; ++u) {
-                    const uint32_t j = j0 + u * kWave + lane;
-                    if (j < cnt) keys[first + j] = mag_key(v[u]);
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-    // Radix select over the keys in LDS.  All candidates have key >= key_lo and the threshold lies a little above
-    // it, so the first digit is taken from key - key_lo (12 bits from bit 11, larger differences in the last bin):
-    // the candidates spread over hundreds of bins, where the leading bits of the keys themselves would put them
-    // all into a handful (LDS atomics on the same address are served one after the other).  Then either the
-    // bin's entries ranked against one another (at most kRankMax of them; their place in the candidate list is
-    // their order among equal keys) or the low 11 bits by a second histogram.  A threshold in the last bin
-    // (k tiny against the candidates) is found on the keys' own digits instead.
-    uint32_t prefix = 0, need = (uint32_t)p.k;
-    bool found = false;
-    {
-        const uint32_t key_lo = w.info[row].key_lo;
-        auto digit_a = [&](uint32_t key) {
-            const uint32_t rel = (key - key_lo) >> kBitsB;
-            return rel < (uint32_t)kBinsA - 1u ? rel : (uint32_t)kBinsA - 1u;
-        };
-        static_assert(kBinsA == kBins1, "the first relative digit uses the 12-bit histogram");
-        for (int i = tid; i < kBinsA; i += kBlk) s.hist[i] = 0u;
-        __syncthreads();
-        for (uint32_t j = tid; j < M; j += kBlk) atomicAdd(&s.hist[digit_a(keys[j])], 1u);
-        __syncthreads();
-        select_bin(s, kBinsA, need);
-        const uint32_t bin_a = s.bin, need_a = s.need, in_bin = s.hist[bin_a];
-        if (tid == 0) s.ncand = 0u;
-        if (tid < kRankMax) s.cand_rank[tid] = 0u;
-        __syncthreads();
-        if (bin_a != (uint32_t)kBinsA - 1u) {
-            found = true;
-            if (in_bin <= (uint32_t)kRankMax) {
-                for (uint32_t j = tid; j < M; j += kBlk) {
-                    const uint32_t key = keys[j];
-                    if (digit_a(key) == bin_a) {
-                        const uint32_t at = atomicAdd(&s.ncand, 1u);
-                        s.cand_key[at] = key;
-                        s.cand_idx[at] = j;
-                    }
-                }
-                __syncthreads();
-                rank_gathered(s, need_a);
-                prefix = s.bin;
-                need = s.need;
-            } else {
-                for (int i = tid; i < kBinsB; i += kBlk) s.hist[i] = 0u;
-                __syncthreads();
-                for (uint32_t j = tid; j < M; j += kBlk) {
-                    const uint32_t key = keys[j];
-                    if (digit_a(key) == bin_a) atomicAdd(&s.hist[(key - key_lo) & ((uint32_t)kBinsB - 1u)], 1u);
-                }
-                __syncthreads();
-                select_bin(s, kBinsB, need_a);
-                prefix = key_lo + ((bin_a << kBitsB) | s.bin);
-                need = s.need;
-            }
-            __syncthreads();
-        }
-    }
-    if (!found) {
-        const int shifts[3] = {kBits2 + kBits3, kBits3, 0};
-        const int pshifts[3] = {31, kBits2 + kBits3, kBits3};
-        const int bins[3] = {kBins1, kBins2, kBins3};
-        for (int pass = 0; pass < 3; ++pass) {
-            for (int i = tid; i < bins[pass]; i += kBlk) s.hist[i] = 0u;
-            __syncthreads();
-            for (uint32_t j = tid; j < M; j += kBlk) {
-                const uint32_t key = keys[j];
-                if ((key >> pshifts[pass]) == prefix) atomicAdd(&s.hist[(key >> shifts[pass]) & (bins[pass] - 1)], 1u);
-            }
-            __syncthreads();
-            select_bin(s, bins[pass], need);
-            prefix = (prefix << (pass == 0 ? 0 : (pass == 1 ? kBits2 : kBits3))) | s.bin;
-            need = s.need;
-            const uint32_t in_bin = s.hist[s.bin];
-            if (tid == 0) s.ncand = 0u;
-            if (tid < kRankMax) s.cand_rank[tid] = 0u;
-            __syncthreads();
-            if (pass == 0 && in_bin <= (uint32_t)kRankMax) {
-                for (uint32_t j = tid; j < M; j += kBlk) {
-                    const uint32_t key = keys[j];
-                    if ((key >> (kBits2 + kBits3)) == prefix) {
-                        const uint32_t at = atomicAdd(&s.ncand, 1u);
-                        s.cand_key[at] = key;
-                        s.cand_idx[at] = j;
-                    }
-                }
-                __syncthreads();
-                rank_gathered(s, need);
-                prefix = s.bin;
-                need = s.need;
-                break;
-            }
-        }
-    }
-    const uint32_t T = prefix, q = need;
-
-    // ordered emission: counts of this wavefront's range, prefix over the wavefronts ...
-    uint32_t n_gt = 0, n_eq = 0;
-    for (uint32_t base = lo; base < hi; base += kWave) {
-        const uint32_t j = base + lane;
-        const uint32_t key = j < hi ? keys[j] : 0u;
-        n_gt += popc64(__ballot(j < hi && key > T));
-        n_eq += popc64(__ballot(j < hi && key == T));
-    }
-    if (lane == 0) {
-        s.wave_a[wave] = n_gt;
-        s.wave_b[wave] = n_eq;
-    }
-    __syncthreads();
-    uint32_t gt_before = 0, eq_run = 0;
-    for (int v = 0; v < wave; ++v) {
-        gt_before += s.wave_a[v];
-        eq_run += s.wave_b[v];
-    }
-    uint32_t out_run = gt_before + (eq_run < q ? eq_run : q);
-    int32_t *out_idx = p.out_idx + row * p.k;
-    float *out_val = p.out_val + row * p.k;
-    float *g_row = UPDATE ? p.g_i + row * p.d : nullptr;
-    // one step of the emission over 64 lanes in candidate order; `in` marks lanes that hold a candidate
-    auto emit_step = [&](bool in, uint32_t key, int32_t e, float v, float nx) {
-        const bool gt = in && key > T, eq = in && key == T;
-        const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
-        const uint32_t eq_below = eq_run + lanes_below(m_eq);
-        const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
-        if (gt || (eq && eq_below < q)) {
-            const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
-            out_idx[pos] = e;
-            out_val[pos] = v;
-            if (UPDATE) g_row[e] = nx;          // Algorithm 2, line 6
-        }
-        const uint32_t eq_next = eq_run + popc64(m_eq);
-        out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
-        eq_run = eq_next;
-    };
-    // ... then the slots in order: (position, value[, new g_i entry]) of a whole batch are loaded, then the
-    // kept ones written
-    if (!crowded) {
-        for (int t0 = 0; t0 < n_units; t0 += kSlotBatch) {
-            int32_t e[kSlotBatch];
-            float v[kSlotBatch], nx[kSlotBatch];
-            uint32_t key[kSlotBatch];
-            bool in[kSlotBatch];
-#pragma unroll
-            for (int u = 0; u < kSlotBatch; ++u) {
-                const int sl = unit_slot(t0 + u);
-                const uint32_t j = unit_entry(t0 + u);
-                const int slc = sl < s1 ? sl : s1 - 1;
-                const uint32_t first = off[slc], cnt = off[slc + 1] - first;
-                in[u] = t0 + u < n_units && sl < s1 && j < cnt;
-                const int64_t at = (int64_t)slc * w.L + (in[u] ? j : 0u);
-                e[u] = cand_idx[at];
-                v[u] = cand_val[at];
-                nx[u] = UPDATE ? cand_new[at] : 0.f;
-                key[u] = in[u] ? keys[first + j] : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < kSlotBatch; ++u) emit_step(in[u], key[u], e[u], v[u], nx[u]);
-        }
-    } else {
-        for (int sl = s0; sl < s1; ++sl) {
-            const uint32_t first = off[sl], cnt = off[sl + 1] - first;
-            for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSlotBatch) {
-                int32_t e[kSlotBatch];
-                float v[kSlotBatch], nx[kSlotBatch];
-#pragma unroll
-                for (int u = 0; u < kSlotBatch; ++u) {
-                    const uint32_t j = j0 + u * kWave + lane;
-                    const int64_t at = (int64_t)sl * w.L + (j < cnt ? j : 0u);
-                    e[u] = cand_idx[at];
-                    v[u] = cand_val[at];
-                    nx[u] = UPDATE ? cand_new[at] : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < kSlotBatch; ++u) {
-                    const uint32_t j = j0 + u * kWave + lane;
-                    emit_step(j < cnt, j < cnt ? keys[first + j] : 0u, e[u], v[u], nx[u]);
-                }
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------- candidate stages (large k)
-// exclusive prefix sum over the workgroup's threads; total returned through *total
-template <int THREADS>
-__device__ uint32_t cand_block_scan(uint32_t v, uint32_t *lds_wave /*[THREADS / 64]*/, uint32_t *total) {
-    const uint32_t incl = wave_inclusive_scan(v);
-    const int wave = threadIdx.x / kWave;
-    __syncthreads();                       // lds_wave may still be in use by a previous scan
-    if (lane_id() == kWave - 1) lds_wave[wave] = incl;
-    __syncthreads();
-    uint32_t before = 0, all = 0;
-    for (int v2 = 0; v2 < THREADS / kWave; ++v2) {
-        const uint32_t t = lds_wave[v2];
-        if (v2 < wave) before += t;
-        all += t;
-    }
-    *total = all;
-    return before + incl - v;
-}
-
-// Digit selection over the row's merged histogram (written by the previous kernel): largest bin b
-// with count(bins > b) < need <= count(bins >= b).  lds_out[0] = b, lds_out[1] = need - count(bins > b).
-template <int NBINS, int THREADS>
-__device__ void select_digit(const uint32_t *hist, uint32_t need, uint32_t *lds_wave, uint32_t *lds_out) {
-    constexpr int PER = NBINS >= THREADS ? NBINS / THREADS : 1;      // bins per thread, walked from the top
-    static_assert(NBINS % PER == 0 && NBINS / PER <= THREADS, "histogram must divide over the workgroup");
-    const bool active = (int)threadIdx.x < NBINS / PER;
+    RowInfo *info = w.info + row;
+    const bool rescue = blockIdx.x == gridDim.x - 1;
+    const int64_t sl_first = rescue ? 0 : (int64_t)blockIdx.x * kWgSlots + wave * kSPW;
+    // everything whose address is known now
+    const RowInfo ri = *info;
+    constexpr int PER = kHistBins / kCandThreads;
     uint32_t h[PER];
-    uint32_t mine = 0;
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        h[j] = active ? hist[NBINS - 1 - ((int)threadIdx.x * PER + j)] : 0u;
-        mine += h[j];
+    for (int j = 0; j < PER; ++j) h[j] = w.hist_a[row * kHistBins + kHistBins - 1 - (tid * PER + j)];
+    uint32_t cnt[kSPW];
+    const uint2 *slot[kSPW];
+    uint2 c[kSPW][kPre];
+#pragma unroll
+    for (int s = 0; s < kSPW; ++s) {
+        const bool active = !rescue && sl_first + s < w.nslot;
+        const int64_t slc = active ? sl_first + s : 0;
+        cnt[s] = w.slot_cnt[row * w.nslot + slc];
+        slot[s] = w.cand + (row * w.nslot + slc) * w.L;
+#pragma unroll
+        for (int q = 0; q < kPre; ++q) c[s][q] = slot[s][q * kWave + lane];
+        if (!active) cnt[s] = 0u;
     }
-    uint32_t total;
-    const uint32_t above = cand_block_scan<THREADS>(mine, lds_wave, &total);
-    if (active && above < need && need <= above + mine) {
-        uint32_t c = above;
+
+    const bool second = ri.use2 != 0u;
+    const uint32_t key_lo = second ? ri.key_lo2 : ri.key_lo, shift = second ? ri.shift2 : ri.shift;
+    if (second) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) h[j] = w.hist_b[row * kHistBins + kHistBins - 1 - (tid * PER + j)];
+    }
+    // T's bin: the largest bin b with count(bins > b) < k <= count(bins >= b)
+    uint32_t mine = 0, total;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) mine += h[j];
+    const uint32_t higher = cand_block_scan<kCandThreads>(mine, lds_wave, &total);
+    const uint32_t need = (uint32_t)p.k;
+    if (higher < need && need <= higher + mine) {         // exactly one thread, if total >= k
+        uint32_t run = higher;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-            if (need > c && need <= c + h[j]) {
-                lds_out[0] = (uint32_t)(NBINS - 1 - ((int)threadIdx.x * PER + j));
-                lds_out[1] = need - c;
+            if (need > run && need <= run + h[j]) {
+                lds_out[0] = (uint32_t)(kHistBins - 1 - (tid * PER + j));
+                lds_out[1] = need - run;
+                lds_out[2] = h[j];
             }
-            c += h[j];
+            run += h[j];
         }
     }
     __syncthreads();
-}
-
-__device__ void zero_global_hist(uint32_t *hist, int bins) {
-    for (int i = threadIdx.x; i < bins; i += blockDim.x) hist[i] = 0u;
-}
-
-// Digit STAGE (1 or 2) of the radix select over the candidates' key - key_lo, kCandBlocks workgroups per
-// row (few, so that the merge below costs a few atomics per bin).  Prologue: stage 1 adds up the slot
-// counts (fewer than k candidates: the estimate failed); stage 2 selects the first digit from the merged
-// histogram (the last bin, which also holds every key beyond the window, cannot be resolved: failed).
-// Body: LDS histogram of this stage's digit over the workgroup's slots, four slots in flight per
-// wavefront, then merged into the row's global histogram.
-// A failed row is left alone by the later kernels, except for one extra workgroup of the count kernel
-// that selects it by the exact one-workgroup algorithm on the original data.
-template <int STAGE>
-__global__ __launch_bounds__(kHistThreads) void cand_hist_kernel(TopkArgs p, Ws w) {
-    static_assert(STAGE == 1 || STAGE == 2, "two digits");
-    constexpr int NB = STAGE == 1 ? kBinsA : kBinsB;
-    __shared__ uint32_t hist[NB];
-    __shared__ uint32_t lds_wave[kHistThreads / kWave], lds_out[2];
-    const int64_t row = blockIdx.y;
-    const int wave = threadIdx.x / kWave, lane = lane_id();
-    RowInfo *info = w.info + row;
-    const uint32_t *slot_cnt = w.slot_cnt + row * w.nslot;
-    const uint32_t key_lo = info->key_lo;
-    uint32_t bin_a = 0;
-    if constexpr (STAGE == 1) {
-        uint32_t mine = 0, M;
-        for (int64_t sl = threadIdx.x; sl < w.nslot; sl += kHistThreads) mine += slot_cnt[sl];
-        (void)cand_block_scan<kHistThreads>(mine, lds_wave, &M);
-        const bool failed = M < (uint32_t)p.k;
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            info->failed = failed ? 1u : 0u;
-            info->M = M;
-        }
-        if (failed) return;
-    } else {
-        if (info->failed) return;
-        select_digit<kBinsA, kHistThreads>(w.hist_a + row * kBinsA, (uint32_t)p.k, lds_wave, lds_out);
+    bool failed = total < need;                                        // fewer than k candidates
+    uint32_t bin_a = 0, need_a = 0;
+    if (!failed) {
         bin_a = lds_out[0];
-        const bool failed = bin_a == (uint32_t)kBinsA - 1u;
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            info->bin_a = bin_a;
-            info->need_a = lds_out[1];
-            if (failed) info->failed = 1u;
-        }
-        if (failed) return;
+        need_a = lds_out[1];
+        failed = bin_a == (uint32_t)kHistBins - 1u || lds_out[2] > (uint32_t)kTieCap;   // beyond the window; crowded
     }
-    for (int i = threadIdx.x; i < NB; i += kHistThreads) hist[i] = 0u;
-    __syncthreads();
-    // kInFlight slots of the wavefront at a time, kSteps steps of 64 candidates of each: all loads of such a
-    // round are issued before the first is used (a slot usually holds fewer than kSteps * 64 candidates)
-    constexpr int kInFlight = 8, kSteps = 4;
-    const int64_t stride = (int64_t)kCandBlocks * (kHistThreads / kWave);
-    for (int64_t sl0 = (int64_t)blockIdx.x * (kHistThreads / kWave) + wave; sl0 < w.nslot; sl0 += stride * kInFlight) {
-        uint32_t cnt[kInFlight], most = 0;
-        const float *val[kInFlight];
-#pragma unroll
-        for (int u = 0; u < kInFlight; ++u) {
-            const int64_t sl = sl0 + u * stride;
-            cnt[u] = sl < w.nslot ? slot_cnt[sl] : 0u;
-            val[u] = w.cand_val + (row * w.nslot + (sl < w.nslot ? sl : 0)) * w.L;
-            most = cnt[u] > most ? cnt[u] : most;
-        }
-        for (uint32_t j0 = 0; j0 < most; j0 += kWave * kSteps) {
-            float v[kSteps][kInFlight];
-#pragma unroll
-            for (int q = 0; q < kSteps; ++q)
-#pragma unroll
-                for (int u = 0; u < kInFlight; ++u) {
-                    const uint32_t j = j0 + q * kWave + lane;
-                    v[q][u] = val[u][j < cnt[u] ? j : 0u];            // clamped: no load behind a branch
-                }
-#pragma unroll
-            for (int q = 0; q < kSteps; ++q)
-#pragma unroll
-                for (int u = 0; u < kInFlight; ++u) {
-                    const uint32_t j = j0 + q * kWave + lane;
-                    if (j >= cnt[u]) continue;
-                    const uint32_t rel = mag_key(v[q][u]) - key_lo;       // candidates have key >= key_lo
-                    const uint32_t a = rel >> kBitsB < (uint32_t)kBinsA - 1u ? rel >> kBitsB : (uint32_t)kBinsA - 1u;
-                    if (STAGE == 1) atomicAdd(&hist[a], 1u);
-                    else if (a == bin_a) atomicAdd(&hist[rel & (kBinsB - 1)], 1u);
-                }
-        }
-    }
-    __syncthreads();
-    uint32_t *merged = STAGE == 1 ? w.hist_a + row * kBinsA : w.hist_b + row * kBinsB;
-    for (int b = threadIdx.x; b < NB; b += kHistThreads) {
-        const uint32_t c = hist[b];
-        if (c) atomicAdd(merged + b, c);
-    }
-}
-
-// One wavefront per slot.  Prologue: threshold key T and tie quota q from the third digit's
-// histogram.  Body: the slot's number of candidates above T and equal to T.
-template <bool DIFF, bool UPDATE>
-__global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws w) {
-    static_assert(kCandThreads == kRowThreads, "the rescue workgroup runs the one-workgroup algorithm");
-    __shared__ RowShared rs;
-    __shared__ uint32_t lds_wave[kCandWaves], lds_out[2];
-    const int64_t row = blockIdx.y;
-    const int wave = threadIdx.x / kWave, lane = lane_id();
-    RowInfo *info = w.info + row;
-    if (blockIdx.x == gridDim.x - 1) {               // the rescue workgroup (DIFF, UPDATE matter here only)
-        if (info->failed) {
-            zero_global_hist(w.hist_a + row * kBinsA, kBinsA);     // left behind if stage 2 declared the failure
+    if (rescue) {
+        if (failed) {
             row_topk<DIFF, UPDATE>(rs, p, row);
+            if (p.agg_start) {                  // the message index of this row, from the pairs just written
+                __syncthreads();
+                const int32_t *out = p.out_idx + row * p.k;
+                int32_t *start = p.agg_start + row * (p.agg_nblk + 1);
+                for (int64_t at = tid; at < p.k; at += kCandThreads) {
+                    const int64_t b_cur = out[at] >> p.agg_shift;
+                    const int64_t b_prev = at > 0 ? out[at - 1] >> p.agg_shift : -1;
+                    for (int64_t b = b_prev + 1; b <= b_cur; ++b) start[b] = (int32_t)at;
+                    if (at == p.k - 1)
+                        for (int64_t b = b_cur + 1; b <= p.agg_nblk; ++b) start[b] = (int32_t)p.k;
+                }
+            }
         }
         return;
     }
-    if (info->failed) return;
-    select_digit<kBinsB, kCandThreads>(w.hist_b + row * kBinsB, info->need_a, lds_wave, lds_out);
-    const uint32_t T = info->key_lo + ((info->bin_a << kBitsB) | lds_out[0]);
-    if (blockIdx.x == 0) {
-        if (threadIdx.x == 0) {
-            info->T = T;
-            info->q = lds_out[1];
-        }
-        zero_global_hist(w.hist_a + row * kBinsA, kBinsA);     // consumed by stage 2
+    if (blockIdx.x == 0 && tid == 0) {
+        info->failed = failed ? 1u : 0u;
+        info->bin_a = bin_a;
+        info->need_a = need_a;
+        info->M = 0u;                        // consumed by the second collect pass: zero for the next call
+        if (failed && p.warm > 0) info->warm_ok[p.warm - 1] = 0u;
     }
-    const int64_t sl = (int64_t)blockIdx.x * kCandWaves + wave;
-    if (sl >= w.nslot) return;
-    const uint32_t cnt = w.slot_cnt[row * w.nslot + sl];
-    const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
-    uint32_t n_gt = 0, n_eq = 0;
-    constexpr int kSteps = 4;
-    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSteps) {
-        float v[kSteps];
+    if (failed) return;
+    uint2 *tie = w.tie + row * kTieCap;
 #pragma unroll
-        for (int q = 0; q < kSteps; ++q) {
-            const uint32_t j = j0 + q * kWave + lane;
-            v[q] = slot_val[j < cnt ? j : 0u];
-        }
+    for (int s = 0; s < kSPW; ++s) {
+        uint32_t above = 0;
+        for (uint32_t j0 = 0; j0 < cnt[s]; j0 += kWave * kPre) {
+            if (j0 > 0) {
 #pragma unroll
-        for (int q = 0; q < kSteps; ++q) {
-            const uint32_t j = j0 + q * kWave + lane;
-            const uint32_t key = mag_key(v[q]);
-            n_gt += popc64(__ballot(j < cnt && key > T));
-            n_eq += popc64(__ballot(j < cnt && key == T));
+                for (int q = 0; q < kPre; ++q) {
+                    const uint32_t j = j0 + q * kWave + lane;
+                    c[s][q] = slot[s][j < cnt[s] ? j : 0u];       // clamped: no load behind a branch
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kPre; ++q) {
+                const uint32_t j = j0 + q * kWave + lane;
+                const uint32_t key = c[s][q].y & 0x7fffffffu;
+                const uint32_t bin = bin_of(key < key_lo ? key_lo : key, key_lo, shift);
+                above += popc64(__ballot(j < cnt[s] && bin > bin_a));
+                const bool in_bin = j < cnt[s] && bin == bin_a;
+                const uint32_t at = wave_append(in_bin, &info->ntie);
+                if (in_bin && at < (uint32_t)kTieCap) tie[at] = make_uint2(c[s][q].x, key);
+            }
         }
-    }
-    if (lane == 0) {
-        w.slot_gt[row * w.nslot + sl] = n_gt;
-        w.slot_eq[row * w.nslot + sl] = n_eq;
+        if (lane == 0 && sl_first + s < w.nslot) w.slot_above[row * w.nslot + sl_first + s] = above;
     }
 }
 
-// Ordered emission, one wavefront per slot.  The workgroup first adds up the counts of all slots of its
-// row before its own (at most kMaxSlots of them), which gives its output offset and the number of ties
-// already used; a wavefront then adds the counts of the workgroup's earlier slots.
-template <bool UPDATE>
+// ---------------------------------------------------------------- emit
+// Ordered emission.  Prologue of every workgroup: the tie list ranked (larger key first, lower position first
+// among equal keys): the entry that need_a - 1 others precede is the last one kept, its key is T, and q counts it
+// and the equal keys before it.  The output offset of a slot is the number of kept entries in all earlier slots:
+// their candidates above T's bin (slot_above, summed by the workgroup) plus the listed entries before the slot's
+// first position that are kept.
+template <bool DIFF, bool UPDATE, int kSPW>
 __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws w) {
-    __shared__ uint32_t before_gt[kCandWaves], before_eq[kCandWaves], own_gt[kCandWaves], own_eq[kCandWaves];
+    constexpr int kWgSlots = kCandWaves * kSPW;      // slots per workgroup
+    __shared__ uint32_t before_above[kCandWaves], own_above[kCandWaves];
+    __shared__ uint32_t tie_key[kTieCap], tie_idx[kTieCap];
+    __shared__ uint32_t sh_T, sh_q;
+    static_assert(kTieCap <= kCandThreads, "one listed entry per thread");
     const int64_t row = blockIdx.y;
-    const int wave = threadIdx.x / kWave, lane = lane_id();
-    const RowInfo *info = w.info + row;
-    if (info->failed) return;                                                     // the whole workgroup
-    if (blockIdx.x == 0) zero_global_hist(w.hist_b + row * kBinsB, kBinsB);       // consumed by count
-    const int64_t sl0 = (int64_t)blockIdx.x * kCandWaves, sl = sl0 + wave;
-    const bool active = sl < w.nslot;
-    const uint32_t T = info->T, q = info->q;
-    const uint32_t *slot_gt = w.slot_gt + row * w.nslot, *slot_eq = w.slot_eq + row * w.nslot;
-    uint32_t gt_part = 0, eq_part = 0;
-    for (int64_t t = threadIdx.x; t < sl0; t += kCandThreads) {
-        gt_part += slot_gt[t];
-        eq_part += slot_eq[t];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = lane_id();
+    RowInfo *info = w.info + row;
+    const int64_t sl0 = (int64_t)blockIdx.x * kWgSlots, sl_first = sl0 + wave * kSPW;
+    // everything whose address is known now
+    const RowInfo ri = *info;
+    const uint2 listed = w.tie[row * kTieCap + (tid < kTieCap ? tid : 0)];
+    const uint32_t *slot_above = w.slot_above + row * w.nslot;
+    uint32_t part = 0;
+    for (int64_t t = tid; t < sl0; t += kCandThreads) part += slot_above[t];
+    uint32_t mine = 0, cnt[kSPW];
+    const uint2 *slot[kSPW];
+    uint2 c[kSPW][kPre];
+#pragma unroll
+    for (int s = 0; s < kSPW; ++s) {
+        const bool active = sl_first + s < w.nslot;
+        const int64_t slc = active ? sl_first + s : 0;
+        mine += active ? slot_above[slc] : 0u;
+        cnt[s] = w.slot_cnt[row * w.nslot + slc];
+        slot[s] = w.cand + (row * w.nslot + slc) * w.L;
+#pragma unroll
+        for (int q = 0; q < kPre; ++q) c[s][q] = slot[s][q * kWave + lane];
+        if (!active) cnt[s] = 0u;
     }
-    const uint32_t mine_gt = active ? slot_gt[sl] : 0u, mine_eq = active ? slot_eq[sl] : 0u;
-    const uint32_t cnt = active ? w.slot_cnt[row * w.nslot + sl] : 0u;
-    gt_part = wave_sum_u32(gt_part);
-    eq_part = wave_sum_u32(eq_part);
-    if (lane == 0) {
-        before_gt[wave] = gt_part;
-        before_eq[wave] = eq_part;
-        own_gt[wave] = mine_gt;
-        own_eq[wave] = mine_eq;
+
+    if (blockIdx.x == 0) {                       // the histograms are consumed: zero for the next call
+        zero_global_hist(w.hist_a + row * kHistBins, kHistBins);
+        if (ri.use2 != 0u) zero_global_hist(w.hist_b + row * kHistBins, kHistBins);
+    }
+    if (ri.failed) return;                                                        // the whole workgroup
+    const uint32_t ntie = ri.ntie < (uint32_t)kTieCap ? ri.ntie : (uint32_t)kTieCap;
+    const uint32_t my_idx = listed.x, my_key = listed.y;
+    if ((uint32_t)tid < ntie) {
+        tie_idx[tid] = my_idx;
+        tie_key[tid] = my_key;
     }
     __syncthreads();
-    if (!active) return;
-    uint32_t gt_run = 0, eq_run = 0;
-    for (int v = 0; v < kCandWaves; ++v) {
-        gt_run += before_gt[v] + (v < wave ? own_gt[v] : 0u);
-        eq_run += before_eq[v] + (v < wave ? own_eq[v] : 0u);
+    if ((uint32_t)tid < ntie) {
+        uint32_t larger = 0, equal_before = 0;
+        for (uint32_t j = 0; j < ntie; ++j) {
+            const uint32_t kj = tie_key[j], ij = tie_idx[j];
+            larger += kj > my_key ? 1u : 0u;
+            equal_before += (kj == my_key && ij < my_idx) ? 1u : 0u;
+        }
+        if (larger + equal_before == ri.need_a - 1u) {       // exactly one thread
+            sh_T = my_key;
+            sh_q = equal_before + 1u;
+        }
     }
+    __syncthreads();
+    const uint32_t T = sh_T, q = sh_q;
+    if (blockIdx.x == 0 && tid == 0) {
+        info->q = q;
+        const int mem = p.warm > 0 ? p.warm - 1 : 0;
+        info->warm_T[mem] = T;
+        info->warm_ok[mem] = p.warm > 0 ? 1u : 0u;
+    }
+
+    part = wave_sum_u32(part);
+    // listed entries before this wavefront's first position: kept ones above T, and ties
+    const uint32_t my_lo = (uint32_t)(sl_first * w.L);
+    uint32_t list_gt = 0, list_eq = 0;
+    for (uint32_t j = lane; j < ntie; j += kWave) {
+        const uint32_t kj = tie_key[j];
+        if (tie_idx[j] < my_lo) {
+            list_gt += kj > T ? 1u : 0u;
+            list_eq += kj == T ? 1u : 0u;
+        }
+    }
+    list_gt = wave_sum_u32(list_gt);
+    list_eq = wave_sum_u32(list_eq);
+    if (lane == 0) {
+        before_above[wave] = part;
+        own_above[wave] = mine;
+    }
+    __syncthreads();
+    if (sl_first >= w.nslot) return;
+    uint32_t gt_run = list_gt, eq_run = list_eq;
+    for (int v = 0; v < kCandWaves; ++v) gt_run += before_above[v] + (v < wave ? own_above[v] : 0u);
     uint32_t out_run = gt_run + (eq_run < q ? eq_run : q);
-    const int32_t *slot_idx = w.cand_idx + (row * w.nslot + sl) * w.L;
-    const float *slot_val = w.cand_val + (row * w.nslot + sl) * w.L;
-    const float *slot_new = w.cand_new + (row * w.nslot + sl) * w.L;
     int32_t *out_idx = p.out_idx + row * p.k;
     float *out_val = p.out_val + row * p.k;
-    constexpr int kSteps = 4;
-    for (uint32_t j0 = 0; j0 < cnt; j0 += kWave * kSteps) {
-        float v[kSteps], nx[kSteps];
-        int32_t e[kSteps];
+    // The aggregation's message index (see aggregate_index_shift): start[b] = output position of the first kept
+    // entry at or beyond coordinate b << shift.  A slot is a whole number of blocks, so every block begins inside
+    // exactly one wavefront's span, and that wavefront writes its start: when it keeps the first entry at or beyond
+    // the block's first coordinate, or at the end of its span for the blocks that follow its last kept entry.
+    int32_t *agg_start = p.agg_start ? p.agg_start + row * (p.agg_nblk + 1) : nullptr;
+    int64_t last_b = ((sl_first * w.L) >> p.agg_shift) - 1;      // blocks up to here have their start
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
-            const uint32_t j = j0 + s * kWave + lane;
-            const uint32_t jc = j < cnt ? j : 0u;                // clamped: no load behind a branch
-            v[s] = slot_val[jc];
-            e[s] = slot_idx[jc];
-            nx[s] = UPDATE ? slot_new[jc] : 0.f;
-        }
+    for (int s = 0; s < kSPW; ++s) {             // consecutive slots: the running offsets carry over
+        for (uint32_t j0 = 0; j0 < cnt[s]; j0 += kWave * kPre) {
+            if (j0 > 0) {
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
-            const uint32_t j = j0 + s * kWave + lane;
-            const bool in = j < cnt;
-            const uint32_t key = mag_key(v[s]);
-            const bool gt = in && key > T, eq = in && key == T;
-            const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
-            const uint32_t eq_below = eq_run + lanes_below(m_eq);
-            const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
-            if (gt || (eq && eq_below < q)) {
-                const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
-                out_idx[pos] = e[s];
-                out_val[pos] = v[s];
-                if (UPDATE) (p.g_i + row * p.d)[e[s]] = nx[s];   // Algorithm 2, line 6
+                for (int u = 0; u < kPre; ++u) {
+                    const uint32_t j = j0 + u * kWave + lane;
+                    c[s][u] = slot[s][j < cnt[s] ? j : 0u];      // clamped: no load behind a branch
+                }
             }
-            const uint32_t eq_next = eq_run + popc64(m_eq);
-            out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
-            eq_run = eq_next;
+#pragma unroll
+            for (int u = 0; u < kPre; ++u) {
+                const uint32_t j = j0 + u * kWave + lane;
+                const bool in = j < cnt[s];
+                const uint2 cu = c[s][u];
+                const uint32_t key = cu.y & 0x7fffffffu;
+                const bool gt = in && key > T, eq = in && key == T;
+                const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
+                const uint32_t eq_below = eq_run + lanes_below(m_eq);
+                const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
+                const bool keep = gt || (eq && eq_below < q);
+                const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
+                if (keep) {
+                    const float v = __uint_as_float(cu.y);
+                    out_idx[pos] = (int32_t)cu.x;
+                    out_val[pos] = v;
+                    if constexpr (UPDATE) {                      // Algorithm 2, line 6
+                        const int64_t at = row * p.d + (int64_t)cu.x;
+                        p.g_i[at] = (DIFF ? p.b[at] : 0.f) + v;
+                    }
+                }
+                if (agg_start) {
+                    const uint64_t m_keep = __ballot(keep);
+                    if (m_keep) {
+                        const int64_t b_cur = (int64_t)(cu.x >> p.agg_shift);
+                        const uint64_t lower = m_keep & ((1ull << lane) - 1ull);
+                        const int prev_lane = lower ? 63 - __clzll((long long)lower) : 0;
+                        const int64_t b_before = __shfl(b_cur, prev_lane, kWave);
+                        const int64_t b_prev = lower ? b_before : last_b;
+                        if (keep)
+                            for (int64_t b = b_prev + 1; b <= b_cur; ++b) agg_start[b] = (int32_t)pos;
+                        last_b = __shfl(b_cur, 63 - __clzll((long long)m_keep), kWave);
+                    }
+                }
+                const uint32_t eq_next = eq_run + popc64(m_eq);
+                out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
+                eq_run = eq_next;
+            }
         }
+    }
+    if (agg_start) {      // blocks of this span after its last kept entry (all of them if it kept nothing)
+        int64_t span_end = (sl_first + kSPW) * w.L;
+        span_end = span_end < p.d ? span_end : p.d;
+        const int64_t b_last = ((span_end - 1) >> p.agg_shift) + (span_end == p.d ? 1 : 0);   // the row's end: start[nblk]
+        for (int64_t b = last_b + 1 + lane; b <= b_last; b += kWave) agg_start[b] = (int32_t)out_run;
     }
 }
 
@@ -908,23 +703,24 @@ __global__ __launch_bounds__(kCandThreads) void zero_words_kernel(uint32_t *p, s
     for (size_t i = (size_t)blockIdx.x * kCandThreads + threadIdx.x; i < words; i += stride) p[i] = 0u;
 }
 
-template <int VEC, bool DIFF, bool UPDATE>
-void launch_collect(const TopkArgs &p, const Ws &w, hipStream_t stream) {
-    hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, UPDATE>), dim3((unsigned)w.G, (unsigned)p.n), dim3(kBlk), 0,
-                       stream, p, w);
+template <int VEC, bool DIFF>
+void launch_collect(const TopkArgs &p, const Ws &w, int mode, hipStream_t stream) {
+    // the second pass has work only after a failed guess: about 64 workgroups, which loop over the slots
+    int64_t g = w.G;
+    if (mode == kSecondPass) g = std::max<int64_t>(1, std::min<int64_t>(w.G, 64 / p.n));
+    const dim3 grid((unsigned)g, (unsigned)p.n), block(kBlk);
+    if (mode == kColdPass) hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kColdPass>), grid, block, 0, stream, p, w);
+    else if (mode == kWarmPass) hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kWarmPass>), grid, block, 0, stream, p, w);
+    else hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kSecondPass>), grid, block, 0, stream, p, w);
 }
 
-template <bool DIFF, bool UPDATE>
-hipError_t launch_select(const TopkArgs &p, const Ws &w, hipStream_t stream) {
-    constexpr size_t kDyn = sizeof(uint32_t) * kSelCap;
-    static PerDeviceOnce configured;   // per instantiation: the attribute belongs to the function
-    const hipError_t cfg = configured([] {
-        return hipFuncSetAttribute(reinterpret_cast<const void *>(&split_select_kernel<DIFF, UPDATE>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDyn);
-    });
-    if (cfg != hipSuccess) return cfg;
-    hipLaunchKernelGGL((split_select_kernel<DIFF, UPDATE>), dim3((unsigned)p.n), dim3(kBlk), kDyn, stream, p, w);
-    return hipGetLastError();
+void launch_collect_any(const TopkArgs &p, const Ws &w, int mode, hipStream_t stream) {
+    const bool diff = p.b != nullptr;
+    const bool vec4 = (p.d % 4 == 0) && ((uintptr_t)p.a % 16 == 0) && (!diff || (uintptr_t)p.b % 16 == 0);
+    if (vec4 && diff) launch_collect<4, true>(p, w, mode, stream);
+    else if (vec4) launch_collect<4, false>(p, w, mode, stream);
+    else if (diff) launch_collect<1, true>(p, w, mode, stream);
+    else launch_collect<1, false>(p, w, mode, stream);
 }
 
 // ---------------------------------------------------------------- k = 1: the entry of largest magnitude
@@ -1000,7 +796,7 @@ __global__ __launch_bounds__(kArgThreads) void argmax_stream_kernel(TopkArgs p, 
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int v = 1; v < kArgWaves; ++v) best = best_of_wave[v] > best ? best_of_wave[v] : best;
-        if (lo < hi) atomicMax(reinterpret_cast<unsigned long long *>(w.hist_a + row * kBinsA), best);
+        if (lo < hi) atomicMax(reinterpret_cast<unsigned long long *>(w.hist_a + row * kHistBins), best);
     }
 }
 
@@ -1008,7 +804,7 @@ template <bool DIFF, bool UPDATE>
 __global__ __launch_bounds__(kArgThreads) void argmax_finish_kernel(TopkArgs p, Ws w) {
     const int64_t row = (int64_t)blockIdx.x * kArgThreads + threadIdx.x;
     if (row >= p.n) return;
-    unsigned long long *slot = reinterpret_cast<unsigned long long *>(w.hist_a + row * kBinsA);
+    unsigned long long *slot = reinterpret_cast<unsigned long long *>(w.hist_a + row * kHistBins);
     const int64_t e = (int64_t)(0xffffffffu - (uint32_t)(*slot & 0xffffffffull));
     *slot = 0ull;
     const float bv = DIFF ? p.b[row * p.d + e] : 0.f;
@@ -1041,13 +837,6 @@ hipError_t launch_argmax(const TopkArgs &p, const Ws &w, hipStream_t stream, con
     return hipGetLastError();
 }
 
-// candidates the collect pass is expected to keep per row (see sample_rank)
-double expected_candidates(int64_t d, int64_t k) {
-    const double ns = d < kSample ? (double)d : (double)kSample;
-    const double mu = (double)k * ns / (double)d;
-    return (mu + 5.0 * std::sqrt(mu) + 8.0) * (double)d / ns * 1.1;
-}
-
 }  // namespace
 
 size_t topk_split_workspace_bytes(int32_t n, int64_t d, int64_t) { return layout(n, d, nullptr, nullptr); }
@@ -1055,8 +844,8 @@ size_t topk_split_workspace_bytes(int32_t n, int64_t d, int64_t) { return layout
 hipError_t launch_topk_split_reset(void *workspace, int32_t n, int64_t d, hipStream_t stream) {
     Ws w;
     layout(n, d, (char *)workspace, &w);
-    // the histograms are the leading, contiguous part of the layout
-    const size_t words = ((char *)w.info - (char *)workspace) / sizeof(uint32_t);
+    // the histograms and the row records are the leading, contiguous part of the layout
+    const size_t words = ((char *)w.slot_cnt - (char *)workspace) / sizeof(uint32_t);
     size_t blocks = (words + kCandThreads - 1) / kCandThreads;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)blocks), dim3(kCandThreads), 0, stream, (uint32_t *)workspace,
@@ -1069,38 +858,33 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
     layout(p.n, p.d, (char *)workspace, &w);
     const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
     if (upd && !diff) return hipErrorInvalidValue;
+    if (p.warm < 0 || p.warm > kWarmSlots) return hipErrorInvalidValue;
+    if (p.agg_start && (p.agg_shift < 0 || p.agg_shift > 11 || p.agg_nblk != ((p.d - 1) >> p.agg_shift) + 1 || p.k == 1))
+        return hipErrorInvalidValue;
     if (p.k == 1) return launch_argmax(p, w, stream, mk);
-    const bool vec4 = (p.d % 4 == 0) && ((uintptr_t)p.a % 16 == 0) && (!diff || (uintptr_t)p.b % 16 == 0);
-    if (vec4 && upd) launch_collect<4, true, true>(p, w, stream);
-    else if (vec4 && diff) launch_collect<4, true, false>(p, w, stream);
-    else if (vec4) launch_collect<4, false, false>(p, w, stream);
-    else if (upd) launch_collect<1, true, true>(p, w, stream);
-    else if (diff) launch_collect<1, true, false>(p, w, stream);
-    else launch_collect<1, false, false>(p, w, stream);
+    launch_collect_any(p, w, p.warm > 0 ? kWarmPass : kColdPass, stream);
     mk(K_TOPK_COLLECT);
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;
-
-    if (expected_candidates(p.d, p.k) <= (double)kSelectMax) {
-        if (upd) st = launch_select<true, true>(p, w, stream);
-        else if (diff) st = launch_select<true, false>(p, w, stream);
-        else st = launch_select<false, false>(p, w, stream);
-        mk(K_TOPK_SELECT);
-        return st;
+    if (p.warm > 0) {
+        launch_collect_any(p, w, kSecondPass, stream);
+        mk(K_TOPK_REFINE);
     }
-    const dim3 hgrid(kCandBlocks, (unsigned)p.n), hblock(kHistThreads);
-    hipLaunchKernelGGL(cand_hist_kernel<1>, hgrid, hblock, 0, stream, p, w);
-    mk(K_TOPK_REFINE);
-    hipLaunchKernelGGL(cand_hist_kernel<2>, hgrid, hblock, 0, stream, p, w);
-    mk(K_TOPK_REFINE);
-    const unsigned slot_blocks = (unsigned)((w.nslot + kCandWaves - 1) / kCandWaves);
+    const int spw = (int64_t)p.n * ((w.nslot + kCandWaves - 1) / kCandWaves) > 256 ? 2 : 1;
+    const unsigned slot_blocks = (unsigned)((w.nslot + kCandWaves * spw - 1) / (kCandWaves * spw));
     const dim3 grid(slot_blocks, (unsigned)p.n), cgrid(slot_blocks + 1, (unsigned)p.n), block(kCandThreads);
-    if (upd) hipLaunchKernelGGL((cand_count_kernel<true, true>), cgrid, block, 0, stream, p, w);
-    else if (diff) hipLaunchKernelGGL((cand_count_kernel<true, false>), cgrid, block, 0, stream, p, w);
-    else hipLaunchKernelGGL((cand_count_kernel<false, false>), cgrid, block, 0, stream, p, w);
+#define EF21_CAND(KERNEL, GRID, DIFF, UPD)                                                               \
+    do {                                                                                                 \
+        if (spw == 2) hipLaunchKernelGGL((KERNEL<DIFF, UPD, 2>), GRID, block, 0, stream, p, w);          \
+        else hipLaunchKernelGGL((KERNEL<DIFF, UPD, 1>), GRID, block, 0, stream, p, w);                   \
+    } while (0)
+    if (upd) EF21_CAND(cand_count_kernel, cgrid, true, true);
+    else if (diff) EF21_CAND(cand_count_kernel, cgrid, true, false);
+    else EF21_CAND(cand_count_kernel, cgrid, false, false);
     mk(K_TOPK_COUNT);
-    if (upd) hipLaunchKernelGGL(cand_emit_kernel<true>, grid, block, 0, stream, p, w);
-    else hipLaunchKernelGGL(cand_emit_kernel<false>, grid, block, 0, stream, p, w);
+    if (upd) EF21_CAND(cand_emit_kernel, grid, true, true);
+    else EF21_CAND(cand_emit_kernel, grid, false, false);
+#undef EF21_CAND
     mk(K_TOPK_EMIT);
     return hipGetLastError();
 }

@@ -331,10 +331,22 @@ size_t aggregate_index_bytes(int32_t n, int64_t d) {      // for the shorter of 
     return sizeof(int32_t) * (size_t)n * ((size_t)((d + kManySub - 1) / kManySub) + 1);
 }
 
+namespace {
+bool aggregate_is_small(int32_t n, int64_t k, int64_t d) {
+    return d <= kSmallD && (int64_t)n * k <= kSmallEntries && (int64_t)n * ((k + kWave - 1) / kWave) <= kSmallSteps;
+}
+}  // namespace
+
+int aggregate_index_shift(int32_t n, int64_t k, int64_t d) {
+    static_assert(kManySub == 1 << 8 && kAggSub == 1 << 11, "block lengths as shifts");
+    if (aggregate_is_small(n, k, d)) return -1;
+    return n >= kManyWorkers ? 8 : 11;
+}
+
 hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int64_t k, int64_t d, float *g, float *x,
-                            float gamma, void *index, hipStream_t stream) {
+                            float gamma, void *index, hipStream_t stream, bool index_ready) {
     const float inv_n = 1.0f / (float)n;
-    if (d <= kSmallD && (int64_t)n * k <= kSmallEntries && (int64_t)n * ((k + kWave - 1) / kWave) <= kSmallSteps) {
+    if (aggregate_is_small(n, k, d)) {
         if (x)
             hipLaunchKernelGGL(aggregate_small_kernel<true>, dim3(1), dim3(kSmallThreads), 0, stream, idx, val, n, k, d,
                                g, x, inv_n, -gamma);
@@ -346,8 +358,9 @@ hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int
     int32_t *start = (int32_t *)index;
     if (n >= kManyWorkers) {
         const int64_t nblk = (d + kManySub - 1) / kManySub;
-        hipLaunchKernelGGL(message_index_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads), (unsigned)n),
-                           dim3(kThreads), 0, stream, idx, k, nblk, kManySub, start);
+        if (!index_ready)
+            hipLaunchKernelGGL(message_index_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads), (unsigned)n),
+                               dim3(kThreads), 0, stream, idx, k, nblk, kManySub, start);
         if (x)
             hipLaunchKernelGGL(aggregate_many_kernel<true>, dim3((unsigned)nblk), dim3(kThreads), 0, stream, idx, val,
                                start, n, k, d, nblk, g, x, inv_n, -gamma);
@@ -357,8 +370,9 @@ hipError_t launch_aggregate(const int32_t *idx, const float *val, int32_t n, int
         return hipGetLastError();
     }
     const int64_t nblk = (d + kAggSub - 1) / kAggSub;
-    hipLaunchKernelGGL(message_index_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads), (unsigned)n),
-                       dim3(kThreads), 0, stream, idx, k, nblk, kAggSub, start);
+    if (!index_ready)
+        hipLaunchKernelGGL(message_index_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads), (unsigned)n),
+                           dim3(kThreads), 0, stream, idx, k, nblk, kAggSub, start);
     const dim3 grid((unsigned)((nblk + kAggWaves - 1) / kAggWaves)), block(kThreads);
     const bool vec4 = (d % 4 == 0) && (((uintptr_t)g | (uintptr_t)(x ? x : g)) % 16 == 0);
     if (x && vec4)

@@ -132,6 +132,22 @@ def student_t_grads(n: int, d: int, seed: int = 0, nu: float = 3.0, scale: float
     return out
 
 
+def student_t_grads_on_device(n: int, d: int, count: int, seed: int = 0, scale: float = 1e-3, device: str = "cuda"):
+    """`count` independent [n][d] float32 draws of scale * t_3 made on the device (torch's generator, seeded):
+    a standard normal over the root mean square of three others.  For timing runs that need a fresh
+    gradient every step and cannot wait for the host generator; parity tests use student_t_grads."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    out = []
+    for _ in range(count):
+        z = torch.randn((n, d), device=device, generator=gen)
+        chi = torch.randn((3, n, d), device=device, generator=gen).square_().sum(0).div_(3.0).sqrt_()
+        out.append((z.div_(chi).mul_(scale)).contiguous())
+        del chi
+    return out
+
+
 # The configurations the build is measured and tested on (sizes only; see each generator).
 CONFIGS = {
     "C0": dict(kind="dense", n=4, d=100, m=250, k=1, gamma=0.1, lam=0.1, iters=100, seed=0),

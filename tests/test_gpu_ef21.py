@@ -166,6 +166,39 @@ def test_step_when_the_sample_misleads(gpu, oracle, k):
         compare_state(torch, h, st, budget)
 
 
+@pytest.mark.parametrize("k", [3000, 40000])
+def test_steps_when_the_remembered_threshold_is_wrong(gpu, oracle, k):
+    """Consecutive steps on long rows: from the second step on, the candidates are collected with the previous
+    step's threshold as the guess.  The scale of the differences then jumps per row: unchanged (the guess
+    holds), up by 300 (the threshold lies far beyond the guess's window), down by 1000 (fewer than k candidates
+    reach the guess), back, and finally one row of equal magnitudes (a crowded bin: the exact per-row algorithm).
+    Whatever the guess, every step must give the oracle's messages and state bit for bit."""
+    torch, binding = gpu
+    n, d, gamma = 3, 300_000, 0.25
+    print(f"wrong warm start k={k}", flush=True)
+    rng = np.random.default_rng(k + 1)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    g_i0 = rng.standard_normal((n, d)).astype(np.float32)
+    g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    budget = RoundingBudget(n, d, gamma)
+    scales = [(1.0, 1.0, 1.0), (1.01, 0.99, 1.0), (300.0, 1e-3, 1.0), (300.0, 1e-3, 1.05), (1.0, 1.0, 0.93),
+              (1e-3, 300.0, 1.0), (1.0, 1.0, 1.0), (1.0, 1.0, 1.0)]
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+        for t, sc in enumerate(scales):
+            noise = rng.standard_normal((n, d)) * np.array(sc)[:, None]
+            if t == len(scales) - 1:
+                noise[1] = np.where(rng.random(d) < 0.5, 0.5, -0.5)      # every magnitude equal
+            grads = (st.g_i + noise).astype(np.float32)
+            oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma)
+            h.step(to_gpu(torch, grads))
+            torch.cuda.synchronize()
+            compare_state(torch, h, st, budget)
+            h.set_state(to_gpu(torch, st.x), None, to_gpu(torch, st.g))
+            budget.reset()
+
+
 def test_first_pass_compresses_zero_vector(gpu, oracle):
     """g_i^0 = grad: the first grad-first pass sees v = 0; k zero-valued pairs at positions 0..k-1
     are emitted and the state does not change."""

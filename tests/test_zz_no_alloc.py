@@ -74,7 +74,7 @@ def test_shapes_without_workspace_and_ties(gpu):
 
 def test_limit_is_an_error_not_an_allocation(gpu):
     torch, binding, lib = gpu
-    n, d, k = 8, 1_000_000, 2000                     # about 96 MB of workspace: beyond the static 64 MiB
+    n, d, k = 10, 1_000_000, 2000                    # about 81 MB of workspace: beyond the static 64 MiB
     rows = torch.zeros((n, d), dtype=torch.float32, device="cuda")
     idx = torch.zeros((n, k), dtype=torch.int32, device="cuda")
     val = torch.zeros((n, k), dtype=torch.float32, device="cuda")
