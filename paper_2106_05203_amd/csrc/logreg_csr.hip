@@ -237,8 +237,8 @@ __global__ __launch_bounds__(kAtrThreads) void csrr_build_kernel(const int64_t *
 // The calling wavefront owns 4 x 64 consecutive segments; lane j holds the entry ranges [b[g], e[g]) of
 // segments j, j + 64, ... (ascending and contiguous over (g, lane); an empty range where there is no
 // segment).  The span is walked in tiles of 1024 entries aligned to four entries: each lane loads four
-// times four consecutive pairs, all loads of the tile in flight together, multiplies the values by
-// vec(index) and stages the products in LDS; then every lane adds, for each of its segments, the piece
+// times four consecutive pairs (the next tile's loads are issued before this tile is summed), multiplies the
+// values by vec(index) and stages the products in LDS; then every lane adds, for each of its segments, the piece
 // that lies in the tile, in storage order (a piece longer than kLongColumn entries by the whole
 // wavefront).  acc[g] receives the sums.  The lists must be readable up to three entries past the span.
 template <class Index, class VecFn>
@@ -246,22 +246,36 @@ __device__ __forceinline__ void segment_sums(const int64_t (&b)[kCscGroups], con
                                              const Index *__restrict__ index, const float *__restrict__ value,
                                              VecFn vec, float *tile, int lane, float (&acc)[kCscGroups]) {
     const int64_t span_b = __shfl(b[0], 0, kWave), span_e = __shfl(e[kCscGroups - 1], kWave - 1, kWave);
+    const int64_t origin = span_b & ~(int64_t)3;               // tiles are aligned to four entries
+    // segment bounds and tile positions relative to the origin (a span has fewer than 2^31 entries)
+    int32_t rb[kCscGroups], re[kCscGroups];
 #pragma unroll
-    for (int g = 0; g < kCscGroups; ++g) acc[g] = 0.f;
+    for (int g = 0; g < kCscGroups; ++g) {
+        acc[g] = 0.f;
+        rb[g] = (int32_t)(b[g] - origin);
+        re[g] = (int32_t)(e[g] - origin);
+    }
+    const int32_t end = (int32_t)(span_e - origin);
     constexpr int kLoads = kTile / (4 * kWave);                // 4
     const int64_t last4 = (span_e - 1) & ~(int64_t)3;          // last aligned quad that holds an entry of the span
-    for (int64_t t0 = span_b & ~(int64_t)3; t0 < span_e; t0 += kTile) {
-        typedef float v4f __attribute__((ext_vector_type(4)));
-        typedef Index v4r __attribute__((ext_vector_type(4)));
-        v4r r[kLoads];
-        v4f v[kLoads];
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    typedef Index v4r __attribute__((ext_vector_type(4)));
+    // the loads of a tile: addresses past the span are clamped (they re-read its last quad), so none sits behind
+    // a branch
+    auto load_tile = [&](int32_t t0, v4r (&r)[kLoads], v4f (&v)[kLoads]) {
 #pragma unroll
         for (int u = 0; u < kLoads; ++u) {
-            int64_t at = t0 + u * (4 * kWave) + 4 * lane;
-            at = at < last4 ? at : last4;                      // clamped (re-reads the last quad): no load behind a branch
+            int64_t at = origin + t0 + u * (4 * kWave) + 4 * lane;
+            at = at < last4 ? at : last4;
             r[u] = __builtin_nontemporal_load(reinterpret_cast<const v4r *>(index + at));
             v[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(value + at));
         }
+    };
+    v4r r[kLoads], r_next[kLoads];
+    v4f v[kLoads], v_next[kLoads];
+    if (0 < end) load_tile(0, r, v);
+    for (int32_t t0 = 0; t0 < end; t0 += kTile) {
+        load_tile(t0 + kTile, r_next, v_next);
 #pragma unroll
         for (int u = 0; u < kLoads; ++u) {
             v4f pr;
@@ -274,15 +288,19 @@ __device__ __forceinline__ void segment_sums(const int64_t (&b)[kCscGroups], con
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int64_t t1 = t0 + kTile < span_e ? t0 + kTile : span_e;
+        const int32_t t1 = t0 + kTile < end ? t0 + kTile : end;
 #pragma unroll
         for (int g = 0; g < kCscGroups; ++g) {
-            const int64_t lo64 = b[g] > t0 ? b[g] : t0, hi64 = e[g] < t1 ? e[g] : t1;
-            const int32_t lo = (int32_t)(lo64 - t0), hi = (int32_t)(hi64 - t0);     // tile coordinates; hi <= lo: nothing
+            const int32_t lo = (rb[g] > t0 ? rb[g] : t0) - t0, hi = (re[g] < t1 ? re[g] : t1) - t0;   // tile coordinates
             if (__ballot(lo < hi) == 0) continue;              // the group has nothing in this tile (uniform)
             const bool is_long = hi - lo > kLongColumn;
-            if (!is_long)
-                for (int32_t t = lo; t < hi; ++t) acc[g] += tile[t];
+            if (!is_long) {
+                int32_t t = lo;
+                float a = acc[g];
+                for (; t + 4 <= hi; t += 4) a = (((a + tile[t]) + tile[t + 1]) + tile[t + 2]) + tile[t + 3];
+                for (; t < hi; ++t) a += tile[t];
+                acc[g] = a;
+            }
             uint64_t todo = __ballot(is_long);
             while (todo) {                                     // uniform in the wavefront
                 const int src = __ffsll((long long)todo) - 1;
@@ -296,6 +314,11 @@ __device__ __forceinline__ void segment_sums(const int64_t (&b)[kCscGroups], con
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            r[u] = r_next[u];
+            v[u] = v_next[u];
+        }
     }
 }
 
@@ -487,8 +510,8 @@ __global__ __launch_bounds__(kCscThreads) void csc_grad_kernel(const int32_t *__
         e[g] = first + cp[c < d ? c + 1 : d];
     }
     float acc[kCscGroups];
-    segment_sums(b, e, csc_row, csc_val, [&](RowIndex r) { return COEF_LDS ? coef_lds[r] : cf[r]; }, tiles[wave], lane,
-                 acc);
+    segment_sums(b, e, csc_row, csc_val, [&](RowIndex r) { return COEF_LDS ? coef_lds[r] : cf[r]; }, tiles[wave],
+                    lane, acc);
 #pragma unroll
     for (int g = 0; g < kCscGroups; ++g) {
         const int64_t c = cb + g * kWave + lane;
