@@ -23,35 +23,85 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
+PROFILES = os.path.join(ROOT, "profiles")
+KERNEL_SOURCES = os.path.join(ROOT, "paper_2106_05203_amd", "csrc")
 
-# HBM bytes per launch of the dominant kernels, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
-# scaled by a plain 1 GiB copy's readings (summaries and commands under profiles/); not measured live.
-MEASURED_TRAFFIC_BYTES = {
-    "C2/grad_main": 804.9e6,       # profiles/ef21_step_C2_hbm_traffic_pmc.md
-    "C4/topk_collect": 739.4e6,    # profiles/ef21_step_C4_hbm_traffic_pmc.md
-    "C3/grad_main": 1307.8e6,      # profiles/ef21_step_C3_hbm_traffic_pmc.md (both passes)
-}
+
+def source_fingerprint() -> str:
+    """Hash of the kernel sources: a profile summary taken at other sources does not describe this library."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(KERNEL_SOURCES)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(KERNEL_SOURCES, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(key: str):
+    """HBM bytes per launch of a dominant kernel from the rocprofv3 --pmc summary under profiles/ (FETCH_SIZE +
+    WRITE_SIZE scaled by a plain copy's readings; the summary holds the commands).  The summaries carry
+    machine-readable lines `traffic <key> <bytes>` and `kernel-sources <fingerprint>`; one taken at other kernel
+    sources than this tree's is refused (None, and a line on stderr), not quoted."""
+    if not os.path.isdir(PROFILES):
+        return None
+    for name in sorted(os.listdir(PROFILES)):
+        if not name.endswith("_pmc.md"):
+            continue
+        text = open(os.path.join(PROFILES, name)).read().split("\n")
+        stamp = [ln.split()[1] for ln in text if ln.startswith("kernel-sources ") and len(ln.split()) > 1]
+        for ln in text:
+            f = ln.split()
+            if len(f) == 3 and f[0] == "traffic" and f[1] == key:
+                if not stamp or stamp[0] != source_fingerprint():
+                    log(f"profiles/{name} was taken at kernel sources {stamp[0] if stamp else '?'}, this tree is "
+                        f"{source_fingerprint()}: its traffic figure for {key} is NOT quoted")
+                    return None
+                return float(f[2])
+    return None
 
 
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def timed_loop(torch, fn, steps: int, warmup: int):
-    """warmup untimed calls, then exactly `steps` calls between synchronisations; (ms per step by the
-    host clock, ms per step by HIP events on the current stream)."""
-    for i in range(warmup):
-        fn(i)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for i in range(steps):
-        fn(warmup + i)
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    return wall_ms / steps, e0.elapsed_time(e1) / steps
+REPEATS = 5
+
+
+class Timed:
+    """`warmup` untimed calls, then REPEATS loops of exactly `steps` calls, each loop between two
+    synchronisations and two HIP events on the current stream.  ms per step: median and minimum over the loops,
+    by the host clock (wall) and by the events (ev)."""
+
+    def __init__(self, torch, fn, steps: int, warmup: int, repeats: int = None):
+        repeats = REPEATS if repeats is None else repeats
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        walls, evs = [], []
+        at = warmup
+        for _ in range(repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record()
+            for i in range(steps):
+                fn(at + i)
+            e1.record()
+            torch.cuda.synchronize()
+            walls.append((time.perf_counter() - t0) * 1e3 / steps)
+            evs.append(e0.elapsed_time(e1) / steps)
+            at += steps
+        walls.sort()
+        evs.sort()
+        self.wall, self.wall_min = walls[len(walls) // 2], walls[0]
+        self.ev, self.ev_min = evs[len(evs) // 2], evs[0]
+        self.repeats, self.steps = repeats, steps
+
+    def fields(self, clock: str = "wall") -> dict:
+        med, low = (self.wall, self.wall_min) if clock == "wall" else (self.ev, self.ev_min)
+        return {"ms_per_step": round(med, 5), "ms_per_step_min": round(low, 5),
+                "timing": f"median and min of {self.repeats} loops of {self.steps} steps, "
+                          + ("host clock around synchronised loops" if clock == "wall" else "HIP events")}
 
 
 def kernel_times(torch, h, fn, steps: int):
@@ -89,29 +139,29 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
     h.set_problem_dense(A, y, c["lam"])
     x0 = torch.zeros(d, device="cuda")
     h.set_state(x0, h.local_grad(x0), None)          # g_i^0 = grad f_i(x^0)
-    wall, ev = timed_loop(torch, lambda i: h.step(), steps, warmup)
+    t = Timed(torch, lambda i: h.step(), steps, warmup)
+    wall = t.wall
     per_kernel, launches = kernel_times(torch, h, lambda i: h.step(), steps)
-    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", "ms_per_step": round(wall, 5),
-           "ms_per_step_events": round(ev, 5), "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()},
+    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", **t.fields(),
+           "ms_per_step_events": round(t.ev, 5), "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()},
            "iteration_algorithmic_bytes": 4 * n * m * d + 4 * n * m + 12 * n * d + 24 * n * k + 12 * d}
     if "grad_main" in per_kernel:
         out["roofline"] = roofline(4.0 * n * m * d + 4.0 * n * m + 4.0 * d, per_kernel["grad_main"],
-                                   "logreg_dense_fused_kernel (grad_main)",
-                                   MEASURED_TRAFFIC_BYTES.get(f"{name}/grad_main"))
+                                   "logreg_dense_fused_kernel (grad_main)", measured_traffic(f"{name}/grad_main"))
     else:                 # (a run that measures the one-launch iteration only)
         out["roofline"] = roofline(out["iteration_algorithmic_bytes"], per_kernel["small_step"],
                                    "small_step_kernel (the whole iteration)", None)
     out["iteration_frac_of_hbm_peak"] = round(out["iteration_algorithmic_bytes"] / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     if name == "C2":      # the same problem under Algorithm 3 (EF21+): two Top-k selections and the choice per worker
-        wall_p, _ = timed_loop(torch, lambda i: h.step(None, binding.PLUS), steps, warmup)
+        tp = Timed(torch, lambda i: h.step(None, binding.PLUS), steps, warmup)
         pk, pl = kernel_times(torch, h, lambda i: h.step(None, binding.PLUS), steps)
-        out["ef21_plus"] = {"value": round(1e3 / wall_p, 2), "unit": "EF21+ iterations/s", "ms_per_step": round(wall_p, 5),
+        out["ef21_plus"] = {"value": round(1e3 / tp.wall, 2), "unit": "EF21+ iterations/s", **tp.fields(),
                             "kernel_ms_per_step": {k_: round(v * pl[k_], 5) for k_, v in pk.items()},
                             "plain_compressor_chosen_last_step": int(h.get_choices()[0].sum().item())}
     if name == "C2":      # and under Algorithm 4 (the original EF, the comparison method), errors started at zero
         h.set_state(x0, torch.zeros((n, d), device="cuda"), None)
-        wall_e, _ = timed_loop(torch, lambda i: h.step(None, binding.CLASSIC_EF), steps, warmup)
-        out["classic_ef"] = {"value": round(1e3 / wall_e, 2), "unit": "EF iterations/s", "ms_per_step": round(wall_e, 5)}
+        te = Timed(torch, lambda i: h.step(None, binding.CLASSIC_EF), steps, warmup)
+        out["classic_ef"] = {"value": round(1e3 / te.wall, 2), "unit": "EF iterations/s", **te.fields()}
     if name == "C2":      # and under Algorithm 5: minibatches of m/8 rows per worker, drawn without replacement, a
         tau = m // 8      # fresh one every iteration (eight batches prepared in HBM, the draw is the caller's)
         rng = np.random.default_rng(c["seed"] + 5)
@@ -122,17 +172,17 @@ def bench_dense(torch, binding, workloads, name: str, steps: int, warmup: int):
         def sto(i):
             h.set_minibatch(batches[i % 8])
             h.step()
-        wall_s, _ = timed_loop(torch, sto, steps, warmup)
+        ts = Timed(torch, sto, steps, warmup)
+        wall_s = ts.wall
         pk, _ = kernel_times(torch, h, sto, steps)
         h.set_minibatch(None)
         gbytes = 4.0 * n * tau * d + 8.0 * n * tau + 4.0 * d
         out["ef21_stochastic"] = {"value": round(1e3 / wall_s, 2), "unit": "Algorithm 5 iterations/s", "tau": tau,
-                                  "ms_per_step": round(wall_s, 5), "grad_main_ms": round(pk["grad_main"], 5),
+                                  **ts.fields(), "grad_main_ms": round(pk["grad_main"], 5),
                                   "grad_main_GBps": round(gbytes / (pk["grad_main"] * 1e-3) / 1e9, 1)}
     if name == "C0":      # launch-bound: beside the three kernels of the default, the one-launch iteration,
-        wall_one, _ = timed_loop(torch, lambda i: h.step(None, binding.ONE_LAUNCH), steps, warmup)
-        out["one_launch"] = {"value": round(1e3 / wall_one, 2), "unit": "EF21 iterations/s",
-                             "ms_per_step": round(wall_one, 5)}
+        t1 = Timed(torch, lambda i: h.step(None, binding.ONE_LAUNCH), steps, warmup)
+        out["one_launch"] = {"value": round(1e3 / t1.wall, 2), "unit": "EF21 iterations/s", **t1.fields()}
         # and the same iterations replayed from a HIP graph of 10 captured steps
         out["hip_graph_10_steps"] = graph_replay(torch, h, steps)
     return out, (W, h)
@@ -189,15 +239,21 @@ def graph_replay(torch, h, steps: int, per_graph: int = 10):
         replays = max(1, steps // per_graph)
         graph.replay()
         side.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(side)
-        for _ in range(replays):
-            graph.replay()
-        e1.record(side)
-        side.synchronize()
+        times = []
+        for _ in range(REPEATS):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(side)
+            for _ in range(replays):
+                graph.replay()
+            e1.record(side)
+            side.synchronize()
+            times.append(e0.elapsed_time(e1) / (replays * per_graph))
     h.use_current_stream()
-    ms = e0.elapsed_time(e1) / (replays * per_graph)
-    return {"ms_per_step": round(ms, 5), "value": round(1e3 / ms, 2), "unit": "EF21 iterations/s"}
+    times.sort()
+    ms = times[len(times) // 2]
+    return {"ms_per_step": round(ms, 5), "ms_per_step_min": round(times[0], 5), "value": round(1e3 / ms, 2),
+            "unit": "EF21 iterations/s",
+            "timing": f"median and min of {REPEATS} loops of {replays} replays of {per_graph} captured steps, HIP events"}
 
 
 def bench_topk(torch, binding, workloads, steps: int, warmup: int):
@@ -209,15 +265,23 @@ def bench_topk(torch, binding, workloads, steps: int, warmup: int):
     for k in c["ks"]:
         idx = torch.empty((n, k), dtype=torch.int32, device="cuda")
         val = torch.empty((n, k), dtype=torch.float32, device="cuda")
-        wall, ev = timed_loop(torch, lambda i: binding.ef21_topk(pool[i % 4], k, idx, val), steps, warmup)
-        wall_hot, ev_hot = timed_loop(torch, lambda i: binding.ef21_topk(pool[0], k, idx, val), steps, warmup)
+        t = Timed(torch, lambda i: binding.ef21_topk(pool[i % 4], k, idx, val), steps, warmup)
+        th = Timed(torch, lambda i: binding.ef21_topk(pool[0], k, idx, val), steps, warmup)
+        ev, ev_hot = t.ev, th.ev
         bytes_call = 4.0 * n * d + 8.0 * n * k
         res[f"k={k}"] = {
             "value": round(n * d / (ev * 1e-3), 1), "unit": "Top-k elements/s", "ms_per_call": round(ev, 5),
-            "ms_per_call_host_clock": round(wall, 5),
+            "ms_per_call_min": round(t.ev_min, 5), "ms_per_call_host_clock": round(t.wall, 5),
+            "timing": t.fields("ev")["timing"],
             "call_frac_of_hbm_peak": round(bytes_call / (ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "same_buffer_every_call": {"value": round(n * d / (ev_hot * 1e-3), 1), "ms_per_call": round(ev_hot, 5)},
         }
+    # the roofline of the workload: the whole call (collect + count + emit) against the bytes of one read of
+    # the rows and one write of the pairs, at the k where it is worst
+    worst = min((kk for kk in res), key=lambda kk: res[kk]["call_frac_of_hbm_peak"])
+    kw = int(worst.split("=")[1])
+    res["roofline"] = roofline(4.0 * n * d + 8.0 * n * kw, res[worst]["ms_per_call"],
+                               f"ef21_topk call, {worst} (all kernels of the call)", None)
     return res
 
 
@@ -232,20 +296,21 @@ def bench_csr(torch, binding, workloads, steps: int, warmup: int):
     h.set_problem_csr(rp, col, val, y, m, c["lam"])
     x0 = torch.zeros(d, device="cuda")
     h.set_state(x0, h.local_grad(x0), None)
-    wall, ev = timed_loop(torch, lambda i: h.step(), steps, warmup)
+    t = Timed(torch, lambda i: h.step(), steps, warmup)
+    wall = t.wall
     per_kernel, launches = kernel_times(torch, h, lambda i: h.step(), steps)
     total_nnz = n * m * nnz
     it_bytes = 8 * total_nnz + 8 * (n * m + 1) + 4 * n * m + 12 * n * d + 24 * n * k + 12 * d
-    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", "ms_per_step": round(wall, 5),
+    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s", **t.fields(),
            "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()}, "iteration_algorithmic_bytes": it_bytes,
            "iteration_frac_of_hbm_peak": round(it_bytes / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     # the gradient takes two passes (two launches of the grad_main class): its algorithmic bytes against both
     out["roofline"] = roofline(8.0 * total_nnz + 8.0 * (n * m + 1) + 4.0 * n * m + 4.0 * n * d,
                                per_kernel["grad_main"] * launches["grad_main"],
                                "csrr_dot_kernel + csc_grad_kernel (grad_main, both passes)",
-                               MEASURED_TRAFFIC_BYTES.get("C3/grad_main"))
+                               measured_traffic("C3/grad_main"))
     h.close()
-    return out
+    return out, W
 
 
 def bench_grads(torch, binding, workloads, steps: int, warmup: int):
@@ -258,30 +323,30 @@ def bench_grads(torch, binding, workloads, steps: int, warmup: int):
     NP = 8
     pool = workloads.student_t_grads_on_device(n, d, NP, seed=c["seed"])
     h = binding.EF21(n, d, k, c["gamma"])
-    wall, ev = timed_loop(torch, lambda i: h.step(pool[i % NP]), steps, warmup)
+    t = Timed(torch, lambda i: h.step(pool[i % NP]), steps, warmup)
+    wall = t.wall
     per_kernel, launches = kernel_times(torch, h, lambda i: h.step(pool[i % NP]), steps)
     it_bytes = 8 * n * d + 12 * d + 24 * n * k
-    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s (gradients supplied)", "ms_per_step": round(wall, 5),
+    out = {"value": round(1e3 / wall, 2), "unit": "EF21 iterations/s (gradients supplied)", **t.fields(),
            "kernel_ms": {k_: round(v, 5) for k_, v in per_kernel.items()}, "iteration_algorithmic_bytes": it_bytes,
            "iteration_frac_of_hbm_peak": round(it_bytes / (wall * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
            "topk_elements_per_s": round(n * d / (sum(v for k_, v in per_kernel.items() if k_.startswith("topk")) * 1e-3), 1)}
     # the comparison method on the same gradients: Algorithm 4 rewrites its whole state e_i every round
     h.set_state(torch.zeros(d, device="cuda"), torch.zeros((n, d), device="cuda"), None)
-    wall_e, _ = timed_loop(torch, lambda i: h.step(pool[i % NP], binding.CLASSIC_EF), steps, warmup)
-    out["classic_ef"] = {"value": round(1e3 / wall_e, 2), "unit": "EF iterations/s (gradients supplied)",
-                         "ms_per_step": round(wall_e, 5)}
+    te = Timed(torch, lambda i: h.step(pool[i % NP], binding.CLASSIC_EF), steps, warmup, repeats=3)
+    out["classic_ef"] = {"value": round(1e3 / te.wall, 2), "unit": "EF iterations/s (gradients supplied)", **te.fields()}
     # Algorithm 3 on the same gradients: two Top-k selections, the distortions and the mean of the rows, each a
     # pass of its own over the long rows
     h.set_state(torch.zeros(d, device="cuda"), torch.zeros((n, d), device="cuda"), None)
-    wall_p, _ = timed_loop(torch, lambda i: h.step(pool[i % NP], binding.PLUS), max(10, steps // 2), max(3, warmup // 2))
+    tp = Timed(torch, lambda i: h.step(pool[i % NP], binding.PLUS), max(10, steps // 2), max(3, warmup // 2), repeats=3)
     pk, pl = kernel_times(torch, h, lambda i: h.step(pool[i % NP], binding.PLUS), max(10, steps // 2))
-    out["ef21_plus"] = {"value": round(1e3 / wall_p, 2), "unit": "EF21+ iterations/s (gradients supplied)",
-                        "ms_per_step": round(wall_p, 5),
+    out["ef21_plus"] = {"value": round(1e3 / tp.wall, 2), "unit": "EF21+ iterations/s (gradients supplied)",
+                        **tp.fields(),
                         "kernel_ms_per_step": {k_: round(v * pl[k_], 5) for k_, v in pk.items()},
                         "plain_compressor_chosen_last_step": int(h.get_choices()[0].sum().item())}
     dom = "topk_collect" if "topk_collect" in per_kernel else "topk_row"
     out["roofline"] = roofline(8.0 * n * d, per_kernel[dom], f"{dom} (reads grad and g_i once)",
-                               MEASURED_TRAFFIC_BYTES.get(f"C4/{dom}"))
+                               measured_traffic(f"C4/{dom}"))
     h.close()
     return out
 
@@ -306,6 +371,43 @@ def cpu_baseline_dense(workloads, W, name: str, budget_s: float = 12.0):
             "sample": f"{its} of the {c['iters']} iterations of {name} at full size ({el:.1f} s)"}
 
 
+def cpu_baseline_csr(workloads, W, budget_s: float = 8.0, max_its: int = 20):
+    """The oracle on C3 at full size, cut to at most `max_its` iterations or `budget_s` seconds."""
+    import numpy as np
+    from oracle import ef21_oracle as oracle
+    c = workloads.CONFIGS["C3"]
+    P = oracle.LogRegCSR(W.rowptr, W.col, W.val, W.y, c["n"], c["m"], c["d"], c["lam"])
+    x0 = np.zeros(P.d)
+    st = oracle.init_state(x0, P.grads(x0), c["k"], init="grad", storage_f32=True)
+    t0 = time.perf_counter()
+    its = 0
+    while True:
+        oracle.iteration(st, P.grads, c["k"], c["gamma"], storage_f32=True)
+        its += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or its >= max_its:
+            break
+    return {"value": round(its / el, 4), "unit": "EF21 iterations/s", "cores": 1, "kind": "oracle",
+            "sample": f"{its} of the {c['iters']} iterations of C3 at full size ({el:.1f} s)"}
+
+
+def cpu_baseline_grads(workloads, workers: int = 2):
+    """The oracle on C4 at full d: one iteration with supplied gradients (the stable full sort of 11.2 million
+    magnitudes per worker takes seconds), on `workers` of the n workers; the rate is scaled to all n."""
+    import numpy as np
+    from oracle import ef21_oracle as oracle
+    c = workloads.CONFIGS["C4"]
+    n, d, k = c["n"], c["d"], c["k"]
+    grads = workloads.student_t_grads(workers, d, seed=c["seed"]).astype(np.float64)
+    st = oracle.EF21State(np.zeros(d), np.zeros((workers, d)), np.zeros(d))
+    t0 = time.perf_counter()
+    oracle.iteration(st, lambda x: grads, k, c["gamma"], storage_f32=True)
+    el = time.perf_counter() - t0
+    return {"value": round(1.0 / (el * n / workers), 5), "unit": "EF21 iterations/s (gradients supplied)", "cores": 1,
+            "kind": "oracle",
+            "sample": f"1 iteration at full d on {workers} of the {n} workers ({el:.1f} s), scaled to {n} workers"}
+
+
 def cpu_baseline_topk(workloads):
     import numpy as np
     from oracle import ef21_oracle as oracle
@@ -324,11 +426,16 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--repeats", type=int, default=5, help="timed loops of --steps steps each (median and min reported)")
     ap.add_argument("--only", default="", help="comma list of C0,C1,C2,C3,C4 (C2, the headline, always runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--print-fingerprint", action="store_true", help="print the hash of the kernel sources and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run five plain device-to-device copies of 1 GiB (reference for HBM byte counters)")
     args = ap.parse_args()
+    if args.print_fingerprint:
+        print(source_fingerprint())
+        return 0
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (workers are rows of a batch; there are no collectives); "
               "run with --gpus 1", file=sys.stderr)
@@ -352,6 +459,8 @@ def main() -> int:
     which = set(filter(None, args.only.split(","))) or {"C0", "C1", "C2", "C3", "C4"}
     K, Wm = args.steps, args.warmup
 
+    global REPEATS
+    REPEATS = max(1, args.repeats)
     ceiling = hbm_ceiling(torch, binding)
     head, (W2, h2) = bench_dense(torch, binding, workloads, "C2", K, Wm)
     extra = {}
@@ -362,28 +471,55 @@ def main() -> int:
     h2.close()
     del W2
     if "C0" in which:
-        extra["C0"], (_, h0) = bench_dense(torch, binding, workloads, "C0", K, Wm)
+        extra["C0"], (W0, h0) = bench_dense(torch, binding, workloads, "C0", K, Wm)
         h0.close()
+        if not args.no_cpu_baseline:
+            extra["C0"]["cpu_baseline"] = cpu_baseline_dense(workloads, W0, "C0")
     if "C1" in which:
         extra["C1"] = bench_topk(torch, binding, workloads, K, Wm)
         if not args.no_cpu_baseline:
             extra["C1"]["cpu_baseline"] = cpu_baseline_topk(workloads)
     if "C3" in which:
-        extra["C3"] = bench_csr(torch, binding, workloads, K, Wm)
+        extra["C3"], W3 = bench_csr(torch, binding, workloads, K, Wm)
+        if not args.no_cpu_baseline:
+            log("timing the CPU oracle on C3")
+            extra["C3"]["cpu_baseline"] = cpu_baseline_csr(workloads, W3)
+        del W3
     if "C4" in which:
         extra["C4"] = bench_grads(torch, binding, workloads, K, Wm)
+        if not args.no_cpu_baseline:
+            log("timing the CPU oracle on C4")
+            extra["C4"]["cpu_baseline"] = cpu_baseline_grads(workloads)
+
+    # the roofline fraction of every measured workload's dominant kernel, and the worst of them beside the headline's
+    by_workload = {"C2": head["roofline"]}
+    for name in ("C1", "C3", "C4"):
+        if name in extra and "roofline" in extra[name]:
+            by_workload[name] = extra[name]["roofline"]
+    worst_name = min(by_workload, key=lambda w_: by_workload[w_]["frac"])
+    iteration_fracs = {"C2": head["iteration_frac_of_hbm_peak"]}
+    for name in ("C3", "C4"):
+        if name in extra:
+            iteration_fracs[name] = extra[name]["iteration_frac_of_hbm_peak"]
 
     c2 = workloads.CONFIGS["C2"]
     line = {
         "metric": "EF21 iterations/s (whole iteration: local gradients, Top-k, state update, aggregation, model step)",
         "value": head["value"], "unit": "iterations/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": head["ms_per_step"], "ms_per_step_min": head["ms_per_step_min"], "timing": head["timing"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"C2: EF21, logistic regression + nonconvex regulariser, n={c2['n']} workers, "
                                f"d={c2['d']}, m={c2['m']} dense fp32 rows per worker, Top-k k={c2['k']}, "
                                f"gamma={c2['gamma']}, lambda={c2['lam']}", "n": c2["n"], "d": c2["d"], "m": c2["m"],
                    "k": c2["k"]},
         "roofline": head["roofline"],
+        "roofline_worst": {"workload": worst_name, **by_workload[worst_name],
+                           "note": "lowest fraction among the dominant kernels of the workloads measured in this run "
+                                   "(algorithmic bytes / HIP-event time / 8 TB/s); the headline's is the best of them"},
+        "roofline_frac_by_workload": {w_: r_["frac"] for w_, r_ in by_workload.items()},
+        "iteration_frac_of_hbm_peak_by_workload": iteration_fracs,
+        "kernel_sources": source_fingerprint(),
         "hbm_measured_ceiling": ceiling,
         "device": device_info(torch),
         "cpu_baseline": cpu,

@@ -78,9 +78,11 @@ int ef21_set_stream(ef21_handle h, void *hip_stream);
  *   out_val [n][k]  the (signed) input values at those positions
  * Exactly k pairs are produced per row even if fewer than k entries are non-zero.
  * Enqueued on `hip_stream` (NULL = null stream).  For rows longer than a few 10^4 entries the
- * call uses a device workspace that the library keeps per device and grows on demand with
- * hipMalloc (a growing call synchronises the device); concurrent ef21_topk calls on one device
- * share that workspace and must not overlap.
+ * call uses a device workspace (about 8 d + 90 000 bytes per row) that the library keeps per device and
+ * stream and grows on demand with hipMalloc (a growing call waits for that stream first).  Calls on
+ * different streams use different workspaces and may overlap; calls on one stream run one after the other.
+ * The workspaces are kept until the process ends (a device that has seen more than 16 streams frees all
+ * of its workspaces after a device-wide wait and starts over).  ef21_topk_static never allocates.
  * EF21_EINVAL: n < 1, n > 65535 (a row is a row of the launch grids), d < 1, d >= 2^31, k < 1, k > d, NULL pointer.
  */
 int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_idx, float *out_val,
@@ -162,8 +164,9 @@ int ef21_set_minibatch(ef21_handle h, const int32_t *rows, int64_t tau);
  * unit vector v of the last step approaches lambda_max from below, so few iterations give a stepsize that is
  * too large by the same factor: 100 to 300 steps bring problems without a dominant direction within about one
  * per cent.  gamma, L, L_i [n]: host memory, each may be NULL.  Uses the handle's loss, lambda and k, and all
- * rows whatever ef21_set_minibatch says; the handle's stepsize is not changed.  Allocates (n + 2) d floats for
- * the call, overwrites the handle's gradient buffer, and returns after the stream has drained.
+ * rows whatever ef21_set_minibatch says; the handle's stepsize is not changed.  The first call on a handle
+ * allocates (n + 2) d floats that the handle keeps; every call overwrites the handle's gradient buffer and
+ * returns after the stream has drained.
  * EF21_ESTATE without a problem; EF21_EINVAL: iterations outside [1, 10^6]; EF21_ENOMEM.
  */
 int ef21_theory_stepsize(ef21_handle h, int32_t iterations, double *gamma, double *L, double *L_i);

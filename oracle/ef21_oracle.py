@@ -456,6 +456,25 @@ def smoothness_constants(problem) -> np.ndarray:
     return out
 
 
+def smoothness_constant_of_f(problem) -> float:
+    """L of the smoothness assumption of Section 3.4 for f = (1/n) sum_i f_i itself, from the definition: the
+    Hessian of f is (1/(n m)) sum_i A_i^T diag(curvatures) A_i plus the regulariser's, so its gradient is Lipschitz
+    with  c * lambda_max((1/(n m)) sum_i A_i^T A_i) + 2 lam  (c and 2 as in smoothness_constants).  Never above
+    the mean of the L_i, the bound the text notes before Theorem 1.  Exact symmetric eigenvalues (numpy); CSR
+    problems are made dense, so small sizes only."""
+    if isinstance(problem, LogRegCSR):
+        A = densify_csr(problem.rowptr, problem.col, problem.val, problem.n, problem.m, problem.d)
+        c = 0.25
+    else:
+        A = problem.A
+        c = 2.0 if isinstance(problem, LeastSquaresDense) else 0.25
+    S = np.zeros((problem.d, problem.d))
+    for i in range(problem.n):
+        Ai = np.asarray(A[i], dtype=np.float64)
+        S += Ai.T @ Ai
+    return float(c * np.linalg.eigvalsh(S / (problem.n * problem.m))[-1] + 2.0 * problem.lam)
+
+
 def theory_stepsize(L_i, alpha: float, L: float = None) -> float:
     """The largest stepsize Theorem 1 allows: 1 / (L + Ltilde sqrt(beta / theta)), Ltilde the quadratic mean of
     the L_i; L defaults to their arithmetic mean (an upper bound on the smoothness constant of f, as noted

@@ -43,15 +43,23 @@ constexpr int64_t kSplitMinRow = 1 << 14;
 
 bool use_split(int64_t d) { return d >= kSplitMinRow; }
 
-// Per-device workspace of the stateless ef21_topk.
-struct SharedWorkspace {
-    std::mutex mu;
-    void *ptr[64] = {};
-    size_t bytes[64] = {};
-    int32_t last_n[64] = {};      // shape of the last call: the layout inside the workspace depends on it
-    int64_t last_d[64] = {};
+// Workspaces of the stateless ef21_topk: one per (device, stream), so that calls on different streams never share
+// one (calls on one stream run one after the other).  They live until the process ends; if a device collects more
+// than kMaxTopkStreams of them, all of that device's are freed after a device-wide wait and the list starts over.
+struct StreamWorkspace {
+    int device = -1;
+    hipStream_t stream = nullptr;
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    int32_t last_n = 0;           // shape of the last call: the layout inside the workspace depends on it
+    int64_t last_d = 0;
 };
-SharedWorkspace g_topk_ws;
+constexpr size_t kMaxTopkStreams = 16;
+struct SharedWorkspaces {
+    std::mutex mu;
+    std::vector<StreamWorkspace> list;
+};
+SharedWorkspaces g_topk_ws;
 
 // Per-device address of `scratch`.
 struct StaticScratch {
@@ -116,6 +124,9 @@ struct ef21_ctx {
     void *plus_scratch = nullptr;
     int32_t *plus_branch = nullptr; // [n]
     double *plus_bm = nullptr;      // [n][2]
+    // power iteration of ef21_theory_stepsize (allocated by the first call)
+    float *power_v = nullptr;       // [n + 2][d]
+    double *power_stats = nullptr;  // [n + 1][2]
     Timing timing;
 };
 
@@ -199,6 +210,8 @@ void free_ctx(ef21_ctx *c) {
     (void)hipFree(c->plus_scratch);
     (void)hipFree(c->plus_branch);
     (void)hipFree(c->plus_bm);
+    (void)hipFree(c->power_v);
+    (void)hipFree(c->power_stats);
     delete c;
 }
 
@@ -346,30 +359,56 @@ int ef21_topk(const float *rows, int32_t n, int64_t d, int64_t k, int32_t *out_i
     if (!rows || !out_idx || !out_val) return fail(EF21_EINVAL, "rows, out_idx and out_val must not be NULL");
     hipStream_t stream = (hipStream_t)hip_stream;
     void *ws = nullptr;
-    if (use_split(d)) {
+    if (topk_needs_workspace(d, k)) {
         int dev = 0;
         EF21_HIP(hipGetDevice(&dev));
-        if (dev < 0 || dev >= 64) return fail(EF21_ESTATE, "device ordinal out of range");
         const size_t need = ef21::topk_split_workspace_bytes(n, d, k);
         std::lock_guard<std::mutex> lock(g_topk_ws.mu);
-        if (g_topk_ws.bytes[dev] < need) {
-            EF21_HIP(hipDeviceSynchronize());
-            (void)hipFree(g_topk_ws.ptr[dev]);
-            g_topk_ws.ptr[dev] = nullptr;
-            g_topk_ws.bytes[dev] = 0;
-            if (hipMalloc(&g_topk_ws.ptr[dev], need) != hipSuccess) {
+        StreamWorkspace *mine = nullptr;
+        size_t on_device = 0;
+        for (auto &e : g_topk_ws.list) {
+            if (e.device != dev) continue;
+            ++on_device;
+            if (e.stream == stream) mine = &e;
+        }
+        if (!mine) {
+            if (on_device >= kMaxTopkStreams) {             // start over on this device
+                EF21_HIP(hipDeviceSynchronize());
+                auto &l = g_topk_ws.list;
+                for (size_t i = 0; i < l.size();) {
+                    if (l[i].device == dev) {
+                        (void)hipFree(l[i].ptr);
+                        l.erase(l.begin() + (long)i);
+                    } else {
+                        ++i;
+                    }
+                }
+            }
+            StreamWorkspace fresh;
+            fresh.device = dev;
+            fresh.stream = stream;
+            g_topk_ws.list.push_back(fresh);
+            mine = &g_topk_ws.list.back();
+        }
+        if (mine->bytes < need) {
+            // earlier calls on this stream may still be using the old block
+            EF21_HIP(hipStreamSynchronize(stream));
+            (void)hipFree(mine->ptr);
+            mine->ptr = nullptr;
+            mine->bytes = 0;
+            if (hipMalloc(&mine->ptr, need) != hipSuccess) {
                 (void)hipGetLastError();
                 return fail(EF21_ENOMEM, "hipMalloc of the Top-k workspace failed");
             }
-            g_topk_ws.bytes[dev] = need;
-            g_topk_ws.last_n[dev] = 0;
+            mine->bytes = need;
+            mine->last_n = 0;
         }
-        ws = g_topk_ws.ptr[dev];
-        if (g_topk_ws.last_n[dev] != n || g_topk_ws.last_d[dev] != d) {
+        ws = mine->ptr;
+        if (mine->last_n != n || mine->last_d != d) {
             hipError_t st = ef21::launch_topk_split_reset(ws, n, d, stream);
             if (st != hipSuccess) return fail_hip(st, "workspace reset launch");
-            g_topk_ws.last_n[dev] = n;
-            g_topk_ws.last_d[dev] = d;
+            mine->last_n = n;
+            mine->last_d = d;
         }
     }
     ef21::TopkArgs p{rows, nullptr, n, d, k, out_idx, out_val, nullptr};
@@ -550,14 +589,18 @@ int ef21_theory_stepsize(ef21_handle h, int32_t iterations, double *gamma, doubl
     const int32_t n = h->n;
     const int64_t d = h->d;
     // rows 0..n-1: the workers' vectors; row n: the vector of the whole problem; row n+1: its product
-    float *v = nullptr;
-    double *stats = nullptr;
-    if (hipMalloc((void **)&v, sizeof(float) * (size_t)(n + 2) * (size_t)d) != hipSuccess ||
-        hipMalloc((void **)&stats, sizeof(double) * 2 * (size_t)(n + 1)) != hipSuccess) {
-        (void)hipGetLastError();
-        (void)hipFree(v);
-        return fail(EF21_ENOMEM, "hipMalloc of the power iteration's vectors failed");
+    if (!h->power_v) {
+        if (hipMalloc((void **)&h->power_v, sizeof(float) * (size_t)(n + 2) * (size_t)d) != hipSuccess ||
+            hipMalloc((void **)&h->power_stats, sizeof(double) * 2 * (size_t)(n + 1)) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(h->power_v);
+            h->power_v = nullptr;
+            h->power_stats = nullptr;
+            return fail(EF21_ENOMEM, "hipMalloc of the power iteration's vectors failed");
+        }
     }
+    float *v = h->power_v;
+    double *stats = h->power_stats;
     float *v_all = v + (size_t)n * d, *w_all = v_all + d;
     int rc = EF21_OK;
     hipError_t st = ef21::launch_power_start(v, n + 1, d, h->stream);
@@ -575,9 +618,7 @@ int ef21_theory_stepsize(ef21_handle h, int32_t iterations, double *gamma, doubl
     std::vector<double> host(2 * (size_t)(n + 1));
     if (st == hipSuccess && rc == EF21_OK)
         st = hipMemcpyAsync(host.data(), stats, sizeof(double) * host.size(), hipMemcpyDeviceToHost, h->stream);
-    const hipError_t sync = hipStreamSynchronize(h->stream);        // also before the vectors are freed
-    (void)hipFree(v);
-    (void)hipFree(stats);
+    const hipError_t sync = hipStreamSynchronize(h->stream);
     if (rc != EF21_OK) return rc;
     if (st != hipSuccess) return fail_hip(st, "power iteration");
     if (sync != hipSuccess) return fail_hip(sync, "power iteration");

@@ -327,8 +327,9 @@ def test_config4_scaled_run(gpu, oracle):
 
 @pytest.mark.timeout(600)
 def test_config4_full_size_step(gpu, oracle):
-    """Config 4 at full size (n = 8, d = 11.2e6, k = 112000): two steps; three workers' messages and
-    g_i rows are compared one by one with the oracle, the rest through invariants."""
+    """Config 4 at full size (n = 8, d = 11.2e6, k = 112000): two steps.  First step (threshold from the sample):
+    the messages and g_i rows of all eight workers one by one against the oracle.  Second step (threshold guessed
+    from the first step's): three workers one by one, the rest through invariants."""
     torch, binding = gpu
     c = workloads.CONFIGS["C4"]
     n, d, k, gamma = c["n"], c["d"], c["k"], c["gamma"]
@@ -343,7 +344,7 @@ def test_config4_full_size_step(gpu, oracle):
             torch.cuda.synchronize()
             idx, val = (a.cpu().numpy() for a in h.get_messages())
             x, g_i, g = (a.cpu().numpy() for a in h.get_state())
-            for i in rows:
+            for i in (range(n) if t == 0 else rows):
                 v = grads[i] - g_i_ref[i]                       # fp32 subtraction, as in line 5
                 ref_idx, ref_val = oracle.topk(v.astype(np.float64), k)
                 assert np.array_equal(idx[i], ref_idx), f"step {t} worker {i}"
@@ -368,6 +369,77 @@ def test_config4_full_size_step(gpu, oracle):
             mean = g_i.astype(np.float64).mean(axis=0)
             assert np.all(np.abs(g - mean) <= 1e-5 * np.abs(mean) + budget.g + line6)
             g_prev = g.astype(np.float64)
+
+
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("order", ["grad_first", "step_first"])
+def test_config3_shape_single_steps(gpu, oracle, order):
+    """Exactly the shape of config 3's Top-k and update (n = 100, d = 50 000, k = 500), gradients supplied: two
+    consecutive steps element by element (the second collects with the first one's threshold as the guess)."""
+    torch, binding = gpu
+    c = workloads.CONFIGS["C3"]
+    n, d, k, gamma = c["n"], c["d"], c["k"], c["gamma"]
+    print(f"C3 shape single steps {order}", flush=True)
+    rng = np.random.default_rng(33)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    g_i0 = (0.1 * rng.standard_normal((n, d))).astype(np.float32)
+    g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    budget = RoundingBudget(n, d, gamma)
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+        for t in range(2):
+            grads = (st.g_i + 0.1 * rng.standard_normal((n, d)) * rng.choice([0.2, 1.0, 3.0], size=(n, 1))).astype(np.float32)
+            oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma, order)
+            h.step(to_gpu(torch, grads), binding.ORDER_GRAD_FIRST if order == "grad_first" else binding.ORDER_STEP_FIRST)
+            torch.cuda.synchronize()
+            compare_state(torch, h, st, budget)
+            h.set_state(to_gpu(torch, st.x), None, to_gpu(torch, st.g))
+            budget.reset()
+
+
+@pytest.mark.timeout(400)
+def test_config3_shape_step_with_internal_csr_gradient(gpu, oracle):
+    """ef21_step(NULL) on a CSR problem of config 3's shape (n = 100, d = 50 000, k = 500, 500 entries per row; 120
+    rows per worker so that the oracle finishes in seconds).  The library's gradients of sampled workers against
+    the oracle's (1e-5 and the rounding floor); then, because the last bits of a gradient may move a near-tie, the
+    step itself against the oracle's lines 5, 6, 8, 3 applied to the library's own gradients: every worker's
+    message and g_i row bit for bit, g and x within the budget."""
+    from helpers import gradient_rounding_floor
+    torch, binding = gpu
+    c = workloads.CONFIGS["C3"]
+    n, d, k, gamma, m, nnz = c["n"], c["d"], c["k"], c["gamma"], 120, c["nnz_per_row"]
+    print("C3 shape step with CSR gradients", flush=True)
+    W = workloads.logreg_csr(n, d, m, nnz, seed=11)
+    P = oracle.LogRegCSR(W.rowptr, W.col, W.val, W.y, n, m, d, c["lam"])
+    rng = np.random.default_rng(12)
+    x0 = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    g_i0 = (1e-3 * rng.standard_normal((n, d))).astype(np.float32)
+    g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
+    budget = RoundingBudget(n, d, gamma)
+    import scipy.sparse as sp
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_problem_csr(to_gpu(torch, W.rowptr, np.int64), to_gpu(torch, W.col, np.int32), to_gpu(torch, W.val),
+                          to_gpu(torch, W.y), m, c["lam"])
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), to_gpu(torch, g0))
+        for t in range(2):
+            x_now = h.get_x()
+            grads = h.local_grad(x_now).cpu().numpy()
+            for i in (0, 37, 99):
+                ref = P.grad_i(i, x_now.cpu().numpy().astype(np.float64))
+                A_i = sp.csr_matrix((W.val[W.rowptr[i * m]:W.rowptr[(i + 1) * m]],
+                                     W.col[W.rowptr[i * m]:W.rowptr[(i + 1) * m]],
+                                     W.rowptr[i * m:(i + 1) * m + 1] - W.rowptr[i * m]), shape=(m, d))
+                bound = 1e-5 * np.abs(ref) + gradient_rounding_floor(A_i, W.y[i], x_now.cpu().numpy(), nnz / 64 + 8, 64,
+                                                                     c["lam"])
+                assert np.all(np.abs(grads[i] - ref) <= bound), f"step {t}: gradient of worker {i}"
+            oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma)
+            h.step()
+            torch.cuda.synchronize()
+            compare_state(torch, h, st, budget)
+            h.set_state(to_gpu(torch, st.x), None, to_gpu(torch, st.g))
+            budget.reset()
 
 
 @pytest.mark.timeout(400)

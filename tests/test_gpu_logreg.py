@@ -19,6 +19,9 @@ def gpu():
     return torch, binding
 
 
+GUARD = 2e-5    # the median allowance of a gradient entry, as a share of the gradient's largest entry
+
+
 def to_gpu(torch, a, dtype=np.float32):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
 
@@ -30,7 +33,10 @@ def assert_grads_close(got, ref, A_dense, y, x, dot_depth, sum_depth, what):
         err = np.abs(got[i].astype(np.float64) - ref[i])
         assert np.all(err <= bound), f"{what}, worker {i}: max err {err.max():.3e}, {int((err > bound).sum())} bad"
         # the floor must stay a floor: tiny next to the gradient's scale
-        assert np.median(bound) <= 5e-5 * np.max(np.abs(ref[i])), f"{what}: tolerance too loose"
+        loose = np.median(bound) / np.max(np.abs(ref[i]))
+        print(f"  {what}, worker {i}: worst coordinate uses {np.max(err / np.maximum(bound, 1e-300)):.3f} of its allowance; "
+              f"median allowance {loose:.2e} of the largest entry", flush=True)
+        assert loose <= GUARD, f"{what}: tolerance too loose"
 
 
 def densify(W):
@@ -216,6 +222,6 @@ def test_config3_full_size_gradient(gpu, oracle):
         bound = 1e-5 * np.abs(ref[i]) + gradient_rounding_floor(A_i, W.y[i], x, nnz / 64 + 8, 64)
         err = np.abs(got[i].astype(np.float64) - ref[i])
         assert np.all(err <= bound), f"worker {i}: max err {err.max():.3e}, {int((err > bound).sum())} bad"
-        assert np.median(bound) <= 5e-5 * np.max(np.abs(ref[i]))
+        assert np.median(bound) <= 2e-5 * np.max(np.abs(ref[i]))
     rel = np.linalg.norm(got - ref, axis=1) / np.linalg.norm(ref, axis=1)
     assert rel.max() <= 1e-6, f"relative error of the gradients in the 2-norm: {rel.max():.3e}"

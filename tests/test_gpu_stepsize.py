@@ -28,14 +28,6 @@ def check(got, exact, below, what):
     assert np.all(got >= exact * (1 - below)), f"{what}: {got} vs {exact}"
 
 
-def exact_L(oracle, P, A):
-    """c lambda_max of the averaged matrix (1/(n m)) sum_i A_i^T A_i, + 2 lam."""
-    n, m, d = A.shape
-    S = A.reshape(n * m, d).astype(np.float64)
-    c = 2.0 if isinstance(P, oracle.LeastSquaresDense) else 0.25
-    return c * np.linalg.eigvalsh(S.T @ S / (n * m))[-1] + 2.0 * P.lam
-
-
 @pytest.mark.parametrize("n,d,m,k", [(4, 100, 250, 3), (3, 333, 41, 10), (2, 4100, 29, 41)])
 @pytest.mark.parametrize("loss", ["logistic", "squares"])
 def test_dense_with_a_dominant_direction(gpu, oracle, n, d, m, k, loss):
@@ -55,7 +47,7 @@ def test_dense_with_a_dominant_direction(gpu, oracle, n, d, m, k, loss):
             h.set_loss(binding.LOSS_LEAST_SQUARES)
         gamma, L, got_i = h.theory_stepsize(150)
     check(got_i, L_i, 1e-4, "L_i")
-    L_exact = exact_L(oracle, P, A)
+    L_exact = oracle.smoothness_constant_of_f(P)
     check([L], [L_exact], 1e-4, "L")
     ref = oracle.theory_stepsize(L_i, k / d, L=L_exact)
     assert ref * (1 - 2e-6) <= gamma <= ref * (1 + 2e-4)
@@ -75,7 +67,7 @@ def test_dense_without_a_dominant_direction(gpu, oracle):
     check(many[2], L_i, 2e-2, "L_i after 300 steps")
     check(few[2], L_i, 0.6, "L_i after 5 steps")
     assert np.all(np.asarray(few[2]) <= np.asarray(many[2]) * (1 + 1e-6))     # the estimate grows with the steps
-    ref = oracle.theory_stepsize(L_i, k / d, L=exact_L(oracle, P, np.asarray(W.A).reshape(n, m, d)))
+    ref = oracle.theory_stepsize(L_i, k / d, L=oracle.smoothness_constant_of_f(P))
     assert ref * (1 - 2e-6) <= many[0] <= ref * 1.03
 
 
@@ -96,8 +88,7 @@ def test_csr(gpu, oracle, sorted_cols):
                           to_gpu(torch, W.y), m, 0.05)
         gamma, L, got_i = h.theory_stepsize(200)
     check(got_i, L_i, 1e-3, "L_i")
-    D = oracle.densify_csr(W.rowptr, col, val, n, m, d)
-    L_exact = exact_L(oracle, P, D)
+    L_exact = oracle.smoothness_constant_of_f(P)
     check([L], [L_exact], 1e-3, "L")
     ref = oracle.theory_stepsize(L_i, k / d, L=L_exact)
     assert ref * (1 - 2e-6) <= gamma <= ref * (1 + 2e-3)

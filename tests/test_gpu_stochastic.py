@@ -44,7 +44,7 @@ def assert_estimators_close(got, ref, A, y, batch, x, dot_depth, sum_depth, lam,
         bound = 1e-5 * np.abs(ref[i]) + floor
         err = np.abs(got[i].astype(np.float64) - ref[i])
         assert np.all(err <= bound), f"{what}, worker {i}: max err {err.max():.3e}, {int((err > bound).sum())} bad"
-        assert np.median(bound) <= 5e-5 * np.max(np.abs(ref[i])), f"{what}: tolerance too loose"
+        assert np.median(bound) <= 2e-5 * np.max(np.abs(ref[i])), f"{what}: tolerance too loose"
 
 
 @pytest.mark.parametrize("n,d,m,tau", [(4, 100, 250, 32), (3, 256, 37, 5), (2, 333, 41, 40), (5, 2000, 301, 64),

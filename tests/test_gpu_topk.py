@@ -214,3 +214,29 @@ def test_error_codes(gpu):
         assert e.value.code == binding.EF21_EINVAL
     with pytest.raises(TypeError):
         binding.ef21_topk(V.double(), 1)
+
+
+def test_calls_on_two_streams_overlap_safely(gpu, oracle):
+    """ef21_topk keeps one workspace per stream: calls enqueued on two streams without any ordering between them
+    (long rows, so both use a workspace) must each give their own input's selection."""
+    torch, binding = gpu
+    n, d, k = 6, 400_000, 4000
+    A = torch.from_numpy(workloads.topk_rows(n, d, seed=21)).cuda()
+    B = torch.from_numpy(workloads.topk_rows(n, d, seed=22)).cuda()
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for rep in range(6):
+        with torch.cuda.stream(s1):
+            ia, va = binding.ef21_topk(A, k)
+        with torch.cuda.stream(s2):
+            ib, vb = binding.ef21_topk(B, k + rep)
+        outs.append((ia, va, ib, vb))
+    torch.cuda.synchronize()
+    ref_a = oracle.topk(A[2].cpu().numpy().astype(np.float64), k)
+    for rep, (ia, va, ib, vb) in enumerate(outs):
+        assert np.array_equal(ia[2].cpu().numpy(), ref_a[0]) and same_bits(va[2].cpu().numpy(), ref_a[1].astype(np.float32))
+        ref_b = oracle.topk(B[4].cpu().numpy().astype(np.float64), k + rep)
+        assert np.array_equal(ib[4].cpu().numpy(), ref_b[0]) and same_bits(vb[4].cpu().numpy(), ref_b[1].astype(np.float32))
+        assert same_bits(va.cpu().numpy(), np.take_along_axis(A.cpu().numpy(), ia.cpu().numpy().astype(np.int64), axis=1))
+        assert same_bits(vb.cpu().numpy(), np.take_along_axis(B.cpu().numpy(), ib.cpu().numpy().astype(np.int64), axis=1))

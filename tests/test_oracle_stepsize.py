@@ -33,6 +33,45 @@ def test_gradients_are_lipschitz_with_these_constants(oracle, kind, lam):
     assert np.all(worst >= 0.2 * L)          # and they are not orders of magnitude too large
 
 
+@pytest.mark.parametrize("kind", ["logistic", "squares"])
+@pytest.mark.parametrize("lam", [0.0, 0.3])
+def test_constant_of_f_is_a_lipschitz_constant_below_the_mean(oracle, kind, lam):
+    """f = (1/n) sum f_i: its gradient (the mean of the workers') changes by at most L |x - y| on random pairs,
+    L is never above the mean of the L_i (the remark before Theorem 1) and never below any bound a pair shows."""
+    P, rng = make(oracle, kind, 3, lam)
+    L, L_i = oracle.smoothness_constant_of_f(P), oracle.smoothness_constants(P)
+    assert L <= np.mean(L_i) * (1 + 1e-12)
+    assert L >= np.min(L_i) / P.n            # one worker's share of the mean alone
+    worst = 0.0
+    for _ in range(200):
+        x, y = rng.standard_normal(P.d) * rng.choice([0.01, 1.0, 5.0]), rng.standard_normal(P.d) * rng.choice([0.01, 1.0])
+        ratio = np.linalg.norm(P.grads(x).mean(axis=0) - P.grads(y).mean(axis=0)) / np.linalg.norm(x - y)
+        assert ratio <= L * (1 + 1e-12)
+        worst = max(worst, ratio)
+    assert worst >= 0.2 * L
+
+
+def test_constant_of_f_is_attained(oracle):
+    """lam = 0: along the top eigenvector v of the averaged matrix the quadratic's mean gradient changes by
+    exactly L |v|; the logistic loss has curvature 1/4 at margin zero, so at x = 0 the change per unit step tends
+    to L.  And a regulariser adds exactly 2 lam (its curvature at 0 is 2, the largest it has)."""
+    for kind in ("squares", "logistic"):
+        P, _ = make(oracle, kind, 4, 0.0)
+        L = oracle.smoothness_constant_of_f(P)
+        S = sum(np.asarray(P.A[i], np.float64).T @ np.asarray(P.A[i], np.float64) for i in range(P.n)) / (P.n * P.m)
+        v = np.linalg.eigh(S)[1][:, -1]
+        h = 1.0 if kind == "squares" else 1e-4
+        change = np.linalg.norm(P.grads(h * v).mean(axis=0) - P.grads(0 * v).mean(axis=0)) / h
+        assert abs(change - L) <= (1e-12 if kind == "squares" else 1e-6) * L
+        Q, _ = make(oracle, kind, 4, 0.3)
+        assert abs(oracle.smoothness_constant_of_f(Q) - (L + 0.6)) <= 1e-12 * L
+    # one worker: f is f_1
+    rng = np.random.default_rng(0)
+    A = rng.standard_normal((1, 30, 5)).astype(np.float32)
+    P1 = oracle.LogRegDense(A, np.ones((1, 30), np.float32), 0.2)
+    assert abs(oracle.smoothness_constant_of_f(P1) - oracle.smoothness_constants(P1)[0]) <= 1e-12
+
+
 def test_constants_are_attained(oracle):
     """lam = 0: the quadratic's gradient changes by exactly L_i |v| along the top eigenvector v; the logistic
     loss has curvature 1/4 at margin zero, so at x = 0 the change per unit step tends to L_i."""
