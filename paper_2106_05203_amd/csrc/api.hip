@@ -113,6 +113,7 @@ struct ef21_ctx {
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
     void *topk_ws = nullptr;
+    void *topk_ws2 = nullptr;       // second long-row workspace: the plain compressor of Algorithm 3
     void *agg_index = nullptr;      // runs of the messages per coordinate sub-block (scratch of line 8)
     void *tickets = nullptr;        // counters of the one-launch iteration (zero between launches)
     void *csr_index = nullptr;      // column-range index of the attached CSR problem
@@ -202,6 +203,7 @@ void free_ctx(ef21_ctx *c) {
     (void)hipFree(c->grad);
     (void)hipFree(c->scratch);
     (void)hipFree(c->topk_ws);
+    (void)hipFree(c->topk_ws2);
     (void)hipFree(c->csr_index);
     (void)hipFree(c->agg_index);
     (void)hipFree(c->tickets);
@@ -648,13 +650,17 @@ static int ensure_plus_buffers(ef21_ctx *c) {
         hipMalloc((void **)&c->plus_val, sizeof(float) * 2 * nk) != hipSuccess ||
         hipMalloc(&c->plus_scratch, ef21::plus_scratch_bytes(c->n, c->d, c->k)) != hipSuccess ||
         hipMalloc((void **)&c->plus_branch, sizeof(int32_t) * (size_t)c->n) != hipSuccess ||
-        hipMalloc((void **)&c->plus_bm, sizeof(double) * 2 * (size_t)c->n) != hipSuccess) {
+        hipMalloc((void **)&c->plus_bm, sizeof(double) * 2 * (size_t)c->n) != hipSuccess ||
+        (c->topk_ws && c->k > 1 &&
+         alloc_split_workspace(&c->topk_ws2, ef21::topk_split_workspace_bytes(c->n, c->d, c->k), c->n, c->d) != hipSuccess)) {
         (void)hipGetLastError();
         (void)hipFree(c->plus_idx);
         (void)hipFree(c->plus_val);
         (void)hipFree(c->plus_scratch);
         (void)hipFree(c->plus_branch);
         (void)hipFree(c->plus_bm);
+        (void)hipFree(c->topk_ws2);
+        c->topk_ws2 = nullptr;
         c->plus_idx = nullptr;
         c->plus_val = nullptr;
         c->plus_scratch = nullptr;
@@ -672,13 +678,23 @@ static int enqueue_plus(ef21_ctx *h, const float *grads, const ef21::Marker &mk)
     float *val_b = h->plus_val, *val_m = h->plus_val + nk;
     ef21::TopkArgs plain{grads, nullptr, h->n, h->d, h->k, idx_b, val_b, nullptr};        // line 5: C(s)
     plain.warm = 2;
-    if (int rc = enqueue_topk(plain, h->topk_ws, h->stream, mk)) return rc;
     ef21::TopkArgs markov{grads, h->g_i, h->n, h->d, h->k, idx_m, val_m, nullptr};        // line 6: C(s - g_i)
     markov.warm = 1;
-    if (int rc = enqueue_topk(markov, h->topk_ws, h->stream, mk)) return rc;
-    hipError_t st = ef21::launch_plus_choose(grads, h->g_i, h->n, h->d, h->k, idx_b, val_b, idx_m, val_m,
-                                             h->plus_scratch, h->plus_branch, h->plus_bm, h->msg_idx, h->msg_val,
-                                             h->stream);                                  // lines 7 and 8
+    int64_t norm_chunks = 0;
+    hipError_t st;
+    if (h->topk_ws2) {
+        // long rows: both selections and the two squared norms of line 7 from ONE pass over s and g_i
+        plain.warm = 1;           // each workspace keeps its own thresholds
+        st = ef21::launch_topk_split_pair(plain, markov, h->topk_ws2, h->topk_ws, h->plus_scratch, h->stream, mk);
+        if (st != hipSuccess) return fail_hip(st, "Top-k kernel launch");
+        norm_chunks = ef21::topk_split_slots(h->n, h->d);
+    } else {
+        if (int rc = enqueue_topk(plain, h->topk_ws, h->stream, mk)) return rc;
+        if (int rc = enqueue_topk(markov, h->topk_ws, h->stream, mk)) return rc;
+    }
+    st = ef21::launch_plus_choose(grads, h->g_i, h->n, h->d, h->k, idx_b, val_b, idx_m, val_m, h->plus_scratch,
+                                  h->plus_branch, h->plus_bm, h->msg_idx, h->msg_val, h->stream,
+                                  norm_chunks);                                            // lines 7 and 8
     if (st == hipSuccess) st = ef21::launch_mean_rows(h->g_i, h->g, h->n, h->d, h->stream);   // line 10
     mk(ef21::K_PLUS);
     if (st != hipSuccess) return fail_hip(st, "EF21+ kernel launch");

@@ -6,6 +6,8 @@
 //           up to the rounding of one fp32 addition), differences and sums in fp64, in a fixed order;
 //   line 8  g_i <- m if M <= B, else b: a sparse update, or a rewrite of the whole row;
 //   line 10 g = (1/n) sum_i g_i is then recomputed from the rows (launch_mean_rows).
+#include <algorithm>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -199,36 +201,44 @@ int64_t kept_blocks_of(int64_t k) { return (k + kKeptBlock - 1) / kKeptBlock; }
 
 }  // namespace
 
+// room for the norm partials of either producer: the norm kernel's chunks, or one per piece of the long-row Top-k
+int64_t plus_norm_chunks_max(int32_t n, int64_t d) { return std::max<int64_t>(chunks_of(d), topk_split_slots(n, d)); }
+
 size_t plus_scratch_bytes(int32_t n, int64_t d, int64_t k) {
-    return sizeof(double2) * (size_t)n * (size_t)(chunks_of(d) + kept_blocks_of(k));
+    return sizeof(double2) * (size_t)n * (size_t)(plus_norm_chunks_max(n, d) + kept_blocks_of(k));
 }
 
 hipError_t launch_plus_choose(const float *s, float *g_i, int32_t n, int64_t d, int64_t k, const int32_t *idx_b,
                               const float *val_b, const int32_t *idx_m, const float *val_m, void *scratch,
-                              int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream) {
-    const int64_t chunks = chunks_of(d);
+                              int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream,
+                              int64_t norm_chunks) {
+    if (norm_chunks < 0 || norm_chunks > plus_norm_chunks_max(n, d)) return hipErrorInvalidValue;
+    const int64_t chunks = norm_chunks > 0 ? norm_chunks : chunks_of(d), grid_chunks = chunks_of(d);
     double2 *part = (double2 *)scratch;
     // kNormChunk is a multiple of four, so with d % 4 == 0 every chunk is whole float4s
     const bool vec4 = (d % 4 == 0) && (((uintptr_t)s | (uintptr_t)g_i) % 16 == 0);
-    if (vec4)
+    if (norm_chunks > 0) {
+        // the partial sums are already there
+    } else if (vec4) {
         hipLaunchKernelGGL(plus_sqnorms_kernel<4>, dim3((unsigned)chunks, (unsigned)n), dim3(kThreads), 0, stream, s,
                            g_i, d, part);
-    else
+    } else {
         hipLaunchKernelGGL(plus_sqnorms_kernel<1>, dim3((unsigned)chunks, (unsigned)n), dim3(kThreads), 0, stream, s,
                            g_i, d, part);
+    }
     const int64_t kblocks = k <= kKeptBlock ? 0 : kept_blocks_of(k);     // short messages: summed by the decide kernel
-    double2 *kept = part + (size_t)n * chunks;
+    double2 *kept = part + (size_t)n * plus_norm_chunks_max(n, d);
     if (kblocks > 0)
         hipLaunchKernelGGL(plus_kept_kernel, dim3((unsigned)kblocks, (unsigned)n), dim3(kThreads), 0, stream, s, g_i,
                            d, val_b, idx_m, k, kept);
     hipLaunchKernelGGL(plus_decide_kernel, dim3((unsigned)n), dim3(kThreads), 0, stream, part, chunks, kept, kblocks, s,
                        g_i, d, val_b, idx_m, k, branch, BM);
     if (vec4)
-        hipLaunchKernelGGL(plus_clear_kernel<4>, dim3((unsigned)chunks, (unsigned)n), dim3(kThreads), 0, stream, branch,
-                           g_i, d);
+        hipLaunchKernelGGL(plus_clear_kernel<4>, dim3((unsigned)grid_chunks, (unsigned)n), dim3(kThreads), 0, stream,
+                           branch, g_i, d);
     else
-        hipLaunchKernelGGL(plus_clear_kernel<1>, dim3((unsigned)chunks, (unsigned)n), dim3(kThreads), 0, stream, branch,
-                           g_i, d);
+        hipLaunchKernelGGL(plus_clear_kernel<1>, dim3((unsigned)grid_chunks, (unsigned)n), dim3(kThreads), 0, stream,
+                           branch, g_i, d);
     int64_t blocks = (k + kThreads - 1) / kThreads;
     if (blocks > 256) blocks = 256;
     hipLaunchKernelGGL(plus_apply_kernel, dim3((unsigned)blocks, (unsigned)n), dim3(kThreads), 0, stream, branch,

@@ -104,6 +104,14 @@ hipError_t launch_topk_row16(const TopkArgs &p, hipStream_t stream);
 // Many workgroups per row for long rows.  Workspace layout and size: topk_split_workspace_bytes.
 size_t topk_split_workspace_bytes(int32_t n, int64_t d, int64_t k);
 hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t stream, const Marker &mk = Marker());
+// Two selections of one pass over the same arrays (Algorithm 3, lines 5 to 7): `plain` selects from the rows of a,
+// `markov` from a - b (plain.a == markov.a, plain.b == nullptr, same n, d, k >= 2, no g_i update, warm both or
+// neither), each with a workspace of its own; norm_parts receives, per row and per piece of the row
+// (topk_split_slots(n, d) pieces), the pair (sum a^2, sum (a - b)^2), differences taken exactly and sums in fp64
+// in a fixed order: double2 [n][topk_split_slots].
+int64_t topk_split_slots(int32_t n, int64_t d);
+hipError_t launch_topk_split_pair(const TopkArgs &plain, const TopkArgs &markov, void *ws_plain, void *ws_markov,
+                                  void *norm_parts, hipStream_t stream, const Marker &mk = Marker());
 // The kernels keep the workspace's histograms and tickets zeroed as long as (n, d) stay the same.
 // A workspace that is new, or was last used with another (n, d), needs this reset first.
 hipError_t launch_topk_split_reset(void *workspace, int32_t n, int64_t d, hipStream_t stream);
@@ -177,11 +185,15 @@ hipError_t launch_small_step(const float *A, const float *y, float *x, float *g,
 // Algorithm 3 (EF21+), lines 7 and 8, for all workers: from the gradients s [n][d], the estimators g_i [n][d]
 // (updated in place) and the two Top-k results (idx_b, val_b) = C(s), (idx_m, val_m) = C(s - g_i), all [n][k]:
 // BM[i] = (B_i, M_i), branch[i] = 1 where the plain compressor wins (M_i > B_i), (msg_idx, msg_val) = the chosen
-// pairs, and g_i <- b or m accordingly.  scratch: plus_scratch_bytes(n, d, k) bytes.
+// pairs, and g_i <- b or m accordingly.  scratch: plus_scratch_bytes(n, d, k) bytes.  If norm_chunks > 0 the
+// leading double2 [n][norm_chunks] of scratch already hold partial sums of (s^2, (s - g_i)^2) per row (from
+// launch_topk_split_pair; norm_chunks <= plus_norm_chunks_max(n, d)) and the pass over s and g_i is skipped.
 size_t plus_scratch_bytes(int32_t n, int64_t d, int64_t k);
+int64_t plus_norm_chunks_max(int32_t n, int64_t d);
 hipError_t launch_plus_choose(const float *s, float *g_i, int32_t n, int64_t d, int64_t k, const int32_t *idx_b,
                               const float *val_b, const int32_t *idx_m, const float *val_m, void *scratch,
-                              int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream);
+                              int32_t *branch, double *BM, int32_t *msg_idx, float *msg_val, hipStream_t stream,
+                              int64_t norm_chunks = 0);
 
 // Power iteration for the smoothness constants of Section 3.4: v [rows][d] <- a fixed positive start vector;
 // and one step: stats[row] = (v^T w / v^T v, |w| / |v|) as two doubles, v <- w / |w|, for w = M v, M symmetric

@@ -412,6 +412,153 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
     if (row_total && threadIdx.x == 0 && wg_total) atomicAdd(row_total, wg_total);
 }
 
+// ---------------------------------------------------------------- collect, two selections in one pass
+// Algorithm 3 (EF21+) selects from two vectors built of the same arrays: the gradient s itself (line 5) and the
+// difference s - g_i (line 6), and needs the squared norms of both (line 7).  This kernel reads s and g_i once
+// and does the work of two collect passes and of the norm pass: candidates, histograms and slot counts of the
+// difference go to workspace `wm` (arguments pm: a = s, b = g_i), those of s to workspace `wp` (warm-start memory
+// warm_p), and every wavefront leaves (sum s^2, sum (s - g_i)^2) over its piece in norms[row][slot], the
+// differences of the stored values taken exactly in fp64 and the sums in a fixed order.
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+template <int VEC, bool WARM>
+__global__ __launch_bounds__(kBlk) void split_collect_pair_kernel(TopkArgs pm, Ws wm, int warm_p, Ws wp,
+                                                                  double2 *__restrict__ norms) {
+    __shared__ RowShared s;                      // its histogram serves the sampling, then the difference
+    __shared__ uint32_t hist_p[kHistBins];
+    __shared__ StageRing rings_m[kBlkWaves], rings_p[kBlkWaves];
+    __shared__ uint32_t wg_total_m, wg_total_p;
+    const int64_t row = blockIdx.y, d = pm.d;
+    const float *a = pm.a + row * d, *b = pm.b + row * d;
+    RowInfo *info_m = wm.info + row, *info_p = wp.info + row;
+    CandFilter fm, fp;
+    fm.hist = s.hist;
+    fp.hist = hist_p;
+    const bool warm_m = WARM && info_m->warm_ok[pm.warm - 1] != 0u, warm_pl = WARM && info_p->warm_ok[warm_p - 1] != 0u;
+    if (warm_m) {
+        const uint32_t T = info_m->warm_T[pm.warm - 1];
+        fm.key_lo = T > kWarmBelow ? T - kWarmBelow : 0u;
+        fm.shift = kShiftWarm;
+    } else {
+        fm.key_lo = estimate_key_lo<true>(s, a, b, d, pm.k);
+        fm.shift = kShiftCold;
+    }
+    if (warm_pl) {
+        const uint32_t T = info_p->warm_T[warm_p - 1];
+        fp.key_lo = T > kWarmBelow ? T - kWarmBelow : 0u;
+        fp.shift = kShiftWarm;
+    } else {
+        fp.key_lo = estimate_key_lo<false>(s, a, nullptr, d, pm.k);
+        fp.shift = kShiftCold;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        info_m->key_lo = fm.key_lo; info_m->shift = fm.shift; info_m->use2 = 0u; info_m->ntie = 0u;
+        info_m->warm_used = warm_m ? 1u : 0u;
+        info_p->key_lo = fp.key_lo; info_p->shift = fp.shift; info_p->use2 = 0u; info_p->ntie = 0u;
+        info_p->warm_used = warm_pl ? 1u : 0u;
+    }
+    for (int i = threadIdx.x; i < kHistBins; i += kBlk) {
+        s.hist[i] = 0u;
+        hist_p[i] = 0u;
+    }
+    if (threadIdx.x == 0) {
+        wg_total_m = 0u;
+        wg_total_p = 0u;
+    }
+    __syncthreads();
+
+    const int wave = threadIdx.x / kWave, lane = lane_id();
+    const int64_t slot_no = (int64_t)blockIdx.x * kBlkWaves + wave;
+    if (slot_no < wm.nslot) {
+        StageRing &ring_m = rings_m[wave], &ring_p = rings_p[wave];
+        const int64_t lo = slot_no * wm.L;
+        const int64_t hi = lo + wm.L < d ? lo + wm.L : d;
+        uint2 *slot_m = wm.cand + (row * wm.nslot + slot_no) * wm.L;
+        uint2 *slot_p = wp.cand + (row * wp.nslot + slot_no) * wp.L;
+        uint32_t cnt_m = 0, flushed_m = 0, cnt_p = 0, flushed_p = 0;
+        double sq_s = 0.0, sq_v = 0.0;
+        constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
+        int64_t base = lo;
+        for (; base + kGroup <= hi; base += kGroup) {
+            float vs[kUnroll][VEC], vd[kUnroll][VEC];
+            if constexpr (VEC == 4) {
+                float4 va[kUnroll], vb[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    va[u] = stream_load4(a + base + u * kStep + lane * 4);
+                    vb[u] = stream_load4(b + base + u * kStep + lane * 4);
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    vs[u][0] = va[u].x; vs[u][1] = va[u].y; vs[u][2] = va[u].z; vs[u][3] = va[u].w;
+                    vd[u][0] = vb[u].x; vd[u][1] = vb[u].y; vd[u][2] = vb[u].z; vd[u][3] = vb[u].w;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    vs[u][0] = stream_load(a + base + u * kStep + lane);
+                    vd[u][0] = stream_load(b + base + u * kStep + lane);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) {
+                    const double sv = (double)vs[u][t], dv = sv - (double)vd[u][t];      // exact
+                    sq_s += sv * sv;
+                    sq_v += dv * dv;
+                    vd[u][t] = vs[u][t] - vd[u][t];                                      // line 6: one fp32 subtraction
+                }
+                const int64_t e0 = base + u * kStep + lane * VEC;
+                append_candidates<VEC, true>(vs[u], e0, hi, fp, ring_p, lane, slot_p, cnt_p, flushed_p);
+                append_candidates<VEC, true>(vd[u], e0, hi, fm, ring_m, lane, slot_m, cnt_m, flushed_m);
+            }
+        }
+        for (; base < hi; base += kStep) {           // checked tail, entry by entry
+            const int64_t e0 = base + lane * VEC;
+            float vs[VEC], vd[VEC];
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) {
+                const bool in = e0 + t < hi;
+                const float sv = in ? a[e0 + t] : 0.f, bv = in ? b[e0 + t] : 0.f;
+                const double dv = (double)sv - (double)bv;
+                sq_s += (double)sv * (double)sv;
+                sq_v += dv * dv;
+                vs[t] = sv;
+                vd[t] = sv - bv;
+            }
+            append_candidates<VEC, false>(vs, e0, hi, fp, ring_p, lane, slot_p, cnt_p, flushed_p);
+            append_candidates<VEC, false>(vd, e0, hi, fm, ring_m, lane, slot_m, cnt_m, flushed_m);
+        }
+        drain_ring(ring_p, flushed_p, cnt_p, lane, slot_p, fp);
+        drain_ring(ring_m, flushed_m, cnt_m, lane, slot_m, fm);
+        sq_s = wave_sum_f64(sq_s);
+        sq_v = wave_sum_f64(sq_v);
+        if (lane == 0) {
+            wm.slot_cnt[row * wm.nslot + slot_no] = cnt_m;
+            wp.slot_cnt[row * wp.nslot + slot_no] = cnt_p;
+            atomicAdd(&wg_total_m, cnt_m);
+            atomicAdd(&wg_total_p, cnt_p);
+            norms[row * wm.nslot + slot_no] = make_double2(sq_s, sq_v);
+        }
+    }
+    __syncthreads();
+    uint32_t *merged_m = wm.hist_a + row * kHistBins, *merged_p = wp.hist_a + row * kHistBins;
+    for (int i = threadIdx.x; i < kHistBins; i += kBlk) {
+        const uint32_t cm = s.hist[i], cp = hist_p[i];
+        if (cm) atomicAdd(merged_m + i, cm);
+        if (cp) atomicAdd(merged_p + i, cp);
+    }
+    if (threadIdx.x == 0) {
+        if (wg_total_m) atomicAdd(&info_m->M, wg_total_m);
+        if (wg_total_p) atomicAdd(&info_p->M, wg_total_p);
+    }
+}
+
 // ---------------------------------------------------------------- count
 // A wavefront of the count and emit kernels takes kSPW consecutive slots (one, or two where one would put more
 // than a workgroup on every compute unit).  The first kPre steps of 64 candidates
@@ -853,19 +1000,10 @@ hipError_t launch_topk_split_reset(void *workspace, int32_t n, int64_t d, hipStr
     return hipGetLastError();
 }
 
-hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t stream, const Marker &mk) {
-    Ws w;
-    layout(p.n, p.d, (char *)workspace, &w);
+namespace {
+// After the first collect pass: the second pass (after a warm start), count and emit.
+hipError_t launch_after_collect(const TopkArgs &p, const Ws &w, hipStream_t stream, const Marker &mk) {
     const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
-    if (upd && !diff) return hipErrorInvalidValue;
-    if (p.warm < 0 || p.warm > kWarmSlots) return hipErrorInvalidValue;
-    if (p.agg_start && (p.agg_shift < 0 || p.agg_shift > 11 || p.agg_nblk != ((p.d - 1) >> p.agg_shift) + 1 || p.k == 1))
-        return hipErrorInvalidValue;
-    if (p.k == 1) return launch_argmax(p, w, stream, mk);
-    launch_collect_any(p, w, p.warm > 0 ? kWarmPass : kColdPass, stream);
-    mk(K_TOPK_COLLECT);
-    hipError_t st = hipGetLastError();
-    if (st != hipSuccess) return st;
     if (p.warm > 0) {
         launch_collect_any(p, w, kSecondPass, stream);
         mk(K_TOPK_REFINE);
@@ -887,6 +1025,55 @@ hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t str
 #undef EF21_CAND
     mk(K_TOPK_EMIT);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_topk_split(const TopkArgs &p, void *workspace, hipStream_t stream, const Marker &mk) {
+    Ws w;
+    layout(p.n, p.d, (char *)workspace, &w);
+    const bool diff = p.b != nullptr, upd = p.g_i != nullptr;
+    if (upd && !diff) return hipErrorInvalidValue;
+    if (p.warm < 0 || p.warm > kWarmSlots) return hipErrorInvalidValue;
+    if (p.agg_start && (p.agg_shift < 0 || p.agg_shift > 11 || p.agg_nblk != ((p.d - 1) >> p.agg_shift) + 1 || p.k == 1))
+        return hipErrorInvalidValue;
+    if (p.k == 1) return launch_argmax(p, w, stream, mk);
+    launch_collect_any(p, w, p.warm > 0 ? kWarmPass : kColdPass, stream);
+    mk(K_TOPK_COLLECT);
+    hipError_t st = hipGetLastError();
+    if (st != hipSuccess) return st;
+    return launch_after_collect(p, w, stream, mk);
+}
+
+int64_t topk_split_slots(int32_t n, int64_t d) {
+    Ws w;
+    plan(n, d, &w);
+    return w.nslot;
+}
+
+hipError_t launch_topk_split_pair(const TopkArgs &plain, const TopkArgs &markov, void *ws_plain, void *ws_markov,
+                                  void *norm_parts, hipStream_t stream, const Marker &mk) {
+    if (plain.b || !markov.b || plain.a != markov.a || plain.n != markov.n || plain.d != markov.d ||
+        plain.k != markov.k || plain.g_i || markov.g_i || plain.agg_start || markov.agg_start || plain.k < 2 ||
+        plain.warm < 0 || plain.warm > kWarmSlots || markov.warm < 0 || markov.warm > kWarmSlots ||
+        (plain.warm > 0) != (markov.warm > 0) || !norm_parts)
+        return hipErrorInvalidValue;
+    Ws wp, wm;
+    layout(plain.n, plain.d, (char *)ws_plain, &wp);
+    layout(markov.n, markov.d, (char *)ws_markov, &wm);
+    const bool vec4 = (markov.d % 4 == 0) && ((uintptr_t)markov.a % 16 == 0) && ((uintptr_t)markov.b % 16 == 0);
+    const bool warm = markov.warm > 0;
+    const dim3 grid((unsigned)wm.G, (unsigned)markov.n), block(kBlk);
+    double2 *norms = (double2 *)norm_parts;
+    if (vec4 && warm) hipLaunchKernelGGL((split_collect_pair_kernel<4, true>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
+    else if (vec4) hipLaunchKernelGGL((split_collect_pair_kernel<4, false>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
+    else if (warm) hipLaunchKernelGGL((split_collect_pair_kernel<1, true>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
+    else hipLaunchKernelGGL((split_collect_pair_kernel<1, false>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
+    mk(K_TOPK_COLLECT);
+    hipError_t st = hipGetLastError();
+    if (st != hipSuccess) return st;
+    st = launch_after_collect(plain, wp, stream, mk);
+    if (st != hipSuccess) return st;
+    return launch_after_collect(markov, wm, stream, mk);
 }
 
 }  // namespace ef21
