@@ -53,7 +53,7 @@ static_assert(kCandThreads == kRowThreads && kBlk == kRowThreads, "the rescue ru
 constexpr uint32_t kShiftCold = 11, kShiftWarm = 10;
 constexpr uint32_t kWarmBelow = 1u << 20;
 constexpr int kTieCap = 1024;                // entries of T's bin that are ranked directly (one per thread)
-constexpr int kWarmSlots = 2;                // remembered thresholds per row (TopkArgs::warm = 1 .. kWarmSlots)
+constexpr int kWarmSlots = 1;                // remembered thresholds per row (TopkArgs::warm = 1 .. kWarmSlots)
 enum CollectMode { kColdPass = 0, kWarmPass = 1, kSecondPass = 2 };
 
 struct __attribute__((aligned(64))) RowInfo {     // one cache line per row
@@ -61,19 +61,25 @@ struct __attribute__((aligned(64))) RowInfo {     // one cache line per row
     uint32_t key_lo2, shift2;     // ... of the second pass, valid if use2
     uint32_t use2;                // the second pass redid this row: its histogram is hist_b
     uint32_t warm_used;           // the first pass started from a remembered threshold
-    uint32_t failed;              // the row went to the exact one-workgroup algorithm
+    uint32_t failed;              // kRowFailed: the row went to the exact one-workgroup algorithm in the count kernel;
+                                  // kRowCrowded: T's bin holds more than kTieCap candidates (see tie_min, tie_max)
     uint32_t bin_a, need_a;       // bin of T; entries still needed from that bin
     uint32_t ntie;                // length of the tie list
     uint32_t M;                   // candidates of the first pass (zero between calls)
     uint32_t q;                   // number of entries equal to the threshold key T that are kept
     uint32_t warm_T[kWarmSlots], warm_ok[kWarmSlots];   // thresholds T of earlier calls (the last call's: warm_T[0] if warm == 0)
+    uint32_t tie_min, tie_max;    // crowded bin: smallest and largest key in it.  Equal: T is that key (many equal
+                                  // magnitudes at the threshold, e.g. zeros), no ranking needed.  Different: the
+                                  // exact one-workgroup algorithm, in the emit kernel.
 };
+enum { kRowFine = 0, kRowFailed = 1, kRowCrowded = 2 };
 static_assert(sizeof(RowInfo) == 64, "one cache line");
 
 struct Ws {
     uint32_t *hist_a, *hist_b;            // [n][kHistBins] each, kept zero between calls
     RowInfo *info;                        // [n]
     uint32_t *slot_cnt, *slot_above;      // [n][nslot] candidates of a slot; those in bins above T's
+    uint32_t *slot_inbin;                 // [n][nslot] those in T's bin (written for crowded bins only)
     uint2 *tie;                           // [n][kTieCap] (position, key) of the candidates in T's bin
     uint2 *cand;                          // [n][nslot][L] (position, value bits) of the candidates
     int64_t L;                            // entries per wavefront piece = slot capacity
@@ -115,14 +121,14 @@ size_t layout(int32_t n, int64_t d, char *base, Ws *w) {
     char *hb = take(sizeof(uint32_t) * (size_t)n * kHistBins);
     char *inf = take(sizeof(RowInfo) * (size_t)n);
     const size_t slots = sizeof(uint32_t) * (size_t)n * tmp.nslot;
-    char *s0 = take(slots), *s1 = take(slots);
+    char *s0 = take(slots), *s1 = take(slots), *s2 = take(slots);
     char *tl = take(sizeof(uint2) * (size_t)n * kTieCap);
     char *cd = take(sizeof(uint2) * (size_t)n * tmp.nslot * tmp.L);
     if (w) {
         *w = tmp;
         w->hist_a = (uint32_t *)ha; w->hist_b = (uint32_t *)hb;
         w->info = (RowInfo *)inf;
-        w->slot_cnt = (uint32_t *)s0; w->slot_above = (uint32_t *)s1;
+        w->slot_cnt = (uint32_t *)s0; w->slot_above = (uint32_t *)s1; w->slot_inbin = (uint32_t *)s2;
         w->tie = (uint2 *)tl;
         w->cand = (uint2 *)cd;
     }
@@ -341,6 +347,8 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
             info->shift = f.shift;
             info->use2 = 0u;
             info->ntie = 0u;                 // the count kernel appends to the list
+            info->tie_min = 0xffffffffu;
+            info->tie_max = 0u;
             info->warm_used = warm ? 1u : 0u;
         }
     }
@@ -457,8 +465,10 @@ __global__ __launch_bounds__(kBlk) void split_collect_pair_kernel(TopkArgs pm, W
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         info_m->key_lo = fm.key_lo; info_m->shift = fm.shift; info_m->use2 = 0u; info_m->ntie = 0u;
+        info_m->tie_min = 0xffffffffu; info_m->tie_max = 0u;
         info_m->warm_used = warm_m ? 1u : 0u;
         info_p->key_lo = fp.key_lo; info_p->shift = fp.shift; info_p->use2 = 0u; info_p->ntie = 0u;
+        info_p->tie_min = 0xffffffffu; info_p->tie_max = 0u;
         info_p->warm_used = warm_pl ? 1u : 0u;
     }
     for (int i = threadIdx.x; i < kHistBins; i += kBlk) {
@@ -560,6 +570,25 @@ __global__ __launch_bounds__(kBlk) void split_collect_pair_kernel(TopkArgs pm, W
 }
 
 // ---------------------------------------------------------------- count
+// The exact one-workgroup algorithm on the original data for a row whose guess failed, and the message index of
+// the row if the caller asked for one.  All kCandThreads threads of the workgroup must call.
+template <bool DIFF, bool UPDATE>
+__device__ void rescue_row(RowShared &rs, const TopkArgs &p, int64_t row) {
+    row_topk<DIFF, UPDATE>(rs, p, row);
+    if (p.agg_start) {                  // from the pairs just written
+        __syncthreads();
+        const int32_t *out = p.out_idx + row * p.k;
+        int32_t *start = p.agg_start + row * (p.agg_nblk + 1);
+        for (int64_t at = threadIdx.x; at < p.k; at += kCandThreads) {
+            const int64_t b_cur = out[at] >> p.agg_shift;
+            const int64_t b_prev = at > 0 ? out[at - 1] >> p.agg_shift : -1;
+            for (int64_t b = b_prev + 1; b <= b_cur; ++b) start[b] = (int32_t)at;
+            if (at == p.k - 1)
+                for (int64_t b = b_cur + 1; b <= p.agg_nblk; ++b) start[b] = (int32_t)p.k;
+        }
+    }
+}
+
 // A wavefront of the count and emit kernels takes kSPW consecutive slots (one, or two where one would put more
 // than a workgroup on every compute unit).  The first kPre steps of 64 candidates
 // of each (clamped to the slot's capacity, a multiple of 1024) are loaded at the very start of the kernel, together
@@ -626,33 +655,20 @@ __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws
         }
     }
     __syncthreads();
-    bool failed = total < need;                                        // fewer than k candidates
+    bool failed = total < need, crowded = false;                       // fewer than k candidates
     uint32_t bin_a = 0, need_a = 0;
     if (!failed) {
         bin_a = lds_out[0];
         need_a = lds_out[1];
-        failed = bin_a == (uint32_t)kHistBins - 1u || lds_out[2] > (uint32_t)kTieCap;   // beyond the window; crowded
+        failed = bin_a == (uint32_t)kHistBins - 1u;                    // beyond the window
+        crowded = !failed && lds_out[2] > (uint32_t)kTieCap;           // too many to list: see RowInfo::tie_min
     }
     if (rescue) {
-        if (failed) {
-            row_topk<DIFF, UPDATE>(rs, p, row);
-            if (p.agg_start) {                  // the message index of this row, from the pairs just written
-                __syncthreads();
-                const int32_t *out = p.out_idx + row * p.k;
-                int32_t *start = p.agg_start + row * (p.agg_nblk + 1);
-                for (int64_t at = tid; at < p.k; at += kCandThreads) {
-                    const int64_t b_cur = out[at] >> p.agg_shift;
-                    const int64_t b_prev = at > 0 ? out[at - 1] >> p.agg_shift : -1;
-                    for (int64_t b = b_prev + 1; b <= b_cur; ++b) start[b] = (int32_t)at;
-                    if (at == p.k - 1)
-                        for (int64_t b = b_cur + 1; b <= p.agg_nblk; ++b) start[b] = (int32_t)p.k;
-                }
-            }
-        }
+        if (failed) rescue_row<DIFF, UPDATE>(rs, p, row);
         return;
     }
     if (blockIdx.x == 0 && tid == 0) {
-        info->failed = failed ? 1u : 0u;
+        info->failed = failed ? kRowFailed : (crowded ? kRowCrowded : kRowFine);
         info->bin_a = bin_a;
         info->need_a = need_a;
         info->M = 0u;                        // consumed by the second collect pass: zero for the next call
@@ -660,9 +676,10 @@ __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws
     }
     if (failed) return;
     uint2 *tie = w.tie + row * kTieCap;
+    uint32_t key_min = 0xffffffffu, key_max = 0u;
 #pragma unroll
     for (int s = 0; s < kSPW; ++s) {
-        uint32_t above = 0;
+        uint32_t above = 0, inbin = 0;
         for (uint32_t j0 = 0; j0 < cnt[s]; j0 += kWave * kPre) {
             if (j0 > 0) {
 #pragma unroll
@@ -678,11 +695,32 @@ __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws
                 const uint32_t bin = bin_of(key < key_lo ? key_lo : key, key_lo, shift);
                 above += popc64(__ballot(j < cnt[s] && bin > bin_a));
                 const bool in_bin = j < cnt[s] && bin == bin_a;
-                const uint32_t at = wave_append(in_bin, &info->ntie);
-                if (in_bin && at < (uint32_t)kTieCap) tie[at] = make_uint2(c[s][q].x, key);
+                if (!crowded) {
+                    const uint32_t at = wave_append(in_bin, &info->ntie);
+                    if (in_bin && at < (uint32_t)kTieCap) tie[at] = make_uint2(c[s][q].x, key);
+                } else {
+                    inbin += popc64(__ballot(in_bin));
+                    key_min = in_bin && key < key_min ? key : key_min;
+                    key_max = in_bin && key > key_max ? key : key_max;
+                }
             }
         }
-        if (lane == 0 && sl_first + s < w.nslot) w.slot_above[row * w.nslot + sl_first + s] = above;
+        if (lane == 0 && sl_first + s < w.nslot) {
+            w.slot_above[row * w.nslot + sl_first + s] = above;
+            if (crowded) w.slot_inbin[row * w.nslot + sl_first + s] = inbin;
+        }
+    }
+    if (crowded) {
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) {
+            const uint32_t lo_o = __shfl_xor(key_min, o, kWave), hi_o = __shfl_xor(key_max, o, kWave);
+            key_min = lo_o < key_min ? lo_o : key_min;
+            key_max = hi_o > key_max ? hi_o : key_max;
+        }
+        if (lane == 0 && key_min <= key_max) {
+            atomicMin(&info->tie_min, key_min);
+            atomicMax(&info->tie_max, key_max);
+        }
     }
 }
 
@@ -691,25 +729,38 @@ __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws
 // among equal keys): the entry that need_a - 1 others precede is the last one kept, its key is T, and q counts it
 // and the equal keys before it.  The output offset of a slot is the number of kept entries in all earlier slots:
 // their candidates above T's bin (slot_above, summed by the workgroup) plus the listed entries before the slot's
-// first position that are kept.
+// first position that are kept.  Grid (slot blocks + 1, n): the last workgroup of a row is a rescue, for a row
+// whose crowded bin (see RowInfo::tie_min) turned out to hold different keys.  A crowded bin of equal keys needs no
+// list: T is that key, and the ties before a slot are the earlier slots' entries of the bin (slot_inbin).
 template <bool DIFF, bool UPDATE, int kSPW>
 __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws w) {
     constexpr int kWgSlots = kCandWaves * kSPW;      // slots per workgroup
-    __shared__ uint32_t before_above[kCandWaves], own_above[kCandWaves];
+    __shared__ RowShared rs;                     // the rescue's
+    __shared__ uint32_t before_above[kCandWaves], own_above[kCandWaves], before_inbin[kCandWaves], own_inbin[kCandWaves];
     __shared__ uint32_t tie_key[kTieCap], tie_idx[kTieCap];
     __shared__ uint32_t sh_T, sh_q;
     static_assert(kTieCap <= kCandThreads, "one listed entry per thread");
     const int64_t row = blockIdx.y;
     const int tid = threadIdx.x, wave = tid / kWave, lane = lane_id();
     RowInfo *info = w.info + row;
-    const int64_t sl0 = (int64_t)blockIdx.x * kWgSlots, sl_first = sl0 + wave * kSPW;
+    const bool rescue = blockIdx.x == gridDim.x - 1;
+    const int64_t sl0 = rescue ? 0 : (int64_t)blockIdx.x * kWgSlots, sl_first = sl0 + wave * kSPW;
     // everything whose address is known now
     const RowInfo ri = *info;
+    const bool crowded = ri.failed == kRowCrowded;
+    if (rescue) {
+        if (crowded && ri.tie_min != ri.tie_max) rescue_row<DIFF, UPDATE>(rs, p, row);
+        return;
+    }
     const uint2 listed = w.tie[row * kTieCap + (tid < kTieCap ? tid : 0)];
     const uint32_t *slot_above = w.slot_above + row * w.nslot;
-    uint32_t part = 0;
-    for (int64_t t = tid; t < sl0; t += kCandThreads) part += slot_above[t];
-    uint32_t mine = 0, cnt[kSPW];
+    const uint32_t *slot_inbin = w.slot_inbin + row * w.nslot;
+    uint32_t part = 0, part_in = 0;
+    for (int64_t t = tid; t < sl0; t += kCandThreads) {
+        part += slot_above[t];
+        if (crowded) part_in += slot_inbin[t];
+    }
+    uint32_t mine = 0, mine_in = 0, cnt[kSPW];
     const uint2 *slot[kSPW];
     uint2 c[kSPW][kPre];
 #pragma unroll
@@ -717,6 +768,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
         const bool active = sl_first + s < w.nslot;
         const int64_t slc = active ? sl_first + s : 0;
         mine += active ? slot_above[slc] : 0u;
+        mine_in += active && crowded ? slot_inbin[slc] : 0u;
         cnt[s] = w.slot_cnt[row * w.nslot + slc];
         slot[s] = w.cand + (row * w.nslot + slc) * w.L;
 #pragma unroll
@@ -728,8 +780,8 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
         zero_global_hist(w.hist_a + row * kHistBins, kHistBins);
         if (ri.use2 != 0u) zero_global_hist(w.hist_b + row * kHistBins, kHistBins);
     }
-    if (ri.failed) return;                                                        // the whole workgroup
-    const uint32_t ntie = ri.ntie < (uint32_t)kTieCap ? ri.ntie : (uint32_t)kTieCap;
+    if (ri.failed == kRowFailed || (crowded && ri.tie_min != ri.tie_max)) return;     // the whole workgroup
+    const uint32_t ntie = crowded ? 0u : (ri.ntie < (uint32_t)kTieCap ? ri.ntie : (uint32_t)kTieCap);
     const uint32_t my_idx = listed.x, my_key = listed.y;
     if ((uint32_t)tid < ntie) {
         tie_idx[tid] = my_idx;
@@ -749,7 +801,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
         }
     }
     __syncthreads();
-    const uint32_t T = sh_T, q = sh_q;
+    const uint32_t T = crowded ? ri.tie_min : sh_T, q = crowded ? ri.need_a : sh_q;
     if (blockIdx.x == 0 && tid == 0) {
         info->q = q;
         const int mem = p.warm > 0 ? p.warm - 1 : 0;
@@ -758,6 +810,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
     }
 
     part = wave_sum_u32(part);
+    part_in = wave_sum_u32(part_in);
     // listed entries before this wavefront's first position: kept ones above T, and ties
     const uint32_t my_lo = (uint32_t)(sl_first * w.L);
     uint32_t list_gt = 0, list_eq = 0;
@@ -773,11 +826,16 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
     if (lane == 0) {
         before_above[wave] = part;
         own_above[wave] = mine;
+        before_inbin[wave] = part_in;
+        own_inbin[wave] = mine_in;
     }
     __syncthreads();
     if (sl_first >= w.nslot) return;
     uint32_t gt_run = list_gt, eq_run = list_eq;
-    for (int v = 0; v < kCandWaves; ++v) gt_run += before_above[v] + (v < wave ? own_above[v] : 0u);
+    for (int v = 0; v < kCandWaves; ++v) {
+        gt_run += before_above[v] + (v < wave ? own_above[v] : 0u);
+        eq_run += before_inbin[v] + (v < wave ? own_inbin[v] : 0u);      // zero unless the bin is crowded
+    }
     uint32_t out_run = gt_run + (eq_run < q ? eq_run : q);
     int32_t *out_idx = p.out_idx + row * p.k;
     float *out_val = p.out_val + row * p.k;
@@ -1010,7 +1068,7 @@ hipError_t launch_after_collect(const TopkArgs &p, const Ws &w, hipStream_t stre
     }
     const int spw = (int64_t)p.n * ((w.nslot + kCandWaves - 1) / kCandWaves) > 256 ? 2 : 1;
     const unsigned slot_blocks = (unsigned)((w.nslot + kCandWaves * spw - 1) / (kCandWaves * spw));
-    const dim3 grid(slot_blocks, (unsigned)p.n), cgrid(slot_blocks + 1, (unsigned)p.n), block(kCandThreads);
+    const dim3 cgrid(slot_blocks + 1, (unsigned)p.n), block(kCandThreads);     // + 1: a row's rescue workgroup
 #define EF21_CAND(KERNEL, GRID, DIFF, UPD)                                                               \
     do {                                                                                                 \
         if (spw == 2) hipLaunchKernelGGL((KERNEL<DIFF, UPD, 2>), GRID, block, 0, stream, p, w);          \
@@ -1020,8 +1078,9 @@ hipError_t launch_after_collect(const TopkArgs &p, const Ws &w, hipStream_t stre
     else if (diff) EF21_CAND(cand_count_kernel, cgrid, true, false);
     else EF21_CAND(cand_count_kernel, cgrid, false, false);
     mk(K_TOPK_COUNT);
-    if (upd) EF21_CAND(cand_emit_kernel, grid, true, true);
-    else EF21_CAND(cand_emit_kernel, grid, false, false);
+    if (upd) EF21_CAND(cand_emit_kernel, cgrid, true, true);
+    else if (diff) EF21_CAND(cand_emit_kernel, cgrid, true, false);
+    else EF21_CAND(cand_emit_kernel, cgrid, false, false);
 #undef EF21_CAND
     mk(K_TOPK_EMIT);
     return hipGetLastError();

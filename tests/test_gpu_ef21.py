@@ -199,6 +199,41 @@ def test_steps_when_the_remembered_threshold_is_wrong(gpu, oracle, k):
             budget.reset()
 
 
+@pytest.mark.parametrize("kind", ["equal", "distinct"])
+def test_step_with_a_crowded_threshold_bin(gpu, oracle, kind):
+    """Long rows whose threshold falls into a cluster of thousands of equal (or consecutive) magnitudes, inside the
+    step: two steps, so that the second starts from the first one's threshold."""
+    torch, binding = gpu
+    n, d, k, gamma = 3, 250_000, 3000, 0.25
+    print(f"crowded bin step, {kind}", flush=True)
+    rng = np.random.default_rng(9)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    g_i0 = np.zeros((n, d), dtype=np.float32)
+    st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), np.zeros(d))
+    budget = RoundingBudget(n, d, gamma)
+    with binding.EF21(n, d, k, gamma) as h:
+        h.set_state(to_gpu(torch, x0), to_gpu(torch, g_i0), None)
+        for t in range(2):
+            noise = 0.1 * rng.standard_normal((n, d))
+            for i in range(n):
+                pos = rng.choice(d, size=6000, replace=False)
+                sign = np.where(rng.random(6000) < 0.5, 1.0, -1.0)
+                if kind == "equal":
+                    noise[i, pos] = sign
+                else:
+                    bits = np.float32(1.0).view(np.uint32) + rng.permutation(6000).astype(np.uint32)
+                    noise[i, pos] = bits.view(np.float32).astype(np.float64) * sign
+            # differences that are exactly the planted values: the state is zero at the planted positions' scale
+            grads = (noise + (st.g_i if kind == "equal" and t == 0 else 0.0)).astype(np.float32) if t == 0 else \
+                    (st.g_i + noise).astype(np.float32)
+            oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma)
+            h.step(to_gpu(torch, grads))
+            torch.cuda.synchronize()
+            compare_state(torch, h, st, budget)
+            h.set_state(to_gpu(torch, st.x), None, to_gpu(torch, st.g))
+            budget.reset()
+
+
 def test_first_pass_compresses_zero_vector(gpu, oracle):
     """g_i^0 = grad: the first grad-first pass sees v = 0; k zero-valued pairs at positions 0..k-1
     are emitted and the state does not change."""

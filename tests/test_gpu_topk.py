@@ -240,3 +240,22 @@ def test_calls_on_two_streams_overlap_safely(gpu, oracle):
         assert np.array_equal(ib[4].cpu().numpy(), ref_b[0]) and same_bits(vb[4].cpu().numpy(), ref_b[1].astype(np.float32))
         assert same_bits(va.cpu().numpy(), np.take_along_axis(A.cpu().numpy(), ia.cpu().numpy().astype(np.int64), axis=1))
         assert same_bits(vb.cpu().numpy(), np.take_along_axis(B.cpu().numpy(), ib.cpu().numpy().astype(np.int64), axis=1))
+
+
+@pytest.mark.parametrize("kind", ["equal", "distinct"])
+def test_crowded_threshold_bin_on_long_rows(gpu, oracle, kind):
+    """Thousands of candidates share the histogram bin of the threshold: 6000 copies of one magnitude (no ranking
+    needed: ties go to the lower positions), or 6000 consecutive floats (too many to rank: the exact per-row
+    algorithm takes over).  k is chosen so that the threshold falls inside the cluster."""
+    rng = np.random.default_rng(8)
+    n, d = 3, 250_000
+    V = (0.1 * rng.standard_normal((n, d))).astype(np.float32)
+    for i in range(n):
+        pos = rng.choice(d, size=6000, replace=False)
+        if kind == "equal":
+            V[i, pos] = np.where(rng.random(6000) < 0.5, 1.0, -1.0).astype(np.float32)
+        else:
+            bits = np.float32(1.0).view(np.uint32) + rng.permutation(6000).astype(np.uint32)
+            V[i, pos] = bits.view(np.float32) * np.where(rng.random(6000) < 0.5, 1.0, -1.0).astype(np.float32)
+    for k in (3000, 5999, 6001):
+        check(gpu, oracle, V, k)
