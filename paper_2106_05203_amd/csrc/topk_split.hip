@@ -724,6 +724,75 @@ __global__ __launch_bounds__(kCandThreads) void cand_count_kernel(TopkArgs p, Ws
     }
 }
 
+// Ordered emission by one wavefront that walks candidates in position order, 64 at a time: the running output
+// offset, the ties seen so far, and (if asked for) the aggregation's message index, start[b] = output position of
+// the first kept entry at or beyond coordinate b << shift.  A wavefront's span [span_lo, span_end) is a whole number
+// of index blocks, so every block begins inside exactly one wavefront's span, and that wavefront writes its start:
+// when it keeps the first entry at or beyond the block's first coordinate, or at the end of its span for the
+// blocks that follow its last kept entry (all of them if it kept nothing).
+template <bool DIFF, bool UPDATE>
+struct Emitter {
+    const TopkArgs &p;
+    int64_t row;
+    uint32_t T, q;               // threshold key; entries equal to T that are kept (the first q in position order)
+    uint32_t out_run, eq_run;    // kept entries, and entries equal to T, before the next step
+    int32_t *out_idx;
+    float *out_val;
+    int32_t *agg_start;
+    int64_t last_b;              // index blocks up to here have their start
+    int lane;
+
+    __device__ Emitter(const TopkArgs &p_, int64_t row_, uint32_t T_, uint32_t q_, uint32_t gt_before,
+                       uint32_t eq_before, int64_t span_lo, int lane_)
+        : p(p_), row(row_), T(T_), q(q_), out_run(gt_before + (eq_before < q_ ? eq_before : q_)), eq_run(eq_before),
+          out_idx(p_.out_idx + row_ * p_.k), out_val(p_.out_val + row_ * p_.k),
+          agg_start(p_.agg_start ? p_.agg_start + row_ * (p_.agg_nblk + 1) : nullptr),
+          last_b((span_lo >> p_.agg_shift) - 1), lane(lane_) {}
+
+    // one step: `in` marks the lanes that hold a candidate (position rec.x, value bits rec.y); all lanes call
+    __device__ __forceinline__ void step(bool in, uint2 rec) {
+        const uint32_t key = rec.y & 0x7fffffffu;
+        const bool gt = in && key > T, eq = in && key == T;
+        const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
+        const uint32_t eq_below = eq_run + lanes_below(m_eq);
+        const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
+        const bool keep = gt || (eq && eq_below < q);
+        const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
+        if (keep) {
+            const float v = __uint_as_float(rec.y);
+            out_idx[pos] = (int32_t)rec.x;
+            out_val[pos] = v;
+            if constexpr (UPDATE) {                      // Algorithm 2, line 6
+                const int64_t at = row * p.d + (int64_t)rec.x;
+                p.g_i[at] = (DIFF ? p.b[at] : 0.f) + v;
+            }
+        }
+        if (agg_start) {
+            const uint64_t m_keep = __ballot(keep);
+            if (m_keep) {
+                const int64_t b_cur = (int64_t)(rec.x >> p.agg_shift);
+                const uint64_t lower = m_keep & ((1ull << lane) - 1ull);
+                const int prev_lane = lower ? 63 - __clzll((long long)lower) : 0;
+                const int64_t b_before = __shfl(b_cur, prev_lane, kWave);
+                const int64_t b_prev = lower ? b_before : last_b;
+                if (keep)
+                    for (int64_t b = b_prev + 1; b <= b_cur; ++b) agg_start[b] = (int32_t)pos;
+                last_b = __shfl(b_cur, 63 - __clzll((long long)m_keep), kWave);
+            }
+        }
+        const uint32_t eq_next = eq_run + popc64(m_eq);
+        out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
+        eq_run = eq_next;
+    }
+
+    // after the last step of a span that ends at span_end (clamped to the row's end by the caller)
+    __device__ __forceinline__ void finish(int64_t span_end) {
+        if (!agg_start) return;
+        const int64_t b_last = ((span_end - 1) >> p.agg_shift) + (span_end == p.d ? 1 : 0);   // the row's end: start[nblk]
+        for (int64_t b = last_b + 1 + lane; b <= b_last; b += kWave) agg_start[b] = (int32_t)out_run;
+    }
+};
+
 // ---------------------------------------------------------------- emit
 // Ordered emission.  Prologue of every workgroup: the tie list ranked (larger key first, lower position first
 // among equal keys): the entry that need_a - 1 others precede is the last one kept, its key is T, and q counts it
@@ -836,15 +905,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
         gt_run += before_above[v] + (v < wave ? own_above[v] : 0u);
         eq_run += before_inbin[v] + (v < wave ? own_inbin[v] : 0u);      // zero unless the bin is crowded
     }
-    uint32_t out_run = gt_run + (eq_run < q ? eq_run : q);
-    int32_t *out_idx = p.out_idx + row * p.k;
-    float *out_val = p.out_val + row * p.k;
-    // The aggregation's message index (see aggregate_index_shift): start[b] = output position of the first kept
-    // entry at or beyond coordinate b << shift.  A slot is a whole number of blocks, so every block begins inside
-    // exactly one wavefront's span, and that wavefront writes its start: when it keeps the first entry at or beyond
-    // the block's first coordinate, or at the end of its span for the blocks that follow its last kept entry.
-    int32_t *agg_start = p.agg_start ? p.agg_start + row * (p.agg_nblk + 1) : nullptr;
-    int64_t last_b = ((sl_first * w.L) >> p.agg_shift) - 1;      // blocks up to here have their start
+    Emitter<DIFF, UPDATE> em(p, row, T, q, gt_run, eq_run, sl_first * w.L, lane);
 #pragma unroll
     for (int s = 0; s < kSPW; ++s) {             // consecutive slots: the running offsets carry over
         for (uint32_t j0 = 0; j0 < cnt[s]; j0 += kWave * kPre) {
@@ -856,51 +917,11 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kPre; ++u) {
-                const uint32_t j = j0 + u * kWave + lane;
-                const bool in = j < cnt[s];
-                const uint2 cu = c[s][u];
-                const uint32_t key = cu.y & 0x7fffffffu;
-                const bool gt = in && key > T, eq = in && key == T;
-                const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
-                const uint32_t eq_below = eq_run + lanes_below(m_eq);
-                const uint32_t ties_before = (eq_below < q ? eq_below : q) - (eq_run < q ? eq_run : q);
-                const bool keep = gt || (eq && eq_below < q);
-                const uint32_t pos = out_run + lanes_below(m_gt) + ties_before;
-                if (keep) {
-                    const float v = __uint_as_float(cu.y);
-                    out_idx[pos] = (int32_t)cu.x;
-                    out_val[pos] = v;
-                    if constexpr (UPDATE) {                      // Algorithm 2, line 6
-                        const int64_t at = row * p.d + (int64_t)cu.x;
-                        p.g_i[at] = (DIFF ? p.b[at] : 0.f) + v;
-                    }
-                }
-                if (agg_start) {
-                    const uint64_t m_keep = __ballot(keep);
-                    if (m_keep) {
-                        const int64_t b_cur = (int64_t)(cu.x >> p.agg_shift);
-                        const uint64_t lower = m_keep & ((1ull << lane) - 1ull);
-                        const int prev_lane = lower ? 63 - __clzll((long long)lower) : 0;
-                        const int64_t b_before = __shfl(b_cur, prev_lane, kWave);
-                        const int64_t b_prev = lower ? b_before : last_b;
-                        if (keep)
-                            for (int64_t b = b_prev + 1; b <= b_cur; ++b) agg_start[b] = (int32_t)pos;
-                        last_b = __shfl(b_cur, 63 - __clzll((long long)m_keep), kWave);
-                    }
-                }
-                const uint32_t eq_next = eq_run + popc64(m_eq);
-                out_run += popc64(m_gt) + ((eq_next < q ? eq_next : q) - (eq_run < q ? eq_run : q));
-                eq_run = eq_next;
-            }
+            for (int u = 0; u < kPre; ++u) em.step(j0 + u * kWave + lane < cnt[s], c[s][u]);
         }
     }
-    if (agg_start) {      // blocks of this span after its last kept entry (all of them if it kept nothing)
-        int64_t span_end = (sl_first + kSPW) * w.L;
-        span_end = span_end < p.d ? span_end : p.d;
-        const int64_t b_last = ((span_end - 1) >> p.agg_shift) + (span_end == p.d ? 1 : 0);   // the row's end: start[nblk]
-        for (int64_t b = last_b + 1 + lane; b <= b_last; b += kWave) agg_start[b] = (int32_t)out_run;
-    }
+    const int64_t span_end = (sl_first + kSPW) * w.L;
+    em.finish(span_end < p.d ? span_end : p.d);
 }
 
 __global__ __launch_bounds__(kCandThreads) void zero_words_kernel(uint32_t *p, size_t words) {
