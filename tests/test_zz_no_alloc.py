@@ -83,3 +83,46 @@ def test_limit_is_an_error_not_an_allocation(gpu):
     assert rc == binding.EF21_EINVAL
     assert b"static scratch" in lib.ef21_last_error()
     assert lib.ef21_topk_static(None, 1, 4, 1, C.c_void_p(idx.data_ptr()), C.c_void_p(val.data_ptr()), None) == binding.EF21_EINVAL
+
+
+def test_static_entry_point_under_graph_capture(gpu):
+    """One of the callers it is for: a HIP graph.  The call is captured once (after an eager call of the same shape,
+    which does the per-device set-up) and replayed on new contents of the same input buffer, with eager work and
+    synchronisations between the replays; every replay must equal an eager ef21_topk of the same contents."""
+    torch, binding, lib = gpu
+    n, d, k = 3, 150_000, 1200
+    rows = torch.zeros((n, d), dtype=torch.float32, device="cuda")
+    idx = torch.full((n, k), -7, dtype=torch.int32, device="cuda")
+    val = torch.zeros((n, k), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+
+    def static_call(stream):
+        rc = lib.ef21_topk_static(C.c_void_p(rows.data_ptr()), n, d, k, C.c_void_p(idx.data_ptr()),
+                                  C.c_void_p(val.data_ptr()), C.c_void_p(stream.cuda_stream))
+        assert rc == binding.EF21_OK, lib.ef21_last_error().decode()
+
+    rows.copy_(torch.from_numpy(workloads.topk_rows(n, d, seed=20)))
+    torch.cuda.synchronize()
+    static_call(side)                                     # eager: set-up happens here, outside the capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        static_call(side)
+    for seed in (21, 22, 23):
+        V = workloads.topk_rows(n, d, seed=seed)
+        if seed == 23:
+            V = np.round(V * 2) / 2                       # many equal magnitudes
+        rows.copy_(torch.from_numpy(np.ascontiguousarray(V, dtype=np.float32)))
+        idx.fill_(-7)
+        val.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_idx, got_val = idx.cpu().numpy().copy(), val.cpu().numpy().copy()
+        ref_idx = torch.empty_like(idx)
+        ref_val = torch.empty_like(val)
+        binding.ef21_topk(rows, k, ref_idx, ref_val)      # eager work between the replays
+        torch.cuda.synchronize()
+        print(f"graph replay of ef21_topk_static, seed {seed}", flush=True)
+        assert np.array_equal(got_idx, ref_idx.cpu().numpy())
+        assert same_bits(got_val, ref_val.cpu().numpy())
