@@ -114,6 +114,52 @@ def test_single_steps_on_random_shapes(gpu, oracle):
             compare_state(torch, h, st, budget)
 
 
+def test_step_sequences_on_random_shapes_and_distributions(gpu, oracle):
+    """Sixteen seeded sequences of five steps each on long rows (the candidate path, which remembers the threshold
+    from step to step): gradients of different kinds (Gaussian, heavy-tailed, many equal magnitudes, mostly zeros,
+    two halves of very different scale, magnitudes in ascending order) whose scale jumps up or down between steps,
+    so that the remembered threshold is now right, now too low, now too high.  Messages and g_i bit for bit every
+    step, g and x within the rounding budget (resynchronised after each step)."""
+    torch, binding = gpu
+    rng = np.random.default_rng(2106)
+    kinds = ["normal", "student", "ties", "sparse", "halves", "ascending"]
+    for case in range(16):
+        d = int(rng.integers(*[(16_384, 18_000), (60_000, 70_000), (100_000, 400_000), (900_000, 1_300_000)][case % 4]))
+        n = int(rng.integers(1, max(2, min(9, 2_500_000 // d + 1))))
+        k = int(max(2, min(d, d * 10 ** rng.uniform(-3.5, -1.0))))
+        kind = kinds[case % len(kinds)]
+        gamma = 0.25
+        print(f"sequence {case}: n={n} d={d} k={k} {kind}", flush=True)
+        base = rng.standard_normal((n, d))
+        if kind == "student":
+            base = base / np.sqrt(rng.chisquare(3, (n, d)) / 3)
+        elif kind == "ties":
+            base = np.round(base * 2) / 2
+        elif kind == "sparse":
+            base[rng.random((n, d)) < 0.995] = 0.0
+        elif kind == "halves":
+            base[:, : d // 2] *= 1e-6
+        elif kind == "ascending":
+            base = np.sort(np.abs(base), axis=1)
+        base = base.astype(np.float32)
+        x0 = rng.standard_normal(d).astype(np.float32)
+        st = oracle.EF21State(x0.astype(np.float64), np.zeros((n, d)), np.zeros(d))
+        budget = RoundingBudget(n, d, gamma)
+        scale = 1.0
+        with binding.EF21(n, d, k, gamma) as h:
+            h.set_state(to_gpu(torch, x0), to_gpu(torch, np.zeros((n, d))), to_gpu(torch, np.zeros(d)))
+            for t in range(5):
+                scale *= [1.0, 1.05, 3.0, 0.25, 1.0][int(rng.integers(5))]
+                noise = 0.3 * rng.standard_normal((n, d)) if kind not in ("ties", "sparse") else 0.0
+                grads = ((base + noise) * scale).astype(np.float32)
+                oracle_step(oracle, st, budget, grads.astype(np.float64), k, gamma)
+                h.step(to_gpu(torch, grads))
+                torch.cuda.synchronize()
+                compare_state(torch, h, st, budget)
+                h.set_state(to_gpu(torch, st.x), None, to_gpu(torch, st.g))
+                budget.reset()
+
+
 @pytest.mark.parametrize("n,d,k", [(16, 20_000, 600), (17, 20_000, 600), (33, 70_001, 1500), (67, 16_500, 300)])
 def test_step_with_many_workers_and_clustered_messages(gpu, oracle, n, d, k):
     """Sixteen workers and more take the aggregation that splits the workers over four wavefronts; the large
