@@ -33,5 +33,26 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_client.c")
+C_CLIENT = os.path.join(os.path.dirname(HERE), "tests", "c_client")
+
+
+def build_c_client(verbose: bool = False) -> str:
+    """Compile tests/c_client.c, a client of the library written in plain C, with gcc (the host compiler: the
+    client holds no device code) against include/ef21.h, libef21.so and the HIP runtime.  The library is found
+    at run time relative to the executable."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(os.path.dirname(HERE), "include"), "-I", os.path.join(rocm, "include"),
+           C_CLIENT_SRC, "-o", C_CLIENT, "-L", HERE, "-lef21", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../paper_2106_05203_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"),
+           "-Wl,-rpath-link," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_client(verbose=True))

@@ -33,6 +33,16 @@ def test_header_symbols_exported(lib):
         assert hasattr(raw, name), f"{name} is declared in include/ef21.h but not exported"
 
 
+@pytest.mark.parametrize("compiler,std", [("gcc", "-std=c99"), ("g++", "-std=c++11")])
+def test_header_is_plain_c_and_cxx(compiler, std, tmp_path):
+    """include/ef21.h alone (only <stdint.h> beneath it) compiles as C99 and as C++11 without warnings."""
+    import subprocess
+    src = tmp_path / ("use_header.c" if compiler == "gcc" else "use_header.cpp")
+    src.write_text('#include "ef21.h"\nint main(void) { return ef21_last_error() == 0 && EF21_OK; }\n')
+    subprocess.check_call([compiler, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
+
+
 def test_argument_errors_need_no_gpu(lib):
     buf = (C.c_float * 8)()
     ibuf = (C.c_int32 * 8)()
