@@ -7,7 +7,7 @@
 //   collect   A key `key_lo` that (almost surely) at least k entries of the row reach is fixed first: from the
 //             threshold key T of the previous call on the same quantity, lowered by a few per cent (warm start:
 //             inside ef21_step consecutive iterations select nearly the same T), else from a fixed sample of the
-//             row (32 evenly spaced pieces of 256 entries) that every workgroup of the row looks at.  Then each
+//             row (64 evenly spaced pieces of 64 entries) that every workgroup of the row looks at.  Then each
 //             wavefront streams a contiguous piece of the row and appends the entries with key >= key_lo
 //             ("candidates", one or two per cent of the row) in position order to its own slot of the workspace,
 //             counting them into the workgroup's LDS histogram of (key - key_lo) >> shift on the way (4096 bins;
@@ -35,13 +35,13 @@ namespace {
 
 constexpr int kBlk = kRowThreads;            // collect / rescue workgroups
 constexpr int kBlkWaves = kBlk / kWave;
-constexpr int kSample = 8192;                // sampled entries per row
+constexpr int kSample = 4096;                // sampled entries per row
 constexpr int kSamplePer = kSample / kBlk;
-constexpr int kPieceLen = 256, kPieces = kSample / kPieceLen;
+constexpr int kPieceLen = 64, kPieces = kSample / kPieceLen;   // a wavefront's load is one piece
 constexpr int kMaxSlots = 4096;              // slots (wavefront pieces) per row
 constexpr int kCandThreads = 1024;           // count / emit workgroups: one wavefront per slot
 constexpr int kCandWaves = kCandThreads / kWave;
-constexpr int kBins1 = 1 << kBits1, kBins2 = 1 << kBits2;
+constexpr int kBins1 = 1 << kBits1;
 constexpr int kHistBins = 4096;              // bins of the candidates' histogram
 static_assert(kHistBins == kBins1, "the candidates' histogram lives in RowShared::hist");
 static_assert(kCandThreads == kRowThreads && kBlk == kRowThreads, "the rescue runs the one-workgroup algorithm");
@@ -180,7 +180,9 @@ __device__ __forceinline__ uint32_t sample_rank(int64_t k, int64_t ns, int64_t d
 }
 
 // Lower bound of the candidate keys from the sample, identical in every workgroup of a row (it depends on
-// the data only).  22 significant bits; 0 means "every entry is a candidate".
+// the data only): the lower edge of the bin, in a histogram of the keys' 12 leading bits (1/16 octave), that holds
+// the sample's r-th largest key.  A finer bound would save a few per cent of the candidates, which cost little,
+// for a second histogram pass, which costs a microsecond in every workgroup.  0 means "every entry is a candidate".
 template <bool DIFF>
 __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b, int64_t d, int64_t k) {
     const int64_t ns = d < kSample ? d : kSample;
@@ -204,17 +206,7 @@ __device__ uint32_t estimate_key_lo(RowShared &s, const float *a, const float *b
         if (skey[j] != 0xffffffffu) atomicAdd(&s.hist[skey[j] >> (kBits2 + kBits3)], 1u);
     __syncthreads();
     select_bin(s, kBins1, r);
-    const uint32_t d1 = s.bin, r1 = s.need;
-    __syncthreads();
-    for (int i = threadIdx.x; i < kBins2; i += kBlk) s.hist[i] = 0u;
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < kSamplePer; ++j)
-        if (skey[j] != 0xffffffffu && (skey[j] >> (kBits2 + kBits3)) == d1)
-            atomicAdd(&s.hist[(skey[j] >> kBits3) & (kBins2 - 1)], 1u);
-    __syncthreads();
-    select_bin(s, kBins2, r1);
-    const uint32_t key_lo = ((d1 << kBits2) | s.bin) << kBits3;
+    const uint32_t key_lo = s.bin << (kBits2 + kBits3);
     __syncthreads();
     return key_lo;
 }

@@ -14,6 +14,13 @@ def close_per_coordinate(got, ref, rel=1e-5):
     return not bad.any(), (float(err.max()) if err.size else 0.0, int(bad.sum()))
 
 
+def sampled_positions(d):
+    """The entries of a long row (d > 4096) that the library's long-row Top-k samples to guess its candidate
+    threshold: 64 evenly spaced pieces of 64 entries (the constants of csrc/topk_split.hip, restated here so that
+    tests can build rows on which the sample misleads)."""
+    return np.concatenate([(p * (d - 64)) // 63 + np.arange(64) for p in range(64)])
+
+
 def same_bits(a, b):
     """Bitwise equality of two float32 arrays (so -0.0 != +0.0 and equal NaNs compare equal)."""
     a = np.ascontiguousarray(a, dtype=np.float32)

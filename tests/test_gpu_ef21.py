@@ -7,7 +7,7 @@ in fp32 in worker order, the oracle in fp64); f(x^t) within 1e-4 relative over a
 import numpy as np
 import pytest
 
-from helpers import RoundingBudget, close_per_coordinate, same_bits
+from helpers import RoundingBudget, close_per_coordinate, same_bits, sampled_positions
 from paper_2106_05203_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -189,7 +189,7 @@ def test_step_with_many_workers_and_clustered_messages(gpu, oracle, n, d, k):
 
 @pytest.mark.parametrize("k", [5000, 60000])
 def test_step_when_the_sample_misleads(gpu, oracle, k):
-    """Long rows whose large differences sit exactly on the 32 sampled pieces: the candidate threshold
+    """Long rows whose large differences sit exactly on the sampled pieces: the candidate threshold
     guessed from the sample keeps fewer than k candidates and the exact per-row algorithm takes over,
     inside the step (difference, state update) for the small-k and the large-k candidate stage."""
     torch, binding = gpu
@@ -200,7 +200,7 @@ def test_step_when_the_sample_misleads(gpu, oracle, k):
     x0 = rng.standard_normal(d).astype(np.float32)
     g0 = g_i0.astype(np.float64).mean(axis=0).astype(np.float32)
     grads = (g_i0 + 1e-3 * rng.standard_normal((n, d))).astype(np.float32)
-    pos = np.concatenate([(p * (d - 256)) // 31 + np.arange(256) for p in range(32)])
+    pos = sampled_positions(d)
     grads[:, pos] += (1.0 + rng.random((n, pos.size))).astype(np.float32)
     st = oracle.EF21State(x0.astype(np.float64), g_i0.astype(np.float64), g0.astype(np.float64))
     budget = RoundingBudget(n, d, gamma)

@@ -3,7 +3,7 @@ positions bit-exact, values bit-exact (they are copies of the inputs)."""
 import numpy as np
 import pytest
 
-from helpers import same_bits
+from helpers import same_bits, sampled_positions
 from paper_2106_05203_amd import workloads
 
 pytestmark = pytest.mark.gpu
@@ -127,14 +127,14 @@ def test_long_rows_degenerate(gpu, oracle):
 
 @pytest.mark.parametrize("k", [10000, 60000])
 def test_long_rows_misleading_sample(gpu, oracle, k):
-    """The long-row path guesses a candidate threshold from 32 evenly spaced pieces of 256 entries.
+    """The long-row path guesses a candidate threshold from 64 evenly spaced pieces of 64 entries.
     Here the large values sit exactly on those pieces and nowhere else, so the guess keeps far fewer
     than k candidates and the exact per-row algorithm has to take over (both the small-k and the
     large-k variant of the candidate stage)."""
     d = 300_000
     rng = np.random.default_rng(k)
     V = (rng.standard_normal((3, d)) * 1e-3).astype(np.float32)
-    pos = np.concatenate([(p * (d - 256)) // 31 + np.arange(256) for p in range(32)])
+    pos = sampled_positions(d)
     V[:, pos] = (1.0 + rng.random((3, pos.size))).astype(np.float32)
     V[2] = np.abs(V[2])
     check(gpu, oracle, V, k)
@@ -148,7 +148,7 @@ def test_long_rows_sample_far_too_low(gpu, oracle, k):
     d = 300_000
     rng = np.random.default_rng(k + 1)
     V = (1000.0 * (1.0 + rng.random((3, d)))).astype(np.float32)
-    pos = np.concatenate([(p * (d - 256)) // 31 + np.arange(256) for p in range(32)])
+    pos = sampled_positions(d)
     V[:, pos] = (rng.standard_normal((3, pos.size)) * 1e-3).astype(np.float32)
     V[1] = -V[1]
     check(gpu, oracle, V, k)
