@@ -90,8 +90,9 @@ struct Ws {
 size_t align256(size_t b) { return (b + 255) / 256 * 256; }
 
 void plan(int32_t n, int64_t d, Ws *w) {
-    // one 1024-thread workgroup per CU, two (in two rounds: the kernel's registers let one be resident) for inputs
-    // of 2^26 entries and more
+    // one 1024-thread workgroup per CU; two for inputs of 2^26 entries and more (the collect kernels need 44
+    // registers per lane and 36 KB of LDS, so two are resident).  Measured: short inputs lose with a second
+    // workgroup per CU (each repeats the sampling prologue), long ones with fewer or more than two.
     int64_t max_g = ((int64_t)n * d >= ((int64_t)1 << 26) ? 512 : 256) / n;
     if (max_g < 1) max_g = 1;
     if (max_g > kMaxSlots / kBlkWaves) max_g = kMaxSlots / kBlkWaves;
