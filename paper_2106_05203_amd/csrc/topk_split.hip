@@ -292,12 +292,12 @@ __device__ __forceinline__ void drain_ring(const StageRing &ring, uint32_t flush
         ring_to_slot(ring, flushed, cnt - flushed < 64 ? cnt - flushed : 64, lane, slot, f);
 }
 
-// A wavefront walks its piece in steps of 64*VEC entries (VEC = 4 needs 16-byte aligned rows), four
-// steps per group.  Whole groups are loaded without any bounds check so that all loads of a group
+// A wavefront walks its piece in steps of 64*VEC entries (VEC = 4 needs 16-byte aligned rows), U steps per
+// group (VEC = 1: four).  Whole groups are loaded without any bounds check so that all loads of a group
 // are in flight together; only the last piece of a row has a checked tail.
 // MODE: kColdPass key_lo from the sample; kWarmPass from the threshold remembered in slot p.warm if there is
 // one, else from the sample; kSecondPass: only rows whose warm start failed, from the sample, into hist_b.
-template <int VEC, bool DIFF, int MODE>
+template <int VEC, bool DIFF, int MODE, int U>
 __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
     __shared__ RowShared s;
     __shared__ StageRing rings[kBlkWaves];
@@ -358,25 +358,48 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
         const int64_t hi = lo + w.L < d ? lo + w.L : d;
         uint2 *slot = w.cand + (row * w.nslot + slot_no) * w.L;
         uint32_t cnt = 0, flushed = 0;
-        constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
+        constexpr int kStep = kWave * VEC, kUnroll = VEC == 4 ? U : 4, kGroup = kStep * kUnroll;
         int64_t base = lo;
-        for (; base + kGroup <= hi; base += kGroup) {
-            float v[kUnroll][VEC];
-            if constexpr (VEC == 4) {
-                float4 va[kUnroll], vb[kUnroll];
+        if constexpr (VEC == 4) {
+            // Groups of U steps, two register buffers: the next group's loads are issued before this group is
+            // filtered, so that a wavefront has loads in flight while it computes.  After the last group the
+            // "next" loads all read the piece's first 16 bytes (one cached line) instead of sitting behind a
+            // branch.  What is in flight per compute unit is 1024 lanes x workgroups per unit x arrays x 2 U x 16
+            // bytes; measured best at 64 to 128 KB (see launch_collect).
+            float4 va[kUnroll], vb[kUnroll];
+            if (base + kGroup <= hi) {
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     va[u] = stream_load4(a + base + u * kStep + lane * 4);
                     if constexpr (DIFF) vb[u] = stream_load4(b + base + u * kStep + lane * 4);
                 }
+            }
+            for (; base + kGroup <= hi; base += kGroup) {
+                const bool more = base + 2 * kGroup <= hi;
+                float4 na[kUnroll], nb[kUnroll];
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
-                    v[u][0] = va[u].x; v[u][1] = va[u].y; v[u][2] = va[u].z; v[u][3] = va[u].w;
-                    if constexpr (DIFF) {
-                        v[u][0] -= vb[u].x; v[u][1] -= vb[u].y; v[u][2] -= vb[u].z; v[u][3] -= vb[u].w;
-                    }
+                    const int64_t at = more ? base + kGroup + u * kStep + lane * 4 : lo;
+                    na[u] = stream_load4(a + at);
+                    if constexpr (DIFF) nb[u] = stream_load4(b + at);
                 }
-            } else {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    float v[VEC] = {va[u].x, va[u].y, va[u].z, va[u].w};
+                    if constexpr (DIFF) {
+                        v[0] -= vb[u].x; v[1] -= vb[u].y; v[2] -= vb[u].z; v[3] -= vb[u].w;
+                    }
+                    append_candidates<VEC, true>(v, base + u * kStep + lane * VEC, hi, f, ring, lane, slot, cnt, flushed);
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    va[u] = na[u];
+                    if constexpr (DIFF) vb[u] = nb[u];
+                }
+            }
+        } else {
+            for (; base + kGroup <= hi; base += kGroup) {
+                float v[kUnroll][VEC];
                 float vb[kUnroll];
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
@@ -387,10 +410,10 @@ __global__ __launch_bounds__(kBlk) void split_collect_kernel(TopkArgs p, Ws w) {
 #pragma unroll
                     for (int u = 0; u < kUnroll; ++u) v[u][0] -= vb[u];
                 }
-            }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                append_candidates<VEC, true>(v[u], base + u * kStep + lane * VEC, hi, f, ring, lane, slot, cnt, flushed);
+                for (int u = 0; u < kUnroll; ++u)
+                    append_candidates<VEC, true>(v[u], base + u * kStep + lane * VEC, hi, f, ring, lane, slot, cnt, flushed);
+            }
         }
         for (; base < hi; base += kStep) {           // checked tail, entry by entry
             const int64_t e0 = base + lane * VEC;
@@ -426,7 +449,7 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
     return v;
 }
 
-template <int VEC, bool WARM>
+template <int VEC, bool WARM, int U>
 __global__ __launch_bounds__(kBlk) void split_collect_pair_kernel(TopkArgs pm, Ws wm, int warm_p, Ws wp,
                                                                   double2 *__restrict__ norms) {
     __shared__ RowShared s;                      // its histogram serves the sampling, then the difference
@@ -484,29 +507,10 @@ __global__ __launch_bounds__(kBlk) void split_collect_pair_kernel(TopkArgs pm, W
         uint2 *slot_p = wp.cand + (row * wp.nslot + slot_no) * wp.L;
         uint32_t cnt_m = 0, flushed_m = 0, cnt_p = 0, flushed_p = 0;
         double sq_s = 0.0, sq_v = 0.0;
-        constexpr int kStep = kWave * VEC, kUnroll = 4, kGroup = kStep * kUnroll;
+        constexpr int kStep = kWave * VEC, kUnroll = VEC == 4 ? U : 4, kGroup = kStep * kUnroll;
         int64_t base = lo;
-        for (; base + kGroup <= hi; base += kGroup) {
-            float vs[kUnroll][VEC], vd[kUnroll][VEC];
-            if constexpr (VEC == 4) {
-                float4 va[kUnroll], vb[kUnroll];
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    va[u] = stream_load4(a + base + u * kStep + lane * 4);
-                    vb[u] = stream_load4(b + base + u * kStep + lane * 4);
-                }
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    vs[u][0] = va[u].x; vs[u][1] = va[u].y; vs[u][2] = va[u].z; vs[u][3] = va[u].w;
-                    vd[u][0] = vb[u].x; vd[u][1] = vb[u].y; vd[u][2] = vb[u].z; vd[u][3] = vb[u].w;
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    vs[u][0] = stream_load(a + base + u * kStep + lane);
-                    vd[u][0] = stream_load(b + base + u * kStep + lane);
-                }
-            }
+        // one group: the squared norms of line 7, the difference of line 6, both filters
+        auto filter_group = [&](float (&vs)[kUnroll][VEC], float (&vd)[kUnroll][VEC]) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
 #pragma unroll
@@ -519,6 +523,49 @@ __global__ __launch_bounds__(kBlk) void split_collect_pair_kernel(TopkArgs pm, W
                 const int64_t e0 = base + u * kStep + lane * VEC;
                 append_candidates<VEC, true>(vs[u], e0, hi, fp, ring_p, lane, slot_p, cnt_p, flushed_p);
                 append_candidates<VEC, true>(vd[u], e0, hi, fm, ring_m, lane, slot_m, cnt_m, flushed_m);
+            }
+        };
+        if constexpr (VEC == 4) {
+            // two register buffers, as in split_collect_kernel: the next group's loads before this group's work
+            float4 va[kUnroll], vb[kUnroll];
+            if (base + kGroup <= hi) {
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    va[u] = stream_load4(a + base + u * kStep + lane * 4);
+                    vb[u] = stream_load4(b + base + u * kStep + lane * 4);
+                }
+            }
+            for (; base + kGroup <= hi; base += kGroup) {
+                const bool more = base + 2 * kGroup <= hi;
+                float4 na[kUnroll], nb[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int64_t at = more ? base + kGroup + u * kStep + lane * 4 : lo;
+                    na[u] = stream_load4(a + at);
+                    nb[u] = stream_load4(b + at);
+                }
+                float vs[kUnroll][VEC], vd[kUnroll][VEC];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    vs[u][0] = va[u].x; vs[u][1] = va[u].y; vs[u][2] = va[u].z; vs[u][3] = va[u].w;
+                    vd[u][0] = vb[u].x; vd[u][1] = vb[u].y; vd[u][2] = vb[u].z; vd[u][3] = vb[u].w;
+                }
+                filter_group(vs, vd);
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    va[u] = na[u];
+                    vb[u] = nb[u];
+                }
+            }
+        } else {
+            for (; base + kGroup <= hi; base += kGroup) {
+                float vs[kUnroll][VEC], vd[kUnroll][VEC];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    vs[u][0] = stream_load(a + base + u * kStep + lane);
+                    vd[u][0] = stream_load(b + base + u * kStep + lane);
+                }
+                filter_group(vs, vd);
             }
         }
         for (; base < hi; base += kStep) {           // checked tail, entry by entry
@@ -922,15 +969,30 @@ __global__ __launch_bounds__(kCandThreads) void zero_words_kernel(uint32_t *p, s
     for (size_t i = (size_t)blockIdx.x * kCandThreads + threadIdx.x; i < words; i += stride) p[i] = 0u;
 }
 
+template <int VEC, bool DIFF, int U>
+void launch_collect_u(const TopkArgs &p, const Ws &w, int mode, const dim3 &grid, hipStream_t stream) {
+    const dim3 block(kBlk);
+    if (mode == kColdPass) hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kColdPass, U>), grid, block, 0, stream, p, w);
+    else if (mode == kWarmPass) hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kWarmPass, U>), grid, block, 0, stream, p, w);
+    else hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kSecondPass, U>), grid, block, 0, stream, p, w);
+}
+
 template <int VEC, bool DIFF>
 void launch_collect(const TopkArgs &p, const Ws &w, int mode, hipStream_t stream) {
     // the second pass has work only after a failed guess: about 64 workgroups, which loop over the slots
     int64_t g = w.G;
     if (mode == kSecondPass) g = std::max<int64_t>(1, std::min<int64_t>(w.G, 64 / p.n));
-    const dim3 grid((unsigned)g, (unsigned)p.n), block(kBlk);
-    if (mode == kColdPass) hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kColdPass>), grid, block, 0, stream, p, w);
-    else if (mode == kWarmPass) hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kWarmPass>), grid, block, 0, stream, p, w);
-    else hipLaunchKernelGGL((split_collect_kernel<VEC, DIFF, kSecondPass>), grid, block, 0, stream, p, w);
+    const dim3 grid((unsigned)g, (unsigned)p.n);
+    // Steps per group.  Two arrays and two workgroups per compute unit: one step (128 KB in flight per unit; C4:
+    // 138 us against 142 with two steps and 147 without the second buffer); otherwise two (one array, one workgroup
+    // per unit, the C1 call: 31.7 us against 36 with one step and 33 with four).
+    if constexpr (VEC == 4 && DIFF) {
+        if (g * p.n > 256) {
+            launch_collect_u<VEC, DIFF, 1>(p, w, mode, grid, stream);
+            return;
+        }
+    }
+    launch_collect_u<VEC, DIFF, 2>(p, w, mode, grid, stream);
 }
 
 void launch_collect_any(const TopkArgs &p, const Ws &w, int mode, hipStream_t stream) {
@@ -1137,10 +1199,16 @@ hipError_t launch_topk_split_pair(const TopkArgs &plain, const TopkArgs &markov,
     const bool warm = markov.warm > 0;
     const dim3 grid((unsigned)wm.G, (unsigned)markov.n), block(kBlk);
     double2 *norms = (double2 *)norm_parts;
-    if (vec4 && warm) hipLaunchKernelGGL((split_collect_pair_kernel<4, true>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
-    else if (vec4) hipLaunchKernelGGL((split_collect_pair_kernel<4, false>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
-    else if (warm) hipLaunchKernelGGL((split_collect_pair_kernel<1, true>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
-    else hipLaunchKernelGGL((split_collect_pair_kernel<1, false>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms);
+    const bool two_per_cu = wm.G * markov.n > 256;      // steps per group: see launch_collect
+#define EF21_PAIR(VEC, WARM, U) \
+    hipLaunchKernelGGL((split_collect_pair_kernel<VEC, WARM, U>), grid, block, 0, stream, markov, wm, plain.warm, wp, norms)
+    if (vec4 && warm && two_per_cu) EF21_PAIR(4, true, 1);
+    else if (vec4 && warm) EF21_PAIR(4, true, 2);
+    else if (vec4 && two_per_cu) EF21_PAIR(4, false, 1);
+    else if (vec4) EF21_PAIR(4, false, 2);
+    else if (warm) EF21_PAIR(1, true, 2);
+    else EF21_PAIR(1, false, 2);
+#undef EF21_PAIR
     mk(K_TOPK_COLLECT);
     hipError_t st = hipGetLastError();
     if (st != hipSuccess) return st;
