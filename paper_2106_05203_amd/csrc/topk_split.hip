@@ -789,8 +789,9 @@ struct Emitter {
           agg_start(p_.agg_start ? p_.agg_start + row_ * (p_.agg_nblk + 1) : nullptr),
           last_b((span_lo >> p_.agg_shift) - 1), lane(lane_) {}
 
-    // one step: `in` marks the lanes that hold a candidate (position rec.x, value bits rec.y); all lanes call
-    __device__ __forceinline__ void step(bool in, uint2 rec) {
+    // one step: `in` marks the lanes that hold a candidate (position rec.x, value bits rec.y); all lanes call.
+    // have_b: b_pre is the value of b at the candidate's position, loaded by the caller beforehand.
+    __device__ __forceinline__ void step(bool in, uint2 rec, bool have_b = false, float b_pre = 0.f) {
         const uint32_t key = rec.y & 0x7fffffffu;
         const bool gt = in && key > T, eq = in && key == T;
         const uint64_t m_gt = __ballot(gt), m_eq = __ballot(eq);
@@ -804,7 +805,7 @@ struct Emitter {
             out_val[pos] = v;
             if constexpr (UPDATE) {                      // Algorithm 2, line 6
                 const int64_t at = row * p.d + (int64_t)rec.x;
-                p.g_i[at] = (DIFF ? p.b[at] : 0.f) + v;
+                p.g_i[at] = (DIFF ? (have_b ? b_pre : p.b[at]) : 0.f) + v;
             }
         }
         if (agg_start) {
@@ -884,6 +885,19 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
         for (int q = 0; q < kPre; ++q) c[s][q] = slot[s][q * kWave + lane];
         if (!active) cnt[s] = 0u;
     }
+    // Line 6 needs g_i at the kept positions, scattered over the row: the loads for all of the wavefront's first
+    // candidates (kept or not: that is not known yet) are issued here, with everything else, instead of one step
+    // at a time between the stores of the emission.
+    float bpre[kSPW][kPre];
+    if constexpr (DIFF && UPDATE) {
+#pragma unroll
+        for (int s = 0; s < kSPW; ++s)
+#pragma unroll
+            for (int q = 0; q < kPre; ++q) {
+                const bool have = (uint32_t)(q * kWave + lane) < cnt[s];
+                bpre[s][q] = p.b[row * p.d + (have ? (int64_t)c[s][q].x : 0)];
+            }
+    }
 
     if (blockIdx.x == 0) {                       // the histograms are consumed: zero for the next call
         zero_global_hist(w.hist_a + row * kHistBins, kHistBins);
@@ -957,7 +971,10 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kPre; ++u) em.step(j0 + u * kWave + lane < cnt[s], c[s][u]);
+            for (int u = 0; u < kPre; ++u) {
+                if constexpr (DIFF && UPDATE) em.step(j0 + u * kWave + lane < cnt[s], c[s][u], j0 == 0, bpre[s][u]);
+                else em.step(j0 + u * kWave + lane < cnt[s], c[s][u]);
+            }
         }
     }
     const int64_t span_end = (sl_first + kSPW) * w.L;
