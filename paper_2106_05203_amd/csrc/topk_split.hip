@@ -885,16 +885,19 @@ __global__ __launch_bounds__(kCandThreads) void cand_emit_kernel(TopkArgs p, Ws 
         for (int q = 0; q < kPre; ++q) c[s][q] = slot[s][q * kWave + lane];
         if (!active) cnt[s] = 0u;
     }
-    // Line 6 needs g_i at the kept positions, scattered over the row: the loads for all of the wavefront's first
-    // candidates (kept or not: that is not known yet) are issued here, with everything else, instead of one step
-    // at a time between the stores of the emission.
+    // Line 6 needs g_i at the kept positions, scattered over the row: the loads for the wavefront's first
+    // candidates that can be kept (those in T's bin or above: T itself is not known yet) are issued here, with
+    // everything else, instead of one step at a time between the stores of the emission.
     float bpre[kSPW][kPre];
     if constexpr (DIFF && UPDATE) {
+        const uint32_t key_lo = ri.use2 != 0u ? ri.key_lo2 : ri.key_lo, shift = ri.use2 != 0u ? ri.shift2 : ri.shift;
 #pragma unroll
         for (int s = 0; s < kSPW; ++s)
 #pragma unroll
             for (int q = 0; q < kPre; ++q) {
-                const bool have = (uint32_t)(q * kWave + lane) < cnt[s];
+                const uint32_t key = c[s][q].y & 0x7fffffffu;
+                const bool have = (uint32_t)(q * kWave + lane) < cnt[s] &&
+                                  bin_of(key < key_lo ? key_lo : key, key_lo, shift) >= ri.bin_a;
                 bpre[s][q] = p.b[row * p.d + (have ? (int64_t)c[s][q].x : 0)];
             }
     }
