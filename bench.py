@@ -344,6 +344,16 @@ def bench_grads(torch, binding, workloads, steps: int, warmup: int):
                         **tp.fields(),
                         "kernel_ms_per_step": {k_: round(v * pl[k_], 5) for k_, v in pk.items()},
                         "plain_compressor_chosen_last_step": int(h.get_choices()[0].sum().item())}
+    # Fresh draws every step are EF21+'s worst case: g_i says nothing about the next gradient, every worker takes the
+    # plain compressor and its whole row of g_i is rewritten.  Gradients that change slowly (one set plus 5 % of
+    # another), as along a training run, let the Markov compressor win: the state then changes in k places per row.
+    slow = [pool[0] + 0.05 * pool[j] for j in range(1, 5)]
+    h.set_state(torch.zeros(d, device="cuda"), torch.zeros((n, d), device="cuda"), None)
+    ts = Timed(torch, lambda i: h.step(slow[i % 4], binding.PLUS), max(10, steps // 2), max(5, warmup // 2), repeats=3)
+    out["ef21_plus"]["slowly_varying_gradients"] = {
+        "value": round(1e3 / ts.wall, 2), "unit": "EF21+ iterations/s (gradients supplied)", **ts.fields(),
+        "plain_compressor_chosen_last_step": int(h.get_choices()[0].sum().item())}
+    del slow
     dom = "topk_collect" if "topk_collect" in per_kernel else "topk_row"
     out["roofline"] = roofline(8.0 * n * d, per_kernel[dom], f"{dom} (reads grad and g_i once)",
                                measured_traffic(f"C4/{dom}"))
