@@ -12,6 +12,13 @@ pytestmark = pytest.mark.gpu
 
 
 def test_plain_c_client_runs_and_agrees():
+    # The client is started as a child process, which must happen before this process has touched the GPU (a
+    # process that has initialised the GPU should not start other programs).  pytest collects this file before the
+    # other GPU tests, so in a run of the whole suite it comes first; after another GPU test, run it by itself.
+    import sys
+    torch = sys.modules.get("torch")
+    if torch is not None and torch.cuda.is_initialized():
+        pytest.skip("this process has already initialised the GPU: run tests/test_gpu_c_client.py alone")
     if not os.path.exists(build.C_CLIENT):
         build.build_c_client()
     done = subprocess.run([build.C_CLIENT], capture_output=True, text=True, timeout=120)
